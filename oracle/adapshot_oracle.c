@@ -1,0 +1,308 @@
+/*
+ * adapshot_oracle.c -- plain CPU oracle for the AdapShot KV-reuse hot path.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It exists so that the HIP
+ * library can be checked element by element against a slow, obviously correct
+ * implementation.  Only tests, the smoke check and the benchmark's CPU-baseline
+ * leg may call it.  It shares no code, header, table or constant with the HIP
+ * path and is never a fallback for it.
+ *
+ * Everything is written as the defining formula, in straight loops, with fp64
+ * arithmetic.  Stored tensors are either fp32 or bf16 (bf16 passed as uint16 bit
+ * patterns); both convert exactly to fp64 on load, and a result is rounded once,
+ * to nearest-even, when it is stored back in the storage type.  OpenMP is used
+ * only across independent units (tokens, (row, head) pairs, logit rows).
+ *
+ * What each function follows (AdapShot paper):
+ *   plan      -- Position Decoupling and Re-encoding: the two-shot concatenation
+ *                example (shot_B after shot_A gets positions T_A .. T_A+T_B-1),
+ *                and Eq. (probe_context): instruction prefix, then shots in order.
+ *   rot       -- Eq. (rope_encoding) / Eq. (rope_compensation):
+ *                x * cos(a*theta) + rotate_half(x) * sin(a*theta),
+ *                theta_i = base^(-2i/d), halves paired as (i, i + d/2).
+ *   assemble  -- Semantically-Aware KV Cache (concatenate cached blocks in rank
+ *                order) + Eq. (rope_compensation) applied to every key.
+ *   attention -- softmax(q k^T / sqrt(d)) v as in Eq. (attention_score), for the
+ *                probe/query tokens of Eq. (probe_context) over the assembled
+ *                context plus their own tokens (causal).
+ *   entropy   -- Eq. (entropy), H = -sum p log p, here over the whole vocabulary
+ *                of one output distribution, natural log.
+ *
+ * Parity pins for every function live in tests/test_oracle_*.py; none of the
+ * functions below is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum { ORC_KEYS_UNROTATED = 0, ORC_KEYS_ROTATED_LOCAL = 1 };
+
+int32_t adapshot_oracle_threads(void) {
+#ifdef _OPENMP
+    return (int32_t)omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ---- storage <-> fp64 ------------------------------------------------------ */
+
+static double bf16_bits_to_double(uint16_t b) {
+    uint32_t u = ((uint32_t)b) << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return (double)f; /* exact */
+}
+
+/* Round an fp64 value to bf16 (8 significant bits, fp32 exponent range) with
+ * round-to-nearest-even, in ONE rounding step (not via fp32). */
+uint16_t adapshot_oracle_double_to_bf16(double x) {
+    if (isnan(x)) return 0x7FC0u;
+    uint16_t sign = signbit(x) ? 0x8000u : 0u;
+    double ax = fabs(x);
+    if (isinf(ax)) return (uint16_t)(sign | 0x7F80u);
+    if (ax == 0.0) return sign;
+    int e;
+    (void)frexp(ax, &e);          /* ax = f * 2^e, f in [0.5, 1) */
+    int q = e - 8;                /* spacing of bf16 numbers near ax is 2^(e-8) */
+    if (q < -133) q = -133;       /* bf16 subnormal spacing: 2^-126 * 2^-7 */
+    double r = rint(ldexp(ax, -q)); /* rint: current mode = nearest-even */
+    double y = ldexp(r, q);       /* exactly a bf16 value (or 2^128 on overflow) */
+    float f = (float)y;           /* exact, or +inf */
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    return (uint16_t)(sign | (uint16_t)(u >> 16));
+}
+
+static double load_elem(const void* base, int dtype, int64_t idx) {
+    if (dtype == ORC_BF16) return bf16_bits_to_double(((const uint16_t*)base)[idx]);
+    return (double)((const float*)base)[idx];
+}
+
+static void store_elem(void* base, int dtype, int64_t idx, double v) {
+    if (dtype == ORC_BF16) ((uint16_t*)base)[idx] = adapshot_oracle_double_to_bf16(v);
+    else ((float*)base)[idx] = (float)v; /* C conversion: correctly rounded, nearest-even */
+}
+
+/* ---- plan: slot / position indexing ------------------------------------------ */
+
+/* Slot j of the appended context (j = 0..m-1) holds shot s_j = shot_ids[order[j]]
+ * (order == NULL: identity).  With off_0 = 0 and off_j = sum_{r<j} T_{s_r}, token t
+ * of that shot lands at slot slot0 + off_j + t and gets position pos0 + slot.
+ * Outputs are indexed by the appended token (0 .. n-1):
+ *   slot_shot = pool shot id, slot_tok = t, slot_pos = new position,
+ *   slot_src  = token index inside the pool (shot_offsets[s] + t).
+ * Returns n (the number of appended tokens), or -1 for a shot id or an order
+ * entry out of range.  Output pointers may be NULL (then only n is computed). */
+int64_t adapshot_oracle_plan(const int64_t* shot_offsets, int32_t n_shots,
+                             const int32_t* shot_ids, const int32_t* order, int32_t m,
+                             int64_t slot0, int64_t pos0,
+                             int32_t* slot_shot, int32_t* slot_tok,
+                             int64_t* slot_pos, int64_t* slot_src) {
+    int64_t off = 0;
+    for (int32_t j = 0; j < m; ++j) {
+        int32_t oj = order ? order[j] : j;
+        if (oj < 0 || oj >= m) return -1;
+        int32_t s = shot_ids[oj];
+        if (s < 0 || s >= n_shots) return -1;
+        int64_t len = shot_offsets[s + 1] - shot_offsets[s];
+        for (int64_t t = 0; t < len; ++t) {
+            int64_t i = off + t;
+            if (slot_shot) slot_shot[i] = s;
+            if (slot_tok) slot_tok[i] = (int32_t)t;
+            if (slot_pos) slot_pos[i] = pos0 + slot0 + off + t;
+            if (slot_src) slot_src[i] = shot_offsets[s] + t;
+        }
+        off += len;
+    }
+    return off;
+}
+
+/* ---- rot: RoPE at angle multiplier a ----------------------------------------- */
+
+/* y = x (.) cos(a*theta) + rotate_half(x) (.) sin(a*theta), where theta has d/2
+ * entries theta_i = base^(-2i/d), cos/sin are tiled over both halves, and
+ * rotate_half(x) = [-x_{d/2..d-1}, x_{0..d/2-1}].  Written per pair (i, i+d/2). */
+void adapshot_oracle_rot(const double* x, int32_t d, double base, double a, double* y) {
+    int32_t h = d / 2;
+    for (int32_t i = 0; i < h; ++i) {
+        double theta_i = pow(base, -2.0 * (double)i / (double)d);
+        double phi = a * theta_i;
+        double c = cos(phi), s = sin(phi);
+        double x1 = x[i], x2 = x[i + h];
+        y[i] = x1 * c + (-x2) * s;
+        y[i + h] = x2 * c + x1 * s;
+    }
+}
+
+/* ---- assemble: gather + re-encode --------------------------------------------- */
+
+/* For every layer l and appended token i (0..n_new-1), with slot = slot0 + i:
+ *   V_out[l, slot, :, :] = V_pool[l, slot_src[i], :, :]           (bit copy)
+ *   K_out[l, slot, h, :] = rot(K_pool[l, slot_src[i], h, :], a_i)
+ * where a_i = slot_pos[i] if the pool keys carry no rotation (UNROTATED), or
+ * a_i = slot_pos[i] - slot_tok[i] (= Delta, the shot's offset) if they were
+ * prefilled at local positions 0..T-1 (ROTATED_LOCAL), Eq. (rope_compensation).
+ * Pool layout [L][pool_layer_stride_tokens][h_kv][d]; output [L][capacity][h_kv][d].
+ * k_exact (optional, fp64 [L][n_new][h_kv][d]) receives the keys before rounding.
+ * Returns 0, or -1 if slot0 + n_new > capacity. */
+int adapshot_oracle_assemble(const void* k_pool, const void* v_pool, int dtype,
+                             int32_t n_layers, int64_t pool_layer_stride_tokens,
+                             int32_t h_kv, int32_t d, double base, int key_state,
+                             const int64_t* slot_src, const int32_t* slot_tok,
+                             const int64_t* slot_pos, int64_t n_new, int64_t slot0,
+                             void* k_out, void* v_out, int64_t capacity, double* k_exact) {
+    if (slot0 < 0 || slot0 + n_new > capacity) return -1;
+    if (d <= 0 || d % 2 != 0 || d > 1024) return -1;
+    int64_t row = (int64_t)h_kv * d;
+    for (int32_t l = 0; l < n_layers; ++l) {
+#pragma omp parallel for schedule(static)
+        for (int64_t i = 0; i < n_new; ++i) {
+            double x[1024], y[1024];
+            int64_t src = ((int64_t)l * pool_layer_stride_tokens + slot_src[i]) * row;
+            int64_t dst = ((int64_t)l * capacity + slot0 + i) * row;
+            double a = (key_state == ORC_KEYS_ROTATED_LOCAL)
+                           ? (double)(slot_pos[i] - (int64_t)slot_tok[i])
+                           : (double)slot_pos[i];
+            for (int32_t h = 0; h < h_kv; ++h) {
+                for (int32_t e = 0; e < d; ++e) x[e] = load_elem(k_pool, dtype, src + (int64_t)h * d + e);
+                adapshot_oracle_rot(x, d, base, a, y);
+                for (int32_t e = 0; e < d; ++e) {
+                    store_elem(k_out, dtype, dst + (int64_t)h * d + e, y[e]);
+                    if (k_exact) k_exact[((int64_t)l * n_new + i) * row + (int64_t)h * d + e] = y[e];
+                }
+                for (int32_t e = 0; e < d; ++e)
+                    store_elem(v_out, dtype, dst + (int64_t)h * d + e,
+                               load_elem(v_pool, dtype, src + (int64_t)h * d + e));
+            }
+        }
+    }
+    return 0;
+}
+
+/* ---- attention: query rows over the assembled context + causal self ------------- */
+
+/* One layer.  k_cache / v_cache: [>= n_ctx][h_kv][d] (keys already at their
+ * positions).  q: [t_q][h_q][d], k_self / v_self: [t_q][h_kv][d], all given
+ * WITHOUT rotation; row j is rotated to position q_pos0 + j here.  Query head h
+ * uses kv head h / (h_q / h_kv).  Row j sees context slots 0..n_ctx-1 and self
+ * tokens 0..j.  Score = q~ . k / sqrt(d); softmax over all visible keys; output
+ * = sum p * v.  If `pairs` is NULL all (j, h) are computed into out[t_q][h_q][d];
+ * otherwise pairs holds n_pairs (j, h) couples and out is [n_pairs][d].
+ * Returns 0, -1 on bad arguments. */
+int adapshot_oracle_query_attn(const void* k_cache, const void* v_cache, int dtype, int64_t n_ctx,
+                               const void* q, const void* k_self, const void* v_self,
+                               int32_t t_q, int32_t h_q, int32_t h_kv, int32_t d, double base,
+                               int64_t q_pos0, const int32_t* pairs, int64_t n_pairs, double* out) {
+    if (h_kv <= 0 || h_q % h_kv != 0 || d <= 0 || d % 2 != 0 || d > 1024 || t_q < 0 || n_ctx < 0) return -1;
+    int32_t g = h_q / h_kv;
+    int64_t n_units = pairs ? n_pairs : (int64_t)t_q * h_q;
+    double inv_sqrt_d = 1.0 / sqrt((double)d);
+
+    /* rotate the self keys once: ks_rot[j][hk][:] = rot(k_self[j][hk][:], q_pos0 + j) */
+    double* ks_rot = (double*)malloc(sizeof(double) * (size_t)(t_q > 0 ? t_q : 1) * h_kv * d);
+    if (!ks_rot) return -1;
+    for (int32_t j = 0; j < t_q; ++j)
+        for (int32_t hk = 0; hk < h_kv; ++hk) {
+            double x[1024];
+            int64_t o = ((int64_t)j * h_kv + hk) * d;
+            for (int32_t e = 0; e < d; ++e) x[e] = load_elem(k_self, dtype, o + e);
+            adapshot_oracle_rot(x, d, base, (double)(q_pos0 + j), ks_rot + o);
+        }
+
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t u = 0; u < n_units; ++u) {
+        int32_t j = pairs ? pairs[2 * u] : (int32_t)(u / h_q);
+        int32_t h = pairs ? pairs[2 * u + 1] : (int32_t)(u % h_q);
+        double* o = out + u * d;
+        if (j < 0 || j >= t_q || h < 0 || h >= h_q) {
+#pragma omp atomic write
+            failed = 1;
+            continue;
+        }
+        int32_t hk = h / g;
+        int64_t n_keys = n_ctx + j + 1;
+        double* sc = (double*)malloc(sizeof(double) * (size_t)n_keys);
+        if (!sc) {
+#pragma omp atomic write
+            failed = 1;
+            continue;
+        }
+        double x[1024], qr[1024];
+        for (int32_t e = 0; e < d; ++e) x[e] = load_elem(q, dtype, ((int64_t)j * h_q + h) * d + e);
+        adapshot_oracle_rot(x, d, base, (double)(q_pos0 + j), qr);
+
+        double mx = -INFINITY;
+        for (int64_t c = 0; c < n_keys; ++c) {
+            double dot = 0.0;
+            if (c < n_ctx) {
+                int64_t ko = (c * h_kv + hk) * d;
+                for (int32_t e = 0; e < d; ++e) dot += qr[e] * load_elem(k_cache, dtype, ko + e);
+            } else {
+                const double* kr = ks_rot + ((c - n_ctx) * h_kv + hk) * d;
+                for (int32_t e = 0; e < d; ++e) dot += qr[e] * kr[e];
+            }
+            sc[c] = dot * inv_sqrt_d;
+            if (sc[c] > mx) mx = sc[c];
+        }
+        double denom = 0.0;
+        for (int64_t c = 0; c < n_keys; ++c) {
+            sc[c] = exp(sc[c] - mx);
+            denom += sc[c];
+        }
+        for (int32_t e = 0; e < d; ++e) o[e] = 0.0;
+        for (int64_t c = 0; c < n_keys; ++c) {
+            double p = sc[c] / denom;
+            if (c < n_ctx) {
+                int64_t vo = (c * h_kv + hk) * d;
+                for (int32_t e = 0; e < d; ++e) o[e] += p * load_elem(v_cache, dtype, vo + e);
+            } else {
+                int64_t vo = ((c - n_ctx) * h_kv + hk) * d;
+                for (int32_t e = 0; e < d; ++e) o[e] += p * load_elem(v_self, dtype, vo + e);
+            }
+        }
+        free(sc);
+    }
+    free(ks_rot);
+    return failed ? -1 : 0;
+}
+
+/* ---- entropy of softmax(logits) ------------------------------------------------- */
+
+/* H = -sum_v p_v ln p_v with p = softmax(z).  With m = max z, e_v = exp(z_v - m),
+ * s = sum e_v:  ln p_v = (z_v - m) - ln s, so H = ln s - (sum (z_v - m) e_v) / s.
+ * A term with e_v == 0 contributes 0 (p ln p -> 0 as p -> 0), which also covers
+ * logits equal to -infinity.  A row holding a NaN, +infinity, or only -infinity
+ * has no defined distribution and yields NaN. */
+void adapshot_oracle_entropy(const float* logits, int64_t row_stride, int32_t n_rows,
+                             int32_t vocab, double* entropy_out) {
+#pragma omp parallel for schedule(static)
+    for (int32_t r = 0; r < n_rows; ++r) {
+        const float* z = logits + (int64_t)r * row_stride;
+        double m = -INFINITY;
+        int bad = (vocab <= 0);
+        for (int32_t v = 0; v < vocab; ++v) {
+            double zv = (double)z[v];
+            if (isnan(zv) || zv == INFINITY) bad = 1;
+            if (zv > m) m = zv;
+        }
+        if (bad || m == -INFINITY) {
+            entropy_out[r] = NAN;
+            continue;
+        }
+        double s = 0.0, t = 0.0;
+        for (int32_t v = 0; v < vocab; ++v) {
+            double dz = (double)z[v] - m;
+            double e = exp(dz);
+            s += e;
+            if (e > 0.0) t += dz * e;
+        }
+        entropy_out[r] = log(s) - t / s;
+    }
+}

@@ -1,0 +1,423 @@
+"""Pins for the CPU oracle: every oracle function is checked against something
+other than itself -- the paper's worked example, closed forms, invariants,
+library routines on the special cases that reduce to them, and brute force on
+tiny inputs.  CPU only."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _constants():
+    out = {}
+    for line in open(os.path.join(GOLD, "constants.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        k, v = line.split()
+        out[k] = float(v)
+    return out
+
+
+# ---------------------------------------------------------------- bf16 rounding
+
+def test_bf16_rounding_matches_library_on_fp32_inputs(oracle_mod):
+    rng = np.random.default_rng(1)
+    x = np.concatenate([rng.standard_normal(4000).astype(np.float32),
+                        (rng.standard_normal(500) * 1e-30).astype(np.float32),
+                        (rng.standard_normal(500) * 1e30).astype(np.float32),
+                        np.array([0.0, -0.0, 1.0, -1.0, 3.3895314e38, 1e-40, -1e-40, 9.2e-41], np.float32)])
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = np.array([oracle_mod.double_to_bf16(float(v)) for v in x], np.uint16)
+    assert np.array_equal(got, want)
+
+
+def test_bf16_rounding_ties_and_single_step(oracle_mod):
+    f = oracle_mod.double_to_bf16
+    assert f(1.0) == 0x3F80
+    assert f(1.0 + 2.0 ** -8) == 0x3F80           # tie -> even mantissa
+    assert f(1.0 + 3 * 2.0 ** -8) == 0x3F82       # tie -> even mantissa
+    assert f(1.0 + 2.0 ** -8 + 2.0 ** -40) == 0x3F81   # just above the tie: one rounding, not two
+    assert f(1.0 + 2.0 ** -8 - 2.0 ** -40) == 0x3F80
+    assert f(float("inf")) == 0x7F80 and f(float("-inf")) == 0xFF80
+    assert f(3.4e38) == 0x7F80                    # above the largest bf16 (3.3895e38) + half spacing
+    assert f(2.0 ** -133) == 0x0001 and f(2.0 ** -135) == 0x0000
+    assert oracle_mod.bf16_bits_to_f64(np.array([0x3F81], np.uint16))[0] == 1.0078125
+
+
+# ---------------------------------------------------------------- plan / indexing
+
+def test_plan_paper_two_shot_example(oracle_mod):
+    rows = [list(map(int, l.split())) for l in open(os.path.join(GOLD, "two_shot_positions.txt"))
+            if l.strip() and not l.startswith("#")]
+    rows = np.array(rows)
+    offsets = np.array([0, 5, 8], np.int64)        # pool: shot A (5 tokens) then shot B (3 tokens)
+    pl = oracle_mod.plan(offsets, [0, 1], None)
+    assert pl["n"] == 8
+    assert np.array_equal(pl["slot_shot"], rows[:, 1])
+    assert np.array_equal(pl["slot_tok"], rows[:, 2])
+    assert np.array_equal(pl["slot_pos"], rows[:, 3])
+    assert np.array_equal(pl["slot_pos"] - pl["slot_tok"], rows[:, 4])
+    # B before A: B now starts at 0 and A is shifted by T_B
+    pl = oracle_mod.plan(offsets, [0, 1], [1, 0])
+    assert list(pl["slot_shot"]) == [1, 1, 1, 0, 0, 0, 0, 0]
+    assert list(pl["slot_pos"] - pl["slot_tok"]) == [0, 0, 0, 3, 3, 3, 3, 3]
+    assert list(pl["slot_src"]) == [5, 6, 7, 0, 1, 2, 3, 4]
+
+
+def test_plan_bruteforce_concatenation(oracle_mod):
+    rng = np.random.default_rng(7)
+    for trial in range(20):
+        n = int(rng.integers(1, 12))
+        lens = rng.integers(1, 9, size=n)
+        offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        m = int(rng.integers(0, 10))
+        ids = rng.integers(0, n, size=m).astype(np.int32)          # duplicates allowed
+        order = rng.permutation(m).astype(np.int32)
+        slot0, pos0 = int(rng.integers(0, 5)), int(rng.integers(0, 100))
+        pl = oracle_mod.plan(offsets, ids, order, slot0=slot0, pos0=pos0)
+        shot, tok, src = [], [], []
+        for j in range(m):
+            s = int(ids[order[j]])
+            for t in range(int(lens[s])):
+                shot.append(s); tok.append(t); src.append(int(offsets[s]) + t)
+        assert pl["n"] == len(shot)
+        assert list(pl["slot_shot"]) == shot and list(pl["slot_tok"]) == tok and list(pl["slot_src"]) == src
+        assert list(pl["slot_pos"]) == [pos0 + slot0 + i for i in range(len(shot))]
+
+
+def test_plan_rejects_bad_ids(oracle_mod):
+    offsets = np.array([0, 2, 5], np.int64)
+    with pytest.raises(ValueError):
+        oracle_mod.plan(offsets, [0, 2], None)
+    with pytest.raises(ValueError):
+        oracle_mod.plan(offsets, [-1], None)
+    with pytest.raises(ValueError):
+        oracle_mod.plan(offsets, [0, 1], [0, 2])
+    assert oracle_mod.plan(offsets, [], None)["n"] == 0
+
+
+# ---------------------------------------------------------------- rot
+
+def _rot_complex(x, base, a):
+    """Brute force: the pair (x_i, x_{i+d/2}) as a complex number times e^{i a theta_i}."""
+    d = x.shape[-1]
+    h = d // 2
+    z = x[..., :h] + 1j * x[..., h:]
+    theta = np.array([base ** (-2.0 * i / d) for i in range(h)])
+    w = z * np.exp(1j * a * theta)
+    return np.concatenate([w.real, w.imag], axis=-1)
+
+
+@pytest.mark.parametrize("d,base", [(64, 1.0e4), (128, 5.0e5), (128, 1.0e6), (2, 10000.0), (6, 123.0)])
+def test_rot_bruteforce_complex(oracle_mod, d, base):
+    rng = np.random.default_rng(d)
+    for a in [0, 1, 17, 4095, 26000, 131071]:
+        x = rng.standard_normal(d)
+        assert np.allclose(oracle_mod.rot(x, base, a), _rot_complex(x, base, a), rtol=0, atol=1e-11)
+
+
+def test_rot_closed_forms(oracle_mod):
+    c = _constants()
+    e0 = np.zeros(8); e0[0] = 1.0
+    y = oracle_mod.rot(e0, 10000.0, 1.0)             # theta_0 = 1: pair (0, 4) turns by 1 rad
+    want = np.zeros(8); want[0] = c["cos1"]; want[4] = c["sin1"]
+    assert np.allclose(y, want, atol=1e-15)
+    y = oracle_mod.rot(e0, 500000.0, 2.0)
+    want = np.zeros(8); want[0] = c["cos2"]; want[4] = c["sin2"]
+    assert np.allclose(y, want, atol=1e-15)
+    # second half of the pair: (0,1) turns to (-sin, cos)
+    e4 = np.zeros(8); e4[4] = 1.0
+    y = oracle_mod.rot(e4, 10000.0, 1.0)
+    want = np.zeros(8); want[0] = -c["sin1"]; want[4] = c["cos1"]
+    assert np.allclose(y, want, atol=1e-15)
+    # theta_1 = base^(-2/d): d = 4, base = 1e4 -> 0.01, so a = 100 turns pair (1, 3) by 1 rad
+    e1 = np.zeros(4); e1[1] = 1.0
+    y = oracle_mod.rot(e1, 10000.0, 100.0)
+    assert np.allclose(y, [0.0, c["cos1"], 0.0, c["sin1"]], atol=1e-13)
+    # quarter turn maps x_i -> x_{i+d/2}
+    y = oracle_mod.rot(np.array([1.0, 0.0]), 7.0, math.pi / 2)
+    assert np.allclose(y, [0.0, 1.0], atol=1e-15)
+
+
+def test_rot_invariants(oracle_mod):
+    rng = np.random.default_rng(3)
+    d, base = 128, 5.0e5
+    x = rng.standard_normal(d)
+    assert np.array_equal(oracle_mod.rot(x, base, 0.0), x)                     # R(0) = I
+    for a, b in [(3, 5), (100, 26500), (70000, 61071), (12345, -12345)]:
+        ab = oracle_mod.rot(oracle_mod.rot(x, base, a), base, b)
+        assert np.allclose(ab, oracle_mod.rot(x, base, a + b), atol=1e-10)     # R(a)R(b) = R(a+b)
+    y = oracle_mod.rot(x, base, 9999)
+    h = d // 2
+    assert np.allclose(x[:h] ** 2 + x[h:] ** 2, y[:h] ** 2 + y[h:] ** 2, atol=1e-12)  # pair norms kept
+    # q~ . k~ depends on the position difference only
+    q, k = rng.standard_normal(d), rng.standard_normal(d)
+    s0 = oracle_mod.rot(q, base, 500) @ oracle_mod.rot(k, base, 123)
+    s1 = oracle_mod.rot(q, base, 500 + 77777) @ oracle_mod.rot(k, base, 123 + 77777)
+    assert abs(s0 - s1) < 1e-9
+
+
+# ---------------------------------------------------------------- assemble
+
+def _tiny_pool(rng, L, n_shots, hkv, d, lo=2, hi=7):
+    lens = rng.integers(lo, hi, size=n_shots, endpoint=True)
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    k = rng.standard_normal((L, int(offsets[-1]), hkv, d)).astype(np.float32)
+    v = rng.standard_normal((L, int(offsets[-1]), hkv, d)).astype(np.float32)
+    return offsets, k, v
+
+
+def test_assemble_bruteforce_f32(oracle_mod):
+    rng = np.random.default_rng(11)
+    L, hkv, d, base = 2, 2, 8, 100.0
+    offsets, k, v = _tiny_pool(rng, L, 6, hkv, d)
+    ids, order = [4, 1, 1, 5], [2, 0, 3, 1]
+    pos0 = 9
+    pl = oracle_mod.plan(offsets, ids, order, slot0=0, pos0=pos0)
+    cap = pl["n"] + 3
+    ko, vo, kx = oracle_mod.assemble(k, v, "f32", base, oracle_mod.KEYS_UNROTATED, pl, 0, cap, want_exact=True)
+    slot = 0
+    for j in range(4):
+        s = ids[order[j]]
+        for t in range(int(offsets[s + 1] - offsets[s])):
+            src = int(offsets[s]) + t
+            for l in range(L):
+                assert np.array_equal(vo[l, slot], v[l, src])                   # bit copy
+                want = _rot_complex(k[l, src].astype(np.float64), base, pos0 + slot)
+                assert np.allclose(kx[l, slot], want, atol=1e-12)
+                assert np.array_equal(ko[l, slot], want.astype(np.float32))     # rounded once
+            slot += 1
+    assert slot == pl["n"]
+    assert not ko[:, slot:].any() and not vo[:, slot:].any()                    # nothing written past the end
+
+
+def test_assemble_rotated_local_equals_unrotated(oracle_mod):
+    """Keys cached at local positions 0..T-1 and shifted by Delta = offset give the same
+    result as un-rotated keys rotated to the new position (Eq. rope_compensation)."""
+    rng = np.random.default_rng(12)
+    L, hkv, d, base = 1, 2, 16, 1.0e4
+    offsets, k, v = _tiny_pool(rng, L, 5, hkv, d)
+    k64 = k.astype(np.float64)
+    k_local = np.empty_like(k64)
+    for s in range(5):
+        for t in range(int(offsets[s + 1] - offsets[s])):
+            k_local[0, offsets[s] + t] = _rot_complex(k64[0, offsets[s] + t], base, t)
+    ids, order = [3, 0, 4], [1, 2, 0]
+    pl = oracle_mod.plan(offsets, ids, order, slot0=0, pos0=2)
+    _, _, kx_u = oracle_mod.assemble(k, v, "f32", base, oracle_mod.KEYS_UNROTATED, pl, 0, pl["n"], want_exact=True)
+    _, _, kx_r = oracle_mod.assemble(k_local.astype(np.float32), v, "f32", base, oracle_mod.KEYS_ROTATED_LOCAL,
+                                     pl, 0, pl["n"], want_exact=True)
+    assert np.allclose(kx_u, kx_r, atol=2e-6)       # k_local was rounded to fp32 once
+
+
+def test_assemble_bf16_storage_and_append(oracle_mod):
+    rng = np.random.default_rng(13)
+    L, hkv, d, base = 1, 1, 8, 1.0e4
+    offsets, k, v = _tiny_pool(rng, L, 4, hkv, d)
+    kb = torch.from_numpy(k).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    vb = torch.from_numpy(v).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    pl1 = oracle_mod.plan(offsets, [2, 0], None, slot0=0, pos0=0)
+    pl2 = oracle_mod.plan(offsets, [3], None, slot0=pl1["n"], pos0=0)
+    cap = pl1["n"] + pl2["n"]
+    ko, vo, _ = oracle_mod.assemble(kb, vb, "bf16", base, 0, pl1, 0, cap)
+    ko, vo, _ = oracle_mod.assemble(kb, vb, "bf16", base, 0, pl2, pl1["n"], cap, k_out=ko, v_out=vo)
+    # one-shot assembly of all three gives the same cache (append keeps positions contiguous)
+    pl = oracle_mod.plan(offsets, [2, 0, 3], None)
+    ko2, vo2, kx = oracle_mod.assemble(kb, vb, "bf16", base, 0, pl, 0, cap, want_exact=True)
+    assert np.array_equal(ko, ko2) and np.array_equal(vo, vo2)
+    # stored keys are the exact keys rounded to bf16: within half a spacing (<= 2^-8 relative)
+    got = oracle_mod.bf16_bits_to_f64(ko2)
+    assert np.all(np.abs(got - kx) <= 2.0 ** -8 * np.abs(kx) + 1e-40)
+    with pytest.raises(ValueError):
+        oracle_mod.assemble(kb, vb, "bf16", base, 0, pl, 0, cap - 1)
+
+
+# ---------------------------------------------------------------- attention
+
+def _naive_attention(kc, vc, n_ctx, q, ks, vs, base, q_pos0):
+    """Brute force in numpy matrix form with complex-number RoPE (independent of the C loops)."""
+    t_q, h_q, d = q.shape
+    h_kv = ks.shape[1]
+    g = h_q // h_kv
+    out = np.zeros((t_q, h_q, d))
+    qr = np.stack([_rot_complex(q[j].astype(np.float64), base, q_pos0 + j) for j in range(t_q)])
+    kr = np.stack([_rot_complex(ks[j].astype(np.float64), base, q_pos0 + j) for j in range(t_q)])
+    for h in range(h_q):
+        hk = h // g
+        keys = np.concatenate([kc[:n_ctx, hk].astype(np.float64), kr[:, hk]], axis=0)
+        vals = np.concatenate([vc[:n_ctx, hk].astype(np.float64), vs[:, hk].astype(np.float64)], axis=0)
+        s = qr[:, h] @ keys.T / math.sqrt(d)
+        mask = np.ones_like(s, dtype=bool)
+        for j in range(t_q):
+            mask[j, n_ctx + j + 1:] = False
+        s = np.where(mask, s, -np.inf)
+        p = np.exp(s - s.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        out[:, h] = p @ vals
+    return out
+
+
+def _rand_attn_inputs(rng, n_ctx, t_q, h_q, h_kv, d):
+    f = lambda *s: rng.standard_normal(s).astype(np.float32)
+    return f(n_ctx, h_kv, d), f(n_ctx, h_kv, d), f(t_q, h_q, d), f(t_q, h_kv, d), f(t_q, h_kv, d)
+
+
+@pytest.mark.parametrize("n_ctx,t_q,h_q,h_kv,d", [(13, 5, 4, 2, 8), (0, 4, 2, 2, 4), (40, 1, 7, 1, 16), (9, 6, 6, 3, 64)])
+def test_attention_bruteforce(oracle_mod, n_ctx, t_q, h_q, h_kv, d):
+    rng = np.random.default_rng(n_ctx * 31 + t_q)
+    kc, vc, q, ks, vs = _rand_attn_inputs(rng, n_ctx, t_q, h_q, h_kv, d)
+    got = oracle_mod.query_attn(kc, vc, "f32", n_ctx, q, ks, vs, 1.0e4, q_pos0=n_ctx + 3)
+    want = _naive_attention(kc, vc, n_ctx, q, ks, vs, 1.0e4, n_ctx + 3)
+    assert np.allclose(got, want, atol=1e-12)
+    pairs = np.array([[t_q - 1, h_q - 1], [0, 0], [t_q // 2, 1]], np.int32)
+    sub = oracle_mod.query_attn(kc, vc, "f32", n_ctx, q, ks, vs, 1.0e4, n_ctx + 3, pairs=pairs)
+    for i, (j, h) in enumerate(pairs):
+        assert np.array_equal(sub[i], got[j, h])
+
+
+def test_attention_reduces_to_library_sdpa(oracle_mod):
+    """One query token at position 0 (rotation angle 0), one head: textbook softmax(q K^T / sqrt d) V."""
+    rng = np.random.default_rng(21)
+    n_ctx, d = 50, 32
+    kc, vc, q, ks, vs = _rand_attn_inputs(rng, n_ctx, 1, 1, 1, d)
+    got = oracle_mod.query_attn(kc, vc, "f32", n_ctx, q, ks, vs, 5.0e5, q_pos0=0)
+    K = torch.from_numpy(np.concatenate([kc[:, 0], ks[:, 0]])).double()[None, None]
+    V = torch.from_numpy(np.concatenate([vc[:, 0], vs[:, 0]])).double()[None, None]
+    Q = torch.from_numpy(q[:, 0]).double()[None, None]
+    want = torch.nn.functional.scaled_dot_product_attention(Q, K, V)[0, 0].numpy()
+    assert np.allclose(got[:, 0], want, atol=1e-12)
+
+
+def test_attention_library_sdpa_causal_block(oracle_mod):
+    """No context, several tokens from position 0: plain causal self-attention of a rotated sequence.
+    The library routine gets keys/queries rotated by the complex-number brute force."""
+    rng = np.random.default_rng(22)
+    t_q, h, d, base = 7, 2, 16, 1.0e4
+    kc, vc, q, ks, vs = _rand_attn_inputs(rng, 0, t_q, h, h, d)
+    got = oracle_mod.query_attn(kc, vc, "f32", 0, q, ks, vs, base, q_pos0=0)
+    qr = np.stack([_rot_complex(q[j].astype(np.float64), base, j) for j in range(t_q)])
+    kr = np.stack([_rot_complex(ks[j].astype(np.float64), base, j) for j in range(t_q)])
+    Q = torch.from_numpy(qr).permute(1, 0, 2)[None]
+    K = torch.from_numpy(kr).permute(1, 0, 2)[None]
+    V = torch.from_numpy(vs.astype(np.float64)).permute(1, 0, 2)[None]
+    want = torch.nn.functional.scaled_dot_product_attention(Q, K, V, is_causal=True)[0].permute(1, 0, 2).numpy()
+    assert np.allclose(got, want, atol=1e-12)
+
+
+def test_attention_zero_keys_gives_mean_of_visible_values(oracle_mod):
+    rng = np.random.default_rng(23)
+    n_ctx, t_q, h_q, h_kv, d = 11, 4, 4, 2, 8
+    kc, vc, q, ks, vs = _rand_attn_inputs(rng, n_ctx, t_q, h_q, h_kv, d)
+    kc[:] = 0; ks[:] = 0
+    got = oracle_mod.query_attn(kc, vc, "f32", n_ctx, q, ks, vs, 1.0e4, q_pos0=n_ctx)
+    for j in range(t_q):
+        for h in range(h_q):
+            hk = h // 2
+            want = (vc[:, hk].astype(np.float64).sum(0) + vs[: j + 1, hk].astype(np.float64).sum(0)) / (n_ctx + j + 1)
+            assert np.allclose(got[j, h], want, atol=1e-13)
+
+
+def test_attention_needle_and_group_symmetry(oracle_mod):
+    rng = np.random.default_rng(24)
+    n_ctx, t_q, h_q, h_kv, d = 64, 2, 4, 1, 16
+    kc, vc, q, ks, vs = _rand_attn_inputs(rng, n_ctx, t_q, h_q, h_kv, d)
+    q[:, 1] = q[:, 0]; q[:, 2] = q[:, 0]; q[:, 3] = q[:, 0]
+    # plant a key parallel to the rotated query of row 0: its score dwarfs the rest
+    qr0 = _rot_complex(q[0, 0].astype(np.float64), 1.0e4, 100)
+    kc[17, 0] = (50.0 * qr0 / np.linalg.norm(qr0)).astype(np.float32)
+    got = oracle_mod.query_attn(kc, vc, "f32", n_ctx, q, ks, vs, 1.0e4, q_pos0=100)
+    assert np.allclose(got[0, 0], vc[17, 0], atol=1e-6)
+    for h in range(1, 4):
+        assert np.array_equal(got[:, h], got[:, 0])     # same q in a group -> same output
+
+
+def test_chain_relative_position_invariance(oracle_mod):
+    """Shifting pos0 and q_pos0 by the same constant leaves the attention output unchanged."""
+    rng = np.random.default_rng(25)
+    L, hkv, d, base = 1, 2, 16, 1.0e4
+    offsets, k, v = _tiny_pool(rng, L, 6, hkv, d)
+    ids, order = [5, 2, 0], [2, 0, 1]
+    q = rng.standard_normal((3, 4, d)).astype(np.float32)
+    ks = rng.standard_normal((3, hkv, d)).astype(np.float32)
+    vs = rng.standard_normal((3, hkv, d)).astype(np.float32)
+    outs = []
+    for shift in (0, 4321):
+        pl = oracle_mod.plan(offsets, ids, order, slot0=0, pos0=shift)
+        _, vo, kx = oracle_mod.assemble(k, v, "f32", base, 0, pl, 0, pl["n"], want_exact=True)
+        # feed the un-rounded keys so that only the rotation is tested
+        outs.append(_naive_attention(kx[0], vo[0], pl["n"], q, ks, vs, base, shift + pl["n"]))
+        o = oracle_mod.query_attn(kx[0].astype(np.float32), vo[0], "f32", pl["n"], q, ks, vs, base, shift + pl["n"])
+        assert np.allclose(o, outs[-1], atol=1e-5)
+    assert np.allclose(outs[0], outs[1], atol=1e-9)
+
+
+def test_attention_bf16_inputs_widen_exactly(oracle_mod):
+    rng = np.random.default_rng(26)
+    n_ctx, t_q, h_q, h_kv, d = 10, 3, 2, 1, 8
+    arrs = _rand_attn_inputs(rng, n_ctx, t_q, h_q, h_kv, d)
+    bf = [torch.from_numpy(a).to(torch.bfloat16) for a in arrs]
+    bits = [b.view(torch.int16).numpy().view(np.uint16) for b in bf]
+    back = [b.float().numpy() for b in bf]
+    a = oracle_mod.query_attn(bits[0], bits[1], "bf16", n_ctx, bits[2], bits[3], bits[4], 5.0e5, 10)
+    b = oracle_mod.query_attn(back[0], back[1], "f32", n_ctx, back[2], back[3], back[4], 5.0e5, 10)
+    assert np.array_equal(a, b)
+
+
+# ---------------------------------------------------------------- entropy
+
+def test_entropy_closed_forms(oracle_mod):
+    c = _constants()
+    assert abs(oracle_mod.entropy(np.zeros((1, 1000), np.float32))[0] - c["ln1000"]) < 1e-12
+    assert abs(oracle_mod.entropy(np.full((1, 128256), 3.25, np.float32))[0] - c["ln128256"]) < 1e-11
+    z = np.zeros((2, 128256), np.float32)
+    z[0, 77] = 1.0e4
+    z[1, :] = -np.inf; z[1, 5] = 0.0
+    h = oracle_mod.entropy(z)
+    assert h[0] == 0.0 and h[1] == 0.0
+    # n entries at level a, the rest at 0
+    V, n, a = 5000, 37, 4.5
+    z = np.zeros((1, V), np.float32); z[0, 100:100 + n] = a
+    Z = n * math.exp(a) + (V - n)
+    want = math.log(Z) - n * a * math.exp(a) / Z
+    assert abs(oracle_mod.entropy(z)[0] - want) < 1e-12
+    # two classes: binary entropy of sigmoid(z1 - z0)
+    z = np.array([[0.3, -1.1]], np.float32)
+    p = 1.0 / (1.0 + math.exp(float(z[0, 1]) - float(z[0, 0])))
+    assert abs(oracle_mod.entropy(z)[0] - (-(p * math.log(p) + (1 - p) * math.log(1 - p)))) < 1e-14
+
+
+def test_entropy_library_and_shift(oracle_mod):
+    import scipy.special
+    import scipy.stats
+    rng = np.random.default_rng(31)
+    z = (rng.standard_normal((6, 3001)) * 3).astype(np.float32)
+    want = scipy.stats.entropy(scipy.special.softmax(z.astype(np.float64), axis=1), axis=1)
+    got = oracle_mod.entropy(z)
+    assert np.allclose(got, want, atol=1e-12)
+    # logits that are exact in fp32 after the shift: invariance is exact up to fp64 rounding
+    zi = rng.integers(-8, 8, size=(3, 500)).astype(np.float32)
+    assert np.allclose(oracle_mod.entropy(zi), oracle_mod.entropy(zi + 64.0), atol=1e-12)
+    # strided rows
+    big = np.zeros((4, 4000), np.float32); big[:, :3001] = z[:4]
+    assert np.allclose(oracle_mod.entropy(big[:, :3001]), got[:4], atol=0)
+
+
+def test_entropy_invalid_rows_are_nan(oracle_mod):
+    z = np.zeros((3, 16), np.float32)
+    z[0, 3] = np.nan
+    z[1, 3] = np.inf
+    z[2, :] = -np.inf
+    assert np.all(np.isnan(oracle_mod.entropy(z)))
+
+
+def test_entropy_gaussian_logits_statistic(oracle_mod):
+    """iid N(0, s2) logits: E[H] ~ ln V - s2/2 (variance 2 -> ln V - 1), far from the std-2 reading."""
+    from paper_2605_03644_amd import workloads as wl
+    w = wl.WORKLOADS["llama8b_1layer"]
+    z = wl.make_logits(w, "cpu", n_rows=8).numpy()
+    h = oracle_mod.entropy(z)
+    assert abs(h.mean() - (math.log(w.vocab) - 1.0)) < 0.05
