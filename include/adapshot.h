@@ -1,0 +1,146 @@
+/*
+ * libadapshot -- MI355X (gfx950) hot path of AdapShot's semantics-aware KV-cache reuse.
+ *
+ * The path, per query (AdapShot paper, Method section):
+ *   1. gather the cached K/V blocks of the selected shots from the global pool
+ *      into one contiguous many-shot cache, in relevance order
+ *      (Semantically-Aware KV Cache; Eq. prefill defines what the pool holds);
+ *   2. re-encode every gathered key to its new position with the RoPE
+ *      compensation rotation (Position Decoupling and Re-encoding,
+ *      Eq. rope_encoding / Eq. rope_compensation), fused into the gather;
+ *   3. let the probe/query tokens attend over the assembled cache plus their own
+ *      tokens (softmax(q k^T / sqrt(d)) v, the scaling of Eq. attention_score;
+ *      context layout of Eq. probe_context);
+ *   4. reduce each probe's output logits to the entropy of its distribution
+ *      (Eq. entropy), the quantity compared with the threshold tau.
+ *
+ * General conventions
+ *   - Plain C ABI.  Pointers marked DEVICE are HIP device pointers owned by the
+ *     caller (the library never frees or reallocates them); pointers marked HOST
+ *     are ordinary host memory read before the call returns.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All kernels of a call are enqueued on it; calls return without waiting for
+ *     the GPU.  A context owns device scratch (RoPE tables, tile descriptors,
+ *     split partials), so calls on ONE context must be issued in stream order on
+ *     one stream at a time; use one context per concurrent stream.
+ *   - Every function validates its arguments on the host BEFORE launching
+ *     anything: a call that returns an error has written nothing to device
+ *     memory.  The reason is kept per context (adapshot_last_error).
+ *   - Tensor layouts are row-major with the last index contiguous:
+ *       pool     K, V : [n_layers][layer_stride_tokens][n_kv_heads][head_dim]
+ *       cache    K, V : [n_layers][capacity]           [n_kv_heads][head_dim]
+ *       queries  Q    : [t_q][n_q_heads][head_dim]
+ *       self     K, V : [t_q][n_kv_heads][head_dim]
+ *     element type = desc.dtype (fp32, or bf16 as 16-bit patterns).  Base
+ *     pointers must be 16-byte aligned and head_dim * sizeof(element) a multiple
+ *     of 32 bytes.
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - RoPE uses the half-split pairing (i, i + head_dim/2) with
+ *     theta_i = rope_theta^(-2i/head_dim); angles come from tables built in fp64.
+ */
+#ifndef ADAPSHOT_H_
+#define ADAPSHOT_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct adapshot_ctx adapshot_ctx; /* opaque, host side */
+
+typedef enum {
+    ADAPSHOT_OK = 0,
+    ADAPSHOT_EINVAL = 1,    /* null pointer, bad size, unsupported shape, misaligned pointer */
+    ADAPSHOT_ESHOT = 2,     /* shot id or order entry out of range */
+    ADAPSHOT_ECAPACITY = 3, /* cache capacity or max_position exceeded */
+    ADAPSHOT_ESTATE = 4,    /* no pool registered, or n_ctx beyond the assembled length */
+    ADAPSHOT_EDEVICE = 5    /* a HIP runtime call failed (no GPU, out of memory, ...) */
+} adapshot_status;
+
+typedef enum { ADAPSHOT_F32 = 0, ADAPSHOT_BF16 = 1 } adapshot_dtype;
+
+/* How the pool's keys were stored.
+ *   UNROTATED     : keys carry no position; the re-encode angle is p_new * theta.
+ *   ROTATED_LOCAL : each shot was prefilled on its own at positions 0..T-1 (the
+ *                   paper's offline phase); the re-encode angle is
+ *                   Delta * theta with Delta = p_new - t (Eq. rope_compensation). */
+typedef enum { ADAPSHOT_KEYS_UNROTATED = 0, ADAPSHOT_KEYS_ROTATED_LOCAL = 1 } adapshot_key_state;
+
+typedef struct {
+    int32_t n_layers, n_q_heads, n_kv_heads, head_dim;
+    double rope_theta;            /* RoPE base (1e4 in Eq. rope_encoding; model dependent) */
+    int32_t dtype;                /* adapshot_dtype */
+    int32_t key_state;            /* adapshot_key_state */
+    int64_t max_position;         /* largest position + 1 any token may take; 0 = 1048576 */
+} adapshot_model_desc;
+
+/* Create a context for one model shape on the current HIP device: validates the
+ * shape (n_q_heads % n_kv_heads == 0, head_dim even, 16-byte row chunks), builds the
+ * RoPE tables in fp64 and uploads them.  *out is NULL on failure. */
+adapshot_status adapshot_create(const adapshot_model_desc* desc, adapshot_ctx** out);
+void adapshot_destroy(adapshot_ctx* ctx);
+/* Text of the last error on this context ("" if none).  Valid until the next call. */
+const char* adapshot_last_error(const adapshot_ctx* ctx);
+/* Library version / build string. */
+const char* adapshot_version(void);
+
+/* Register the global shot pool (offline phase, Eq. prefill): k_pool / v_pool are
+ * DEVICE pointers BORROWED for the life of the context; shot_offsets is HOST
+ * int64[n_shots + 1], non-decreasing, shot i owning pool tokens
+ * [shot_offsets[i], shot_offsets[i+1]); it is copied.  layer_stride_tokens is the
+ * token count between consecutive layers (>= shot_offsets[n_shots]). */
+adapshot_status adapshot_pool_register(adapshot_ctx* ctx, const void* k_pool, const void* v_pool,
+                                       const int64_t* shot_offsets, int32_t n_shots,
+                                       int64_t layer_stride_tokens);
+
+/* The assembled many-shot cache of one query.  k, v: DEVICE, caller-owned,
+ * [n_layers][capacity][n_kv_heads][head_dim].  len (HOST, in/out) is the number of
+ * slots already filled; assemble appends at slot len.  slot_shot / slot_tok /
+ * slot_pos are optional DEVICE arrays of `capacity` entries (NULL to skip) that
+ * receive, per slot, the pool shot id, the token index inside that shot and the
+ * position the key was re-encoded to. */
+typedef struct {
+    void* k;
+    void* v;
+    int64_t capacity;
+    int64_t len;
+    int32_t* slot_shot;
+    int32_t* slot_tok;
+    int64_t* slot_pos;
+} adapshot_cache;
+
+/* Gather + re-encode (steps 1 and 2).  shot_ids, order: HOST int32[m].  Slot
+ * group j (j = 0..m-1) receives shot shot_ids[order[j]] (order == NULL: identity);
+ * duplicates are allowed and m == 0 is a no-op.  The first appended token lands in
+ * slot cache->len and takes position pos0 + cache->len, later tokens follow
+ * contiguously (pos0 = length of the instruction prefix I of Eq. probe_context).
+ * V rows are bit copies; K rows are rotated in fp32 and rounded to nearest-even.
+ * On success cache->len is advanced.  Errors: ESTATE (no pool), ESHOT,
+ * ECAPACITY (capacity or max_position), EINVAL. */
+adapshot_status adapshot_assemble(adapshot_ctx* ctx, adapshot_cache* cache, const int32_t* shot_ids,
+                                  const int32_t* order, int32_t m, int64_t pos0, void* hip_stream);
+
+/* Query-over-cache attention for one layer (step 3).  Row j (0..t_q-1) attends to
+ * cache slots [0, n_ctx) in full and to self tokens 0..j causally.  q, k_self,
+ * v_self (DEVICE) are given WITHOUT rotation: the library rotates row j of q and
+ * k_self to position q_pos0 + j.  n_ctx <= cache->len.  out: DEVICE
+ * [t_q][n_q_heads][head_dim] in desc.dtype.  Scores and the online softmax are kept
+ * in fp32; bf16 models use bf16 MFMA for q k^T and p v with fp32 accumulation. */
+adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot_cache* cache, int32_t layer,
+                                    int64_t n_ctx, const void* q, const void* k_self,
+                                    const void* v_self, int32_t t_q, int64_t q_pos0, void* out,
+                                    void* hip_stream);
+
+/* Entropy of softmax(logits) per row, natural log (step 4; Eq. entropy taken over
+ * the whole output vocabulary).  logits: DEVICE fp32, row r at logits + r*row_stride
+ * (row_stride >= vocab, in elements); entropy_out: DEVICE fp32[n_rows].  A logit of
+ * -inf contributes 0; a row with a NaN, a +inf or no finite logit gives NaN. */
+adapshot_status adapshot_probe_entropy(adapshot_ctx* ctx, const float* logits, int64_t row_stride,
+                                       int32_t n_rows, int32_t vocab, float* entropy_out,
+                                       void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADAPSHOT_H_ */

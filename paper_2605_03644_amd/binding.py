@@ -1,0 +1,197 @@
+"""Thin ctypes binding of libadapshot (include/adapshot.h).
+
+Argument marshalling only: every step of the hot path runs in the library's HIP
+kernels.  torch is used for device memory (`tensor.data_ptr()`) and for the
+current stream.  There is no fallback: if the shared library is missing or a call
+fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libadapshot.so")
+
+OK, EINVAL, ESHOT, ECAPACITY, ESTATE, EDEVICE = range(6)
+STATUS_NAMES = {OK: "OK", EINVAL: "EINVAL", ESHOT: "ESHOT", ECAPACITY: "ECAPACITY", ESTATE: "ESTATE",
+                EDEVICE: "EDEVICE"}
+F32, BF16 = 0, 1
+KEYS_UNROTATED, KEYS_ROTATED_LOCAL = 0, 1
+
+# every symbol declared in include/adapshot.h
+EXPORTS = ["adapshot_create", "adapshot_destroy", "adapshot_last_error", "adapshot_version",
+           "adapshot_pool_register", "adapshot_assemble", "adapshot_query_attn", "adapshot_probe_entropy"]
+
+
+class ModelDesc(ctypes.Structure):
+    _fields_ = [("n_layers", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("rope_theta", ctypes.c_double), ("dtype", ctypes.c_int32),
+                ("key_state", ctypes.c_int32), ("max_position", ctypes.c_int64)]
+
+
+class CacheStruct(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p), ("capacity", ctypes.c_int64),
+                ("len", ctypes.c_int64), ("slot_shot", ctypes.c_void_p), ("slot_tok", ctypes.c_void_p),
+                ("slot_pos", ctypes.c_void_p)]
+
+
+class AdapshotError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"adapshot {STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+        self.message = message
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libadapshot.so (built in-tree by paper_2605_03644_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} not built: run `python -m paper_2605_03644_amd.build`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.adapshot_create.restype = ctypes.c_int
+    L.adapshot_create.argtypes = [ctypes.POINTER(ModelDesc), ctypes.POINTER(vp)]
+    L.adapshot_destroy.restype = None
+    L.adapshot_destroy.argtypes = [vp]
+    L.adapshot_last_error.restype = ctypes.c_char_p
+    L.adapshot_last_error.argtypes = [vp]
+    L.adapshot_version.restype = ctypes.c_char_p
+    L.adapshot_version.argtypes = []
+    L.adapshot_pool_register.restype = ctypes.c_int
+    L.adapshot_pool_register.argtypes = [vp, vp, vp, vp, i32, i64]
+    L.adapshot_assemble.restype = ctypes.c_int
+    L.adapshot_assemble.argtypes = [vp, ctypes.POINTER(CacheStruct), vp, vp, i32, i64, vp]
+    L.adapshot_query_attn.restype = ctypes.c_int
+    L.adapshot_query_attn.argtypes = [vp, ctypes.POINTER(CacheStruct), i32, i64, vp, vp, vp, i32, i64, vp, vp]
+    L.adapshot_probe_entropy.restype = ctypes.c_int
+    L.adapshot_probe_entropy.argtypes = [vp, vp, i64, i32, i32, vp, vp]
+    _lib = L
+    return L
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream] = None) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _torch_dtype(dtype: int) -> torch.dtype:
+    return torch.float32 if dtype == F32 else torch.bfloat16
+
+
+class Cache:
+    """Caller-owned assembled cache: k, v [L, capacity, H_kv, d] plus optional per-slot index arrays."""
+
+    def __init__(self, ctx: "Context", capacity: int, with_index: bool = True, device=None):
+        d = ctx.desc
+        dev = device if device is not None else ctx.device
+        shape = (d.n_layers, capacity, d.n_kv_heads, d.head_dim)
+        self.k = torch.zeros(shape, dtype=_torch_dtype(d.dtype), device=dev)
+        self.v = torch.zeros(shape, dtype=_torch_dtype(d.dtype), device=dev)
+        self.slot_shot = torch.full((capacity,), -1, dtype=torch.int32, device=dev) if with_index else None
+        self.slot_tok = torch.full((capacity,), -1, dtype=torch.int32, device=dev) if with_index else None
+        self.slot_pos = torch.full((capacity,), -1, dtype=torch.int64, device=dev) if with_index else None
+        self.c = CacheStruct(self.k.data_ptr(), self.v.data_ptr(), capacity, 0,
+                             self.slot_shot.data_ptr() if with_index else None,
+                             self.slot_tok.data_ptr() if with_index else None,
+                             self.slot_pos.data_ptr() if with_index else None)
+
+    @property
+    def len(self) -> int:
+        return int(self.c.len)
+
+    @property
+    def capacity(self) -> int:
+        return int(self.c.capacity)
+
+    def reset(self) -> None:
+        self.c.len = 0
+
+
+class Context:
+    """One model shape on the current device (adapshot_create / adapshot_destroy)."""
+
+    def __init__(self, n_layers: int, n_q_heads: int, n_kv_heads: int, head_dim: int, rope_theta: float,
+                 dtype: int, key_state: int = KEYS_UNROTATED, max_position: int = 0):
+        self.lib = load_library()
+        self.desc = ModelDesc(n_layers, n_q_heads, n_kv_heads, head_dim, float(rope_theta), dtype, key_state,
+                              max_position)
+        self._h = ctypes.c_void_p()
+        st = self.lib.adapshot_create(ctypes.byref(self.desc), ctypes.byref(self._h))
+        if st != OK:
+            raise AdapshotError(st, "adapshot_create failed (bad model description or no usable HIP device)")
+        self.device = torch.device("cuda", torch.cuda.current_device())
+        self._keep = []
+
+    @classmethod
+    def for_workload(cls, w, key_state: int = KEYS_UNROTATED, n_layers: Optional[int] = None,
+                     max_position: int = 0) -> "Context":
+        return cls(w.n_layers if n_layers is None else n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim,
+                   w.rope_theta, F32 if w.dtype == "f32" else BF16, key_state, max_position)
+
+    def close(self) -> None:
+        if self._h:
+            self.lib.adapshot_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def last_error(self) -> str:
+        return self.lib.adapshot_last_error(self._h).decode()
+
+    def _check(self, st: int) -> None:
+        if st != OK:
+            raise AdapshotError(st, self.last_error())
+
+    # -- adapshot_pool_register
+    def pool_register(self, k_pool: torch.Tensor, v_pool: torch.Tensor, shot_offsets: np.ndarray) -> None:
+        off = np.ascontiguousarray(shot_offsets, dtype=np.int64)
+        assert k_pool.is_contiguous() and v_pool.is_contiguous() and k_pool.shape == v_pool.shape
+        self._keep = [k_pool, v_pool]
+        self._check(self.lib.adapshot_pool_register(self._h, k_pool.data_ptr(), v_pool.data_ptr(),
+                                                    off.ctypes.data, off.shape[0] - 1, k_pool.shape[1]))
+
+    # -- adapshot_assemble
+    def assemble(self, cache: Cache, shot_ids: Sequence[int], order: Optional[Sequence[int]] = None,
+                 pos0: int = 0, stream: Optional[torch.cuda.Stream] = None) -> None:
+        ids = np.ascontiguousarray(shot_ids, dtype=np.int32)
+        od = None if order is None else np.ascontiguousarray(order, dtype=np.int32)
+        self._check(self.lib.adapshot_assemble(self._h, ctypes.byref(cache.c), ids.ctypes.data,
+                                               None if od is None else od.ctypes.data, ids.shape[0], pos0,
+                                               _stream_ptr(stream)))
+
+    # -- adapshot_query_attn
+    def query_attn(self, cache: Cache, layer: int, n_ctx: int, q: torch.Tensor, k_self: torch.Tensor,
+                   v_self: torch.Tensor, q_pos0: int, out: Optional[torch.Tensor] = None,
+                   stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+        assert q.is_contiguous() and k_self.is_contiguous() and v_self.is_contiguous()
+        if out is None:
+            out = torch.empty_like(q)
+        self._check(self.lib.adapshot_query_attn(self._h, ctypes.byref(cache.c), layer, n_ctx, q.data_ptr(),
+                                                 k_self.data_ptr(), v_self.data_ptr(), q.shape[0], q_pos0,
+                                                 out.data_ptr(), _stream_ptr(stream)))
+        return out
+
+    # -- adapshot_probe_entropy
+    def probe_entropy(self, logits: torch.Tensor, out: Optional[torch.Tensor] = None,
+                      stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+        assert logits.dtype == torch.float32 and logits.dim() == 2 and logits.stride(1) == 1
+        rows, vocab = logits.shape
+        if out is None:
+            out = torch.empty(rows, dtype=torch.float32, device=logits.device)
+        self._check(self.lib.adapshot_probe_entropy(self._h, logits.data_ptr(), logits.stride(0) if rows > 1 else vocab,
+                                                    rows, vocab, out.data_ptr(), _stream_ptr(stream)))
+        return out

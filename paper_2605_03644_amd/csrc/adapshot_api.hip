@@ -1,0 +1,447 @@
+// Host side of libadapshot: contexts, argument validation, the integer plan
+// (prefix sums -> tile descriptors) and kernel launches.  No device code here.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "adapshot_internal.h"
+
+using namespace adapshot;
+
+namespace adapshot {
+
+hipError_t DevBuf::reserve(size_t need) {
+    if (need <= bytes) return hipSuccess;
+    if (p) {
+        // Earlier kernels may still read the old buffer: drain before freeing it.
+        hipError_t e = hipDeviceSynchronize();
+        if (e != hipSuccess) return e;
+        (void)hipFree(p);
+        p = nullptr;
+        bytes = 0;
+    }
+    size_t want = std::max(need, (size_t)1 << 16);
+    hipError_t e = hipMalloc(&p, want);
+    if (e != hipSuccess) {
+        p = nullptr;
+        return e;
+    }
+    bytes = want;
+    return hipSuccess;
+}
+
+void DevBuf::release() {
+    if (p) (void)hipFree(p);
+    p = nullptr;
+    bytes = 0;
+}
+
+hipError_t PinnedRing::acquire(size_t need, int* slot, void** ptr) {
+    int s = next;
+    next = (next + 1) % kSlots;
+    if (pending[s]) {
+        hipError_t e = hipEventSynchronize(ev[s]);
+        if (e != hipSuccess) return e;
+        pending[s] = false;
+    }
+    if (bytes[s] < need) {
+        if (host[s]) (void)hipHostFree(host[s]);
+        host[s] = nullptr;
+        bytes[s] = 0;
+        size_t want = std::max(need, (size_t)1 << 16);
+        hipError_t e = hipHostMalloc(&host[s], want, hipHostMallocDefault);
+        if (e != hipSuccess) {
+            host[s] = nullptr;
+            return e;
+        }
+        bytes[s] = want;
+    }
+    if (!ev[s]) {
+        hipError_t e = hipEventCreateWithFlags(&ev[s], hipEventDisableTiming);
+        if (e != hipSuccess) return e;
+    }
+    *slot = s;
+    *ptr = host[s];
+    return hipSuccess;
+}
+
+hipError_t PinnedRing::mark_in_use(int slot, hipStream_t stream) {
+    hipError_t e = hipEventRecord(ev[slot], stream);
+    if (e == hipSuccess) pending[slot] = true;
+    return e;
+}
+
+void PinnedRing::release() {
+    for (int s = 0; s < kSlots; ++s) {
+        if (pending[s] && ev[s]) (void)hipEventSynchronize(ev[s]);
+        if (ev[s]) (void)hipEventDestroy(ev[s]);
+        if (host[s]) (void)hipHostFree(host[s]);
+        ev[s] = nullptr;
+        host[s] = nullptr;
+        bytes[s] = 0;
+        pending[s] = false;
+    }
+}
+
+}  // namespace adapshot
+
+static adapshot_status fail(adapshot_ctx* ctx, adapshot_status st, const char* fmt, ...) {
+    if (ctx) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        ctx->last_error = buf;
+    }
+    return st;
+}
+
+static adapshot_status fail_hip(adapshot_ctx* ctx, const char* what, hipError_t e) {
+    (void)hipGetLastError();  // clear the sticky error so that it is not reported twice
+    return fail(ctx, ADAPSHOT_EDEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+static bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+
+extern "C" const char* adapshot_version(void) { return "libadapshot 0.1 (gfx950)"; }
+
+extern "C" const char* adapshot_last_error(const adapshot_ctx* ctx) {
+    return ctx ? ctx->last_error.c_str() : "null context";
+}
+
+// Validation of a model description; no device access.
+static const char* check_desc(const adapshot_model_desc& d) {
+    if (d.n_layers < 1) return "n_layers must be >= 1";
+    if (d.n_kv_heads < 1 || d.n_q_heads < 1) return "head counts must be >= 1";
+    if (d.n_q_heads % d.n_kv_heads != 0) return "n_q_heads must be a multiple of n_kv_heads";
+    if (d.dtype != ADAPSHOT_F32 && d.dtype != ADAPSHOT_BF16) return "dtype must be ADAPSHOT_F32 or ADAPSHOT_BF16";
+    if (d.key_state != ADAPSHOT_KEYS_UNROTATED && d.key_state != ADAPSHOT_KEYS_ROTATED_LOCAL)
+        return "key_state must be ADAPSHOT_KEYS_UNROTATED or ADAPSHOT_KEYS_ROTATED_LOCAL";
+    if (d.head_dim < 2 || d.head_dim % 2 != 0 || d.head_dim > 256) return "head_dim must be even and in [2, 256]";
+    int e = d.dtype == ADAPSHOT_F32 ? 4 : 2;
+    int half_bytes = d.head_dim / 2 * e;
+    if (half_bytes % 16 != 0) return "head_dim * sizeof(element) must be a multiple of 32 bytes";
+    int ch = half_bytes / 16;
+    if (ch != 1 && ch != 2 && ch != 4 && ch != 8 && ch != 16) return "head_dim/2 must span 1, 2, 4, 8 or 16 16-byte chunks";
+    if (!(d.rope_theta > 1.0) || !isfinite(d.rope_theta)) return "rope_theta must be finite and > 1";
+    if (d.max_position < 0 || d.max_position > ((int64_t)1 << 30)) return "max_position must be in [0, 2^30]";
+    return nullptr;
+}
+
+extern "C" adapshot_status adapshot_create(const adapshot_model_desc* desc, adapshot_ctx** out) {
+    if (out) *out = nullptr;
+    if (!desc || !out) return ADAPSHOT_EINVAL;
+    if (check_desc(*desc)) return ADAPSHOT_EINVAL;
+    adapshot_ctx* ctx = new (std::nothrow) adapshot_ctx();
+    if (!ctx) return ADAPSHOT_EDEVICE;
+    ctx->desc = *desc;
+    ctx->elem_bytes = desc->dtype == ADAPSHOT_F32 ? 4 : 2;
+    ctx->row_bytes = (int64_t)desc->n_kv_heads * desc->head_dim * ctx->elem_bytes;
+    ctx->max_position = desc->max_position ? desc->max_position : ((int64_t)1 << 20);
+    ctx->desc.max_position = ctx->max_position;
+
+    hipError_t e = hipGetDevice(&ctx->device);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        delete ctx;
+        return ADAPSHOT_EDEVICE;
+    }
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, ctx->device) == hipSuccess && prop.multiProcessorCount > 0)
+        ctx->n_cu = prop.multiProcessorCount;
+
+    // RoPE tables in fp64, rounded once to fp32.
+    const int half = desc->head_dim / 2;
+    const int64_t n_hi = (ctx->max_position + kRopeLo - 1) / kRopeLo + 1;
+    std::vector<float2> lo((size_t)kRopeLo * half), hi((size_t)n_hi * half);
+    std::vector<double> theta(half);
+    for (int i = 0; i < half; ++i) theta[i] = pow(desc->rope_theta, -2.0 * (double)i / (double)desc->head_dim);
+    for (int r = 0; r < kRopeLo; ++r)
+        for (int i = 0; i < half; ++i) {
+            double a = (double)r * theta[i];
+            lo[(size_t)r * half + i] = make_float2((float)cos(a), (float)sin(a));
+        }
+    for (int64_t r = 0; r < n_hi; ++r)
+        for (int i = 0; i < half; ++i) {
+            double a = (double)(r * kRopeLo) * theta[i];
+            hi[(size_t)r * half + i] = make_float2((float)cos(a), (float)sin(a));
+        }
+    e = hipMalloc((void**)&ctx->tab_lo, lo.size() * sizeof(float2));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->tab_hi, hi.size() * sizeof(float2));
+    if (e == hipSuccess) e = hipMemcpy(ctx->tab_lo, lo.data(), lo.size() * sizeof(float2), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(ctx->tab_hi, hi.data(), hi.size() * sizeof(float2), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        adapshot_destroy(ctx);
+        return ADAPSHOT_EDEVICE;
+    }
+    *out = ctx;
+    return ADAPSHOT_OK;
+}
+
+extern "C" void adapshot_destroy(adapshot_ctx* ctx) {
+    if (!ctx) return;
+    (void)hipDeviceSynchronize();
+    ctx->tile_ring.release();
+    ctx->q_rot.release();
+    ctx->k_rot.release();
+    ctx->part_o.release();
+    ctx->part_ml.release();
+    ctx->ent_part.release();
+    if (ctx->tab_lo) (void)hipFree(ctx->tab_lo);
+    if (ctx->tab_hi) (void)hipFree(ctx->tab_hi);
+    delete ctx;
+}
+
+extern "C" adapshot_status adapshot_pool_register(adapshot_ctx* ctx, const void* k_pool, const void* v_pool,
+                                                  const int64_t* shot_offsets, int32_t n_shots,
+                                                  int64_t layer_stride_tokens) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    if (!k_pool || !v_pool || !shot_offsets) return fail(ctx, ADAPSHOT_EINVAL, "pool_register: null pointer");
+    if (n_shots < 0) return fail(ctx, ADAPSHOT_EINVAL, "pool_register: n_shots < 0");
+    if (!aligned16(k_pool) || !aligned16(v_pool))
+        return fail(ctx, ADAPSHOT_EINVAL, "pool_register: pool pointers must be 16-byte aligned");
+    if (shot_offsets[0] < 0) return fail(ctx, ADAPSHOT_EINVAL, "pool_register: shot_offsets[0] < 0");
+    for (int32_t i = 0; i < n_shots; ++i)
+        if (shot_offsets[i + 1] < shot_offsets[i])
+            return fail(ctx, ADAPSHOT_EINVAL, "pool_register: shot_offsets decreases at %d", i);
+    if (shot_offsets[n_shots] > layer_stride_tokens)
+        return fail(ctx, ADAPSHOT_EINVAL, "pool_register: layer_stride_tokens %lld < pool tokens %lld",
+                    (long long)layer_stride_tokens, (long long)shot_offsets[n_shots]);
+    if (layer_stride_tokens > INT32_MAX)
+        return fail(ctx, ADAPSHOT_EINVAL, "pool_register: more than 2^31-1 tokens per layer");
+    ctx->k_pool = k_pool;
+    ctx->v_pool = v_pool;
+    ctx->shot_offsets.assign(shot_offsets, shot_offsets + n_shots + 1);
+    ctx->n_shots = n_shots;
+    ctx->pool_layer_stride_tokens = layer_stride_tokens;
+    ctx->last_error.clear();
+    return ADAPSHOT_OK;
+}
+
+extern "C" adapshot_status adapshot_assemble(adapshot_ctx* ctx, adapshot_cache* cache, const int32_t* shot_ids,
+                                             const int32_t* order, int32_t m, int64_t pos0, void* hip_stream) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    if (!cache) return fail(ctx, ADAPSHOT_EINVAL, "assemble: null cache");
+    if (m < 0) return fail(ctx, ADAPSHOT_EINVAL, "assemble: m < 0");
+    if (m > 0 && !shot_ids) return fail(ctx, ADAPSHOT_EINVAL, "assemble: null shot_ids");
+    if (!ctx->k_pool) return fail(ctx, ADAPSHOT_ESTATE, "assemble: no pool registered");
+    if (!cache->k || !cache->v) return fail(ctx, ADAPSHOT_EINVAL, "assemble: null cache buffers");
+    if (!aligned16(cache->k) || !aligned16(cache->v))
+        return fail(ctx, ADAPSHOT_EINVAL, "assemble: cache pointers must be 16-byte aligned");
+    if (cache->capacity < 0 || cache->capacity > INT32_MAX || cache->len < 0 || cache->len > cache->capacity)
+        return fail(ctx, ADAPSHOT_EINVAL, "assemble: bad cache capacity/len");
+    if (pos0 < 0) return fail(ctx, ADAPSHOT_EINVAL, "assemble: pos0 < 0");
+
+    // Pass 1 (integer plan): validate ids and total length before anything is written.
+    int64_t total = 0, n_tiles = 0;
+    for (int32_t j = 0; j < m; ++j) {
+        int32_t oj = order ? order[j] : j;
+        if (oj < 0 || oj >= m) return fail(ctx, ADAPSHOT_ESHOT, "assemble: order[%d] = %d out of range", j, oj);
+        int32_t s = shot_ids[oj];
+        if (s < 0 || s >= ctx->n_shots) return fail(ctx, ADAPSHOT_ESHOT, "assemble: shot id %d out of range", s);
+        int64_t len = ctx->shot_offsets[s + 1] - ctx->shot_offsets[s];
+        total += len;
+        n_tiles += (len + kTileTok - 1) / kTileTok;
+    }
+    if (cache->len + total > cache->capacity)
+        return fail(ctx, ADAPSHOT_ECAPACITY, "assemble: %lld + %lld tokens exceed capacity %lld",
+                    (long long)cache->len, (long long)total, (long long)cache->capacity);
+    if (pos0 + cache->len + total > ctx->max_position)
+        return fail(ctx, ADAPSHOT_ECAPACITY, "assemble: position %lld exceeds max_position %lld",
+                    (long long)(pos0 + cache->len + total), (long long)ctx->max_position);
+    if (total == 0) {
+        ctx->last_error.clear();
+        return ADAPSHOT_OK;
+    }
+    if (n_tiles > INT32_MAX) return fail(ctx, ADAPSHOT_EINVAL, "assemble: too many tiles");
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    int slot;
+    void* host;
+    hipError_t e = ctx->tile_ring.acquire((size_t)n_tiles * sizeof(TileDesc), &slot, &host);
+    if (e != hipSuccess) return fail_hip(ctx, "assemble: pinned tile buffer", e);
+
+    // Pass 2: slot j starts at off_j = sum of the lengths before it.
+    TileDesc* tiles = (TileDesc*)host;
+    const bool local = ctx->desc.key_state == ADAPSHOT_KEYS_ROTATED_LOCAL;
+    int64_t slot0 = cache->len, nt = 0;
+    for (int32_t j = 0; j < m; ++j) {
+        int32_t s = shot_ids[order ? order[j] : j];
+        int64_t src = ctx->shot_offsets[s], len = ctx->shot_offsets[s + 1] - src;
+        for (int64_t t0 = 0; t0 < len; t0 += kTileTok) {
+            TileDesc& d = tiles[nt++];
+            d.src_tok = (int32_t)(src + t0);
+            d.dst_slot = (int32_t)(slot0 + t0);
+            d.pos_first = (int32_t)(pos0 + slot0 + t0);
+            d.angle0 = local ? (int32_t)(pos0 + slot0) : d.pos_first;
+            d.angle_step = local ? 0 : 1;
+            d.n_tok = (int32_t)std::min<int64_t>(kTileTok, len - t0);
+            d.shot = s;
+            d.tok0 = (int32_t)t0;
+        }
+        slot0 += len;
+    }
+
+    AssembleParams p;
+    p.k_pool = (const char*)ctx->k_pool;
+    p.v_pool = (const char*)ctx->v_pool;
+    p.k_out = (char*)cache->k;
+    p.v_out = (char*)cache->v;
+    p.tiles = tiles;
+    p.tab_lo = ctx->tab_lo;
+    p.tab_hi = ctx->tab_hi;
+    p.slot_shot = cache->slot_shot;
+    p.slot_tok = cache->slot_tok;
+    p.slot_pos = cache->slot_pos;
+    p.pool_layer_stride_bytes = ctx->pool_layer_stride_tokens * ctx->row_bytes;
+    p.cache_layer_stride_bytes = cache->capacity * ctx->row_bytes;
+    p.n_tiles = (int32_t)nt;
+    p.n_layers = ctx->desc.n_layers;
+    // Enough workgroups to fill the chip several times over; beyond that a group walks its layers
+    // so that the per-token cos/sin are formed once and reused.
+    int64_t want_groups = ((int64_t)ctx->n_cu * 16 + nt - 1) / nt;
+    p.layer_groups = (int32_t)std::max<int64_t>(1, std::min<int64_t>(ctx->desc.n_layers, want_groups));
+    p.n_kv_heads = ctx->desc.n_kv_heads;
+    p.head_dim = ctx->desc.head_dim;
+    p.dtype = ctx->desc.dtype;
+    e = launch_assemble(p, stream);
+    if (e != hipSuccess) return fail_hip(ctx, "assemble: launch", e);
+    e = ctx->tile_ring.mark_in_use(slot, stream);
+    if (e != hipSuccess) return fail_hip(ctx, "assemble: event record", e);
+    cache->len += total;
+    ctx->last_error.clear();
+    return ADAPSHOT_OK;
+}
+
+extern "C" adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot_cache* cache, int32_t layer,
+                                               int64_t n_ctx, const void* q, const void* k_self,
+                                               const void* v_self, int32_t t_q, int64_t q_pos0, void* out,
+                                               void* hip_stream) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    if (!cache || !q || !k_self || !v_self || !out) return fail(ctx, ADAPSHOT_EINVAL, "query_attn: null pointer");
+    if (t_q < 1) return fail(ctx, ADAPSHOT_EINVAL, "query_attn: t_q < 1");
+    if (layer < 0 || layer >= ctx->desc.n_layers) return fail(ctx, ADAPSHOT_EINVAL, "query_attn: layer out of range");
+    if (n_ctx < 0) return fail(ctx, ADAPSHOT_EINVAL, "query_attn: n_ctx < 0");
+    if (n_ctx > cache->len || cache->len > cache->capacity)
+        return fail(ctx, ADAPSHOT_ESTATE, "query_attn: n_ctx %lld beyond assembled length %lld", (long long)n_ctx,
+                    (long long)cache->len);
+    if (n_ctx > 0 && (!cache->k || !cache->v)) return fail(ctx, ADAPSHOT_EINVAL, "query_attn: null cache buffers");
+    if (q_pos0 < 0 || q_pos0 + t_q > ctx->max_position)
+        return fail(ctx, ADAPSHOT_ECAPACITY, "query_attn: query positions exceed max_position");
+    if (!aligned16(q) || !aligned16(k_self) || !aligned16(v_self) || !aligned16(out) || !aligned16(cache->k) ||
+        !aligned16(cache->v))
+        return fail(ctx, ADAPSHOT_EINVAL, "query_attn: pointers must be 16-byte aligned");
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const adapshot_model_desc& d = ctx->desc;
+    const int g = d.n_q_heads / d.n_kv_heads;
+    const int64_t rows = (int64_t)t_q * g;
+    const bool mfma = attn_mfma_supported(d);
+
+    // Split the context so that (kv heads x row tiles x splits) covers the chip about twice;
+    // keys per split is a multiple of the 64-key tile.
+    const int64_t row_tile = mfma ? 128 : 1;
+    const int64_t row_tiles = (rows + row_tile - 1) / row_tile;
+    const int64_t units = d.n_kv_heads * row_tiles * (mfma ? 1 : 1);
+    int64_t key_tiles = (n_ctx + 63) / 64;
+    int64_t n_split = 0, keys_per_split = 64;
+    if (key_tiles > 0) {
+        int64_t target = mfma ? std::max<int64_t>(1, ((int64_t)ctx->n_cu * 2 + units - 1) / units)
+                              : std::max<int64_t>(1, ((int64_t)ctx->n_cu * 8 + units - 1) / units);
+        n_split = std::min<int64_t>(std::min<int64_t>(target, key_tiles), 64);
+        int64_t tiles_per_split = (key_tiles + n_split - 1) / n_split;
+        keys_per_split = tiles_per_split * 64;
+        n_split = (n_ctx + keys_per_split - 1) / keys_per_split;
+    }
+
+    const size_t esz = (size_t)ctx->elem_bytes;
+    hipError_t e = ctx->q_rot.reserve((size_t)t_q * d.n_q_heads * d.head_dim * esz);
+    if (e == hipSuccess) e = ctx->k_rot.reserve((size_t)t_q * d.n_kv_heads * d.head_dim * esz);
+    if (e == hipSuccess)
+        e = ctx->part_o.reserve((size_t)(n_split + 1) * d.n_kv_heads * rows * d.head_dim * sizeof(float));
+    if (e == hipSuccess) e = ctx->part_ml.reserve((size_t)(n_split + 1) * d.n_kv_heads * rows * sizeof(float2));
+    if (e != hipSuccess) return fail_hip(ctx, "query_attn: workspace", e);
+
+    RopeRowsParams rp;
+    rp.q = q;
+    rp.k_self = k_self;
+    rp.q_rot = ctx->q_rot.p;
+    rp.k_rot = ctx->k_rot.p;
+    rp.tab_lo = ctx->tab_lo;
+    rp.tab_hi = ctx->tab_hi;
+    rp.q_pos0 = q_pos0;
+    rp.t_q = t_q;
+    rp.n_q_heads = d.n_q_heads;
+    rp.n_kv_heads = d.n_kv_heads;
+    rp.head_dim = d.head_dim;
+    rp.dtype = d.dtype;
+    rp.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
+    e = launch_rope_rows(rp, stream);
+    if (e != hipSuccess) return fail_hip(ctx, "query_attn: rope launch", e);
+
+    AttnParams ap;
+    const int64_t layer_off = (int64_t)layer * cache->capacity * ctx->row_bytes;
+    ap.k_cache = (const char*)cache->k + layer_off;
+    ap.v_cache = (const char*)cache->v + layer_off;
+    ap.q_rot = ctx->q_rot.p;
+    ap.k_self_rot = ctx->k_rot.p;
+    ap.v_self = v_self;
+    ap.part_o = (float*)ctx->part_o.p;
+    ap.part_ml = (float2*)ctx->part_ml.p;
+    ap.out = out;
+    ap.n_ctx = n_ctx;
+    ap.keys_per_split = keys_per_split;
+    ap.n_split = (int32_t)n_split;
+    ap.t_q = t_q;
+    ap.n_q_heads = d.n_q_heads;
+    ap.n_kv_heads = d.n_kv_heads;
+    ap.head_dim = d.head_dim;
+    ap.dtype = d.dtype;
+    e = mfma ? launch_attn_mfma(ap, stream) : launch_attn_generic(ap, stream);
+    if (e != hipSuccess) return fail_hip(ctx, "query_attn: attention launch", e);
+    e = launch_attn_combine(ap, stream);
+    if (e != hipSuccess) return fail_hip(ctx, "query_attn: combine launch", e);
+    ctx->last_error.clear();
+    return ADAPSHOT_OK;
+}
+
+extern "C" adapshot_status adapshot_probe_entropy(adapshot_ctx* ctx, const float* logits, int64_t row_stride,
+                                                  int32_t n_rows, int32_t vocab, float* entropy_out,
+                                                  void* hip_stream) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    if (n_rows < 0 || vocab < 1) return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy: n_rows < 0 or vocab < 1");
+    if (n_rows == 0) {
+        ctx->last_error.clear();
+        return ADAPSHOT_OK;
+    }
+    if (!logits || !entropy_out) return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy: null pointer");
+    if (row_stride < vocab) return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy: row_stride < vocab");
+    if (((uintptr_t)logits & 3u) || ((uintptr_t)entropy_out & 3u))
+        return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy: pointers must be 4-byte aligned");
+
+    EntropyParams p;
+    p.logits = logits;
+    p.out = entropy_out;
+    p.row_stride = row_stride;
+    p.n_rows = n_rows;
+    p.vocab = vocab;
+    // Chunk of a row per workgroup: large when there are many rows, small when a few rows
+    // must still be spread over all compute units.  Multiple of 1024 floats.
+    int64_t chunk = 8192;
+    while (chunk > 1024 && (int64_t)n_rows * ((vocab + chunk - 1) / chunk) < (int64_t)ctx->n_cu * 4) chunk /= 2;
+    p.chunk = (int32_t)chunk;
+    p.n_chunks = (int32_t)((vocab + chunk - 1) / chunk);
+    hipError_t e = ctx->ent_part.reserve((size_t)n_rows * p.n_chunks * 3 * sizeof(float));
+    if (e != hipSuccess) return fail_hip(ctx, "probe_entropy: workspace", e);
+    p.partials = (float*)ctx->ent_part.p;
+    e = launch_entropy(p, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail_hip(ctx, "probe_entropy: launch", e);
+    ctx->last_error.clear();
+    return ADAPSHOT_OK;
+}

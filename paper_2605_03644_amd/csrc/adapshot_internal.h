@@ -1,0 +1,148 @@
+// Internal declarations shared by the host API and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "adapshot.h"
+
+namespace adapshot {
+
+// ---- RoPE tables --------------------------------------------------------------
+// Angle multiplier a (a position or a position offset) is split as a = 64*hi + lo.
+// tab_hi[hi][i] = (cos, sin)(64*hi*theta_i), tab_lo[lo][i] = (cos, sin)(lo*theta_i),
+// both evaluated in fp64 and rounded once to fp32.  cos/sin(a*theta_i) follows by one
+// angle addition in fp32 (error ~3e-7 absolute), see Eq. (rope_compensation).
+constexpr int kRopeLoBits = 6;
+constexpr int kRopeLo = 1 << kRopeLoBits;
+
+// ---- assemble tiles -------------------------------------------------------------
+// One tile = up to kTileTok consecutive tokens of ONE shot: contiguous in the pool
+// and contiguous in the cache.  Angle of token tau in the tile: angle0 + tau*angle_step.
+constexpr int kTileTok = 32;
+struct TileDesc {
+    int32_t src_tok;     // first pool token (index inside a layer)
+    int32_t dst_slot;    // first cache slot
+    int32_t angle0;      // angle multiplier of the first token
+    int32_t n_tok;       // 1..kTileTok
+    int32_t angle_step;  // 1: keys un-rotated (angle = position); 0: rotated at local positions (angle = shot offset)
+    int32_t shot;        // pool shot id
+    int32_t tok0;        // index of the first token inside its shot
+    int32_t pos_first;   // new position of the first token
+};
+static_assert(sizeof(TileDesc) == 32, "TileDesc is read as two 16-byte words");
+
+struct AssembleParams {
+    const char* k_pool;
+    const char* v_pool;
+    char* k_out;
+    char* v_out;
+    const TileDesc* tiles;  // pinned host memory, read by the kernel
+    const float2* tab_lo;
+    const float2* tab_hi;
+    int32_t* slot_shot;
+    int32_t* slot_tok;
+    int64_t* slot_pos;
+    int64_t pool_layer_stride_bytes;
+    int64_t cache_layer_stride_bytes;
+    int32_t n_tiles;
+    int32_t n_layers;
+    int32_t layer_groups;  // gridDim.y; each group strides over the layers
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t dtype;
+};
+hipError_t launch_assemble(const AssembleParams& p, hipStream_t stream);
+
+// ---- attention --------------------------------------------------------------------
+struct RopeRowsParams {
+    const void* q;       // [t_q][h_q][d]
+    const void* k_self;  // [t_q][h_kv][d]
+    void* q_rot;         // [t_q][h_q][d], scaled by log2(e)/sqrt(d)
+    void* k_rot;         // [t_q][h_kv][d]
+    const float2* tab_lo;
+    const float2* tab_hi;
+    int64_t q_pos0;
+    int32_t t_q, n_q_heads, n_kv_heads, head_dim, dtype;
+    float q_scale;
+};
+hipError_t launch_rope_rows(const RopeRowsParams& p, hipStream_t stream);
+
+// Split plan: splits 0..n_split-1 cover context keys [s*keys_per_split, ...) and
+// split n_split is the causal self part.  Partials are indexed [split][kv head][row]
+// with row = j*g + (h % g).
+struct AttnParams {
+    const void* k_cache;  // one layer [>=n_ctx][h_kv][d]
+    const void* v_cache;
+    const void* q_rot;
+    const void* k_self_rot;
+    const void* v_self;
+    float* part_o;   // [n_split+1][h_kv][rows][d]
+    float2* part_ml; // [n_split+1][h_kv][rows]  (running max in log2 units, sum)
+    void* out;       // [t_q][h_q][d]
+    int64_t n_ctx;
+    int64_t keys_per_split;
+    int32_t n_split;
+    int32_t t_q, n_q_heads, n_kv_heads, head_dim, dtype;
+};
+hipError_t launch_attn_generic(const AttnParams& p, hipStream_t stream);
+hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream);
+bool attn_mfma_supported(const adapshot_model_desc& d);
+hipError_t launch_attn_combine(const AttnParams& p, hipStream_t stream);
+
+// ---- entropy ------------------------------------------------------------------------
+struct EntropyParams {
+    const float* logits;
+    float* out;
+    float* partials;  // [n_rows][n_chunks][3] = (max, sum exp, sum (z-max) exp)
+    int64_t row_stride;
+    int32_t n_rows, vocab, chunk, n_chunks;
+};
+hipError_t launch_entropy(const EntropyParams& p, hipStream_t stream);
+
+// ---- host-side helpers -----------------------------------------------------------------
+struct DevBuf {
+    void* p = nullptr;
+    size_t bytes = 0;
+    hipError_t reserve(size_t need);  // grow-only
+    void release();
+};
+
+struct PinnedRing {
+    static constexpr int kSlots = 8;
+    void* host[kSlots] = {};
+    size_t bytes[kSlots] = {};
+    hipEvent_t ev[kSlots] = {};
+    bool pending[kSlots] = {};
+    int next = 0;
+    // Returns a pinned buffer of at least `need` bytes that no enqueued kernel still reads.
+    hipError_t acquire(size_t need, int* slot, void** ptr);
+    hipError_t mark_in_use(int slot, hipStream_t stream);
+    void release();
+};
+
+}  // namespace adapshot
+
+struct adapshot_ctx {
+    adapshot_model_desc desc;
+    int device = -1;
+    int elem_bytes = 0;
+    int64_t row_bytes = 0;  // n_kv_heads * head_dim * elem_bytes
+    int64_t max_position = 0;
+    // pool
+    const void* k_pool = nullptr;
+    const void* v_pool = nullptr;
+    std::vector<int64_t> shot_offsets;
+    int64_t pool_layer_stride_tokens = 0;
+    int32_t n_shots = 0;
+    // tables
+    float2* tab_lo = nullptr;
+    float2* tab_hi = nullptr;
+    // scratch
+    adapshot::PinnedRing tile_ring;
+    adapshot::DevBuf q_rot, k_rot, part_o, part_ml, ent_part;
+    int n_cu = 256;
+    std::string last_error;
+};

@@ -1,0 +1,191 @@
+// Fused gather + RoPE re-encode (Semantically-Aware KV Cache: concatenation in rank
+// order; Position Decoupling and Re-encoding, Eq. rope_compensation).
+//
+// A tile is up to kTileTok consecutive tokens of one shot: contiguous in the pool and
+// contiguous in the cache, so both sides of the copy are dense byte ranges and every
+// wavefront access is a run of full 128-byte lines.  HBM-bound: per token and layer
+// the kernel reads one K row and one V row and writes one of each.
+//
+//   blockIdx.x = tile, blockIdx.y = layer group (strides over layers), blockIdx.z = 0: K, 1: V.
+//
+// K workgroups first form cos/sin(a*theta_i) for every (token, frequency) of the tile
+// ONCE into LDS -- one fp32 angle addition of two fp64-built table entries,
+// a = 64*hi + lo -- and then stream all heads and layers through it: a lane owns the
+// two 16-byte chunks that hold the pair partners (i, i + d/2), rotates them in fp32 and
+// stores both.  V workgroups are a plain 128-bit copy.
+#include "adapshot_internal.h"
+
+namespace adapshot {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ u32x4 ld16(const char* p) { return __builtin_nontemporal_load((const u32x4*)p); }
+__device__ __forceinline__ void st16(char* p, u32x4 v) { *(u32x4*)p = v; }
+
+__device__ __forceinline__ float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
+// Two fp32 -> packed bf16, round to nearest even (hardware conversion on gfx950).
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    f32x2 f = {lo, hi};
+    bf16x2 b = __builtin_convertvector(f, bf16x2);
+    return __builtin_bit_cast(unsigned, b);
+}
+
+// Rotate the pair partners held in chunks a (first half of the head) and b (second half).
+// cs points at the (cos, sin) entries of this chunk's frequencies in LDS.
+template <int DTYPE>
+__device__ __forceinline__ void rotate_chunks(u32x4& a, u32x4& b, const float2* cs) {
+    if (DTYPE == ADAPSHOT_BF16) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            float2 c0 = cs[2 * w], c1 = cs[2 * w + 1];
+            float x1l = bf16_lo(a[w]), x1h = bf16_hi(a[w]);
+            float x2l = bf16_lo(b[w]), x2h = bf16_hi(b[w]);
+            float y1l = x1l * c0.x - x2l * c0.y, y2l = x2l * c0.x + x1l * c0.y;
+            float y1h = x1h * c1.x - x2h * c1.y, y2h = x2h * c1.x + x1h * c1.y;
+            a[w] = pack_bf16(y1l, y1h);
+            b[w] = pack_bf16(y2l, y2h);
+        }
+    } else {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            float2 c = cs[w];
+            float x1 = __uint_as_float(a[w]), x2 = __uint_as_float(b[w]);
+            a[w] = __float_as_uint(x1 * c.x - x2 * c.y);
+            b[w] = __float_as_uint(x2 * c.x + x1 * c.y);
+        }
+    }
+}
+
+// DTYPE: element type; CH: 16-byte chunks per half head (head_dim/2 * elem / 16).
+template <int DTYPE, int CH>
+__global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p) {
+    constexpr int E = DTYPE == ADAPSHOT_BF16 ? 2 : 4;
+    constexpr int NP = 16 / E;            // pairs per chunk
+    constexpr int HALF = CH * NP;         // head_dim / 2
+    constexpr int HEAD_BYTES = 2 * CH * 16;
+    __shared__ float2 cs[kTileTok * HALF];
+
+    const int tid = threadIdx.x;
+    const TileDesc td = p.tiles[blockIdx.x];
+    const int n_tok = td.n_tok;
+    const int64_t row_bytes = (int64_t)p.n_kv_heads * HEAD_BYTES;
+    const int64_t src_off = (int64_t)td.src_tok * row_bytes;
+    const int64_t dst_off = (int64_t)td.dst_slot * row_bytes;
+
+    if (blockIdx.z == 1) {
+        // ---- V: dense copy of n_tok rows per layer ----
+        const int n16 = (int)((n_tok * row_bytes) >> 4);
+        for (int l = blockIdx.y; l < p.n_layers; l += p.layer_groups) {
+            const char* src = p.v_pool + (int64_t)l * p.pool_layer_stride_bytes + src_off;
+            char* dst = p.v_out + (int64_t)l * p.cache_layer_stride_bytes + dst_off;
+            int i = tid;
+            for (; i + 768 < n16; i += 1024) {
+                u32x4 r0 = ld16(src + ((int64_t)i << 4));
+                u32x4 r1 = ld16(src + ((int64_t)(i + 256) << 4));
+                u32x4 r2 = ld16(src + ((int64_t)(i + 512) << 4));
+                u32x4 r3 = ld16(src + ((int64_t)(i + 768) << 4));
+                st16(dst + ((int64_t)i << 4), r0);
+                st16(dst + ((int64_t)(i + 256) << 4), r1);
+                st16(dst + ((int64_t)(i + 512) << 4), r2);
+                st16(dst + ((int64_t)(i + 768) << 4), r3);
+            }
+            for (; i < n16; i += 256) st16(dst + ((int64_t)i << 4), ld16(src + ((int64_t)i << 4)));
+        }
+        return;
+    }
+
+    // ---- K ----
+    if (blockIdx.y == 0 && tid < n_tok) {
+        if (p.slot_shot) p.slot_shot[td.dst_slot + tid] = td.shot;
+        if (p.slot_tok) p.slot_tok[td.dst_slot + tid] = td.tok0 + tid;
+        if (p.slot_pos) p.slot_pos[td.dst_slot + tid] = (int64_t)td.pos_first + tid;
+    }
+
+    // cos/sin of every (token, frequency) of the tile, two frequencies per step.
+    for (int it = tid; it < n_tok * (HALF / 2); it += 256) {
+        const int tau = it / (HALF / 2);
+        const int f2 = it - tau * (HALF / 2);
+        const int a = td.angle0 + tau * td.angle_step;
+        const f32x4 h = *(const f32x4*)(p.tab_hi + (int64_t)(a >> kRopeLoBits) * HALF + 2 * f2);
+        const f32x4 l = *(const f32x4*)(p.tab_lo + (a & (kRopeLo - 1)) * HALF + 2 * f2);
+        f32x4 r;
+        r[0] = h[0] * l[0] - h[1] * l[1];  // cos(A+B)
+        r[1] = h[1] * l[0] + h[0] * l[1];  // sin(A+B)
+        r[2] = h[2] * l[2] - h[3] * l[3];
+        r[3] = h[3] * l[2] + h[2] * l[3];
+        *(f32x4*)(cs + tau * HALF + 2 * f2) = r;
+    }
+    __syncthreads();
+
+    const int rpt = p.n_kv_heads * CH;  // lane items per token: (head, chunk)
+    const int n_items = n_tok * rpt;
+    for (int l = blockIdx.y; l < p.n_layers; l += p.layer_groups) {
+        const char* src = p.k_pool + (int64_t)l * p.pool_layer_stride_bytes + src_off;
+        char* dst = p.k_out + (int64_t)l * p.cache_layer_stride_bytes + dst_off;
+        for (int base = 0; base < n_items; base += 1024) {
+            u32x4 a[4], b[4];
+            int64_t off[4];
+            int csi[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int f = base + u * 256 + tid;
+                if (f < n_items) {
+                    const int tau = f / rpt;
+                    const int r = f - tau * rpt;
+                    const int h = r / CH;
+                    const int c = r - h * CH;
+                    off[u] = (int64_t)tau * row_bytes + h * HEAD_BYTES + c * 16;
+                    csi[u] = tau * HALF + c * NP;
+                    a[u] = ld16(src + off[u]);
+                    b[u] = ld16(src + off[u] + CH * 16);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int f = base + u * 256 + tid;
+                if (f < n_items) {
+                    rotate_chunks<DTYPE>(a[u], b[u], cs + csi[u]);
+                    st16(dst + off[u], a[u]);
+                    st16(dst + off[u] + CH * 16, b[u]);
+                }
+            }
+        }
+    }
+}
+
+template <int DTYPE, int CH>
+static hipError_t launch_t(const AssembleParams& p, hipStream_t stream) {
+    dim3 grid((unsigned)p.n_tiles, (unsigned)p.layer_groups, 2);
+    hipLaunchKernelGGL((assemble_reencode_kernel<DTYPE, CH>), grid, dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_assemble(const AssembleParams& p, hipStream_t stream) {
+    const int e = p.dtype == ADAPSHOT_BF16 ? 2 : 4;
+    const int ch = p.head_dim / 2 * e / 16;
+    if (p.n_tiles <= 0) return hipSuccess;
+    if (p.dtype == ADAPSHOT_BF16) {
+        switch (ch) {
+            case 1: return launch_t<ADAPSHOT_BF16, 1>(p, stream);
+            case 2: return launch_t<ADAPSHOT_BF16, 2>(p, stream);
+            case 4: return launch_t<ADAPSHOT_BF16, 4>(p, stream);
+            case 8: return launch_t<ADAPSHOT_BF16, 8>(p, stream);
+            case 16: return launch_t<ADAPSHOT_BF16, 16>(p, stream);
+        }
+    } else {
+        switch (ch) {
+            case 1: return launch_t<ADAPSHOT_F32, 1>(p, stream);
+            case 2: return launch_t<ADAPSHOT_F32, 2>(p, stream);
+            case 4: return launch_t<ADAPSHOT_F32, 4>(p, stream);
+            case 8: return launch_t<ADAPSHOT_F32, 8>(p, stream);
+            case 16: return launch_t<ADAPSHOT_F32, 16>(p, stream);
+        }
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace adapshot

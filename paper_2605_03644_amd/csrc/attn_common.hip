@@ -1,0 +1,207 @@
+// Query-over-cache attention, the parts shared by every shape:
+//   rope_rows     -- rotate the probe/query rows and their own keys to positions
+//                    q_pos0 + j (Eq. rope_encoding) and fold the softmax scale
+//                    log2(e)/sqrt(d) (Eq. attention_score's 1/sqrt(d)) into q;
+//   attn_generic  -- a straightforward fp32 split-K kernel (one wavefront per query
+//                    row, head and split) used for fp32 models and for shapes the
+//                    MFMA kernel does not cover;
+//   attn_combine  -- merges the per-split (max, sum, unnormalised output) partials.
+#include "adapshot_internal.h"
+
+namespace adapshot {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int DTYPE>
+__device__ __forceinline__ float load_elem(const void* base, int64_t i) {
+    if (DTYPE == ADAPSHOT_BF16) return __uint_as_float(((unsigned)((const unsigned short*)base)[i]) << 16);
+    return ((const float*)base)[i];
+}
+
+__device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
+    __bf16 b = (__bf16)f;
+    return __builtin_bit_cast(unsigned short, b);
+}
+
+template <int DTYPE>
+__device__ __forceinline__ void store_elem(void* base, int64_t i, float v) {
+    if (DTYPE == ADAPSHOT_BF16) ((unsigned short*)base)[i] = f32_to_bf16_rne(v);
+    else ((float*)base)[i] = v;
+}
+
+// ---- rope_rows ----------------------------------------------------------------------
+// One thread per rotation pair.  Rows 0..t_q*h_q-1 are query rows, the rest self-key rows.
+template <int DTYPE>
+__global__ __launch_bounds__(256) void rope_rows_kernel(RopeRowsParams p) {
+    const int half = p.head_dim >> 1;
+    const int64_t n_q = (int64_t)p.t_q * p.n_q_heads;
+    const int64_t n_k = (int64_t)p.t_q * p.n_kv_heads;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (n_q + n_k) * half) return;
+    const int64_t row = idx / half;
+    const int i = (int)(idx - row * half);
+    const bool is_q = row < n_q;
+    const int64_t r = is_q ? row : row - n_q;
+    const int j = (int)(r / (is_q ? p.n_q_heads : p.n_kv_heads));
+    const int64_t a = p.q_pos0 + j;
+    const float2 h = p.tab_hi[(a >> kRopeLoBits) * half + i];
+    const float2 l = p.tab_lo[(a & (kRopeLo - 1)) * half + i];
+    const float c = h.x * l.x - h.y * l.y;
+    const float s = h.y * l.x + h.x * l.y;
+    const void* src = is_q ? p.q : p.k_self;
+    void* dst = is_q ? p.q_rot : p.k_rot;
+    const int64_t o = r * p.head_dim + i;
+    const float x1 = load_elem<DTYPE>(src, o), x2 = load_elem<DTYPE>(src, o + half);
+    const float sc = is_q ? p.q_scale : 1.0f;
+    store_elem<DTYPE>(dst, o, (x1 * c - x2 * s) * sc);
+    store_elem<DTYPE>(dst, o + half, (x2 * c + x1 * s) * sc);
+}
+
+hipError_t launch_rope_rows(const RopeRowsParams& p, hipStream_t stream) {
+    const int64_t n = (int64_t)p.t_q * (p.n_q_heads + p.n_kv_heads) * (p.head_dim / 2);
+    const unsigned blocks = (unsigned)((n + 255) / 256);
+    if (p.dtype == ADAPSHOT_BF16)
+        hipLaunchKernelGGL(rope_rows_kernel<ADAPSHOT_BF16>, dim3(blocks), dim3(256), 0, stream, p);
+    else
+        hipLaunchKernelGGL(rope_rows_kernel<ADAPSHOT_F32>, dim3(blocks), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+// ---- wavefront reductions --------------------------------------------------------------
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// ---- generic fp32 kernel -----------------------------------------------------------------
+// grid = (t_q * h_q, n_split + 1); one wavefront each.  Lanes run over 64 keys for the
+// scores and over the head dimension for p.v.  Works in log2 units: q is pre-scaled by
+// log2(e)/sqrt(d), so p = 2^(s - m).
+template <int DTYPE>
+__global__ __launch_bounds__(64) void attn_generic_kernel(AttnParams p) {
+    __shared__ float q_s[256];
+    __shared__ float p_s[64];
+    const int lane = threadIdx.x;
+    const int d = p.head_dim;
+    const int g = p.n_q_heads / p.n_kv_heads;
+    const int j = blockIdx.x / p.n_q_heads;
+    const int h = blockIdx.x - j * p.n_q_heads;
+    const int hk = h / g;
+    const int split = blockIdx.y;
+    const bool self = split == p.n_split;
+    const int64_t rows = (int64_t)p.t_q * g;
+    const int64_t row = (int64_t)j * g + (h - hk * g);
+
+    for (int e = lane; e < d; e += 64) q_s[e] = load_elem<DTYPE>(p.q_rot, ((int64_t)j * p.n_q_heads + h) * d + e);
+    __syncthreads();
+
+    const void* kbase = self ? p.k_self_rot : p.k_cache;
+    const void* vbase = self ? p.v_self : p.v_cache;
+    int64_t k0 = self ? 0 : (int64_t)split * p.keys_per_split;
+    int64_t k1 = self ? (int64_t)j + 1 : (k0 + p.keys_per_split < p.n_ctx ? k0 + p.keys_per_split : p.n_ctx);
+
+    float m = -INFINITY, l = 0.f;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t kb = k0; kb < k1; kb += 64) {
+        const int64_t u = kb + lane;
+        float s = -INFINITY;
+        if (u < k1) {
+            const int64_t o = (u * p.n_kv_heads + hk) * d;
+            float dot = 0.f;
+            for (int e = 0; e < d; ++e) dot += q_s[e] * load_elem<DTYPE>(kbase, o + e);
+            s = dot;
+        }
+        const float m_new = fmaxf(m, wave_max(s));
+        const float alpha = exp2f(m - m_new);  // m = -inf on the first block: 0
+        const float pe = (u < k1) ? exp2f(s - m_new) : 0.f;
+        l = l * alpha + wave_sum(pe);
+        m = m_new;
+        p_s[lane] = pe;
+        __syncthreads();
+        const int nk = (int)((k1 - kb) < 64 ? (k1 - kb) : 64);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int e = lane + 64 * c;
+            if (e < d) {
+                float a = acc[c] * alpha;
+                for (int t = 0; t < nk; ++t)
+                    a += p_s[t] * load_elem<DTYPE>(vbase, ((kb + t) * p.n_kv_heads + hk) * d + e);
+                acc[c] = a;
+            }
+        }
+        __syncthreads();
+    }
+    const int64_t pr = ((int64_t)split * p.n_kv_heads + hk) * rows + row;
+    if (lane == 0) p.part_ml[pr] = make_float2(m, l);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const int e = lane + 64 * c;
+        if (e < d) p.part_o[pr * d + e] = acc[c];
+    }
+}
+
+hipError_t launch_attn_generic(const AttnParams& p, hipStream_t stream) {
+    dim3 grid((unsigned)(p.t_q * p.n_q_heads), (unsigned)(p.n_split + 1));
+    if (p.dtype == ADAPSHOT_BF16)
+        hipLaunchKernelGGL(attn_generic_kernel<ADAPSHOT_BF16>, grid, dim3(64), 0, stream, p);
+    else
+        hipLaunchKernelGGL(attn_generic_kernel<ADAPSHOT_F32>, grid, dim3(64), 0, stream, p);
+    return hipGetLastError();
+}
+
+// ---- combine --------------------------------------------------------------------------------
+// One workgroup of 64 lanes per (kv head, row).  out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+// The self split always holds at least one visible key, so the denominator is > 0.
+template <int DTYPE>
+__global__ __launch_bounds__(64) void attn_combine_kernel(AttnParams p) {
+    const int lane = threadIdx.x;
+    const int d = p.head_dim;
+    const int g = p.n_q_heads / p.n_kv_heads;
+    const int64_t rows = (int64_t)p.t_q * g;
+    const int hk = blockIdx.x / rows;
+    const int64_t row = blockIdx.x - (int64_t)hk * rows;
+    const int j = (int)(row / g);
+    const int h = hk * g + (int)(row - (int64_t)j * g);
+    const int ns = p.n_split + 1;
+
+    float M = -INFINITY;
+    for (int s = 0; s < ns; ++s) M = fmaxf(M, p.part_ml[((int64_t)s * p.n_kv_heads + hk) * rows + row].x);
+    float L = 0.f;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < ns; ++s) {
+        const int64_t pr = ((int64_t)s * p.n_kv_heads + hk) * rows + row;
+        const float2 ml = p.part_ml[pr];
+        const float w = exp2f(ml.x - M);
+        if (w == 0.f) continue;  // empty or negligible split; also skips uninitialised garbage times 0
+        L += w * ml.y;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int e = lane + 64 * c;
+            if (e < d) acc[c] += w * p.part_o[pr * d + e];
+        }
+    }
+    const float inv = 1.0f / L;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const int e = lane + 64 * c;
+        if (e < d) store_elem<DTYPE>(p.out, ((int64_t)j * p.n_q_heads + h) * d + e, acc[c] * inv);
+    }
+}
+
+hipError_t launch_attn_combine(const AttnParams& p, hipStream_t stream) {
+    const int g = p.n_q_heads / p.n_kv_heads;
+    dim3 grid((unsigned)((int64_t)p.n_kv_heads * p.t_q * g));
+    if (p.dtype == ADAPSHOT_BF16)
+        hipLaunchKernelGGL(attn_combine_kernel<ADAPSHOT_BF16>, grid, dim3(64), 0, stream, p);
+    else
+        hipLaunchKernelGGL(attn_combine_kernel<ADAPSHOT_F32>, grid, dim3(64), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace adapshot

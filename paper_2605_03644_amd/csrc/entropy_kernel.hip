@@ -1,0 +1,169 @@
+// Entropy of softmax(logits) over the whole vocabulary (Eq. entropy), natural log.
+//
+// With m = max z, e_v = exp(z_v - m), s = sum e_v, t = sum (z_v - m) e_v:
+//     H = ln s - t / s.
+// One HBM pass: a workgroup reduces one chunk of one row to (m, s, t) with an online
+// rescale per 16-element batch; a second tiny kernel merges the chunks of a row.
+// Partials re-base as  s' = s * exp(m - M),  t' = (t + (m - M) * s) * exp(m - M).
+#include "adapshot_internal.h"
+
+namespace adapshot {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+struct Mst {
+    float m, s, t;
+};
+
+// Merge b into a.  -inf maxima (empty parts) are handled by the w == 0 branches.
+__device__ __forceinline__ Mst mst_merge(Mst a, Mst b) {
+    const float M = fmaxf(a.m, b.m);
+    Mst r;
+    r.m = M;
+    if (M == -INFINITY) {  // both empty so far (or all -inf): keep sums as they are (0, or NaN markers)
+        r.s = a.s + b.s;
+        r.t = a.t + b.t;
+        return r;
+    }
+    const float da = a.m - M, db = b.m - M;  // <= 0, may be -inf
+    const float wa = __expf(da), wb = __expf(db);
+    const float ta = wa > 0.f ? (a.t + da * a.s) * wa : 0.f;
+    const float tb = wb > 0.f ? (b.t + db * b.s) * wb : 0.f;
+    r.s = a.s * wa + b.s * wb;
+    r.t = ta + tb;
+    return r;
+}
+
+__device__ __forceinline__ Mst mst_wave_reduce(Mst v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        Mst w;
+        w.m = __shfl_xor(v.m, o, 64);
+        w.s = __shfl_xor(v.s, o, 64);
+        w.t = __shfl_xor(v.t, o, 64);
+        v = mst_merge(v, w);
+    }
+    return v;
+}
+
+// Fold a batch of N values into the running (m, s, t).  NaN logits poison s through exp(NaN).
+template <int N>
+__device__ __forceinline__ void mst_add_batch(Mst& acc, const float (&z)[N]) {
+    float bm = z[0];
+#pragma unroll
+    for (int i = 1; i < N; ++i) bm = fmaxf(bm, z[i]);
+    bool nan = false;
+#pragma unroll
+    for (int i = 0; i < N; ++i) nan |= (z[i] != z[i]);
+    const float M = fmaxf(acc.m, bm);
+    if (nan || M == INFINITY) {  // NaN or +inf logit: the row has no distribution
+        acc.m = M;
+        acc.s = NAN;
+        acc.t = NAN;
+        return;
+    }
+    if (M == -INFINITY) return;  // nothing but -inf so far
+    if (M > acc.m) {
+        const float dm = acc.m - M;
+        const float w = __expf(dm);  // acc.m = -inf -> 0
+        acc.t = w > 0.f ? (acc.t + dm * acc.s) * w : 0.f;
+        acc.s *= w;
+        acc.m = M;
+    }
+    float s = 0.f, t = 0.f;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const float dz = z[i] - M;
+        const float e = __expf(dz);
+        s += e;
+        t += e > 0.f ? dz * e : 0.f;
+    }
+    acc.s += s;
+    acc.t += t;
+}
+
+// grid = (n_chunks, n_rows), 256 threads.  VEC: rows are 16-byte aligned -> float4 loads.
+template <bool VEC>
+__global__ __launch_bounds__(256) void entropy_chunk_kernel(EntropyParams p) {
+    __shared__ Mst red[4];
+    const int tid = threadIdx.x;
+    const float* z = p.logits + (int64_t)blockIdx.y * p.row_stride;
+    const int c0 = blockIdx.x * p.chunk;
+    const int c1 = min(c0 + p.chunk, p.vocab);
+    Mst acc = {-INFINITY, 0.f, 0.f};
+    if (VEC) {
+        // 4 float4 per thread per step, each load instruction covering 4 KB contiguous per workgroup
+        for (int base = c0; base < c1; base += 4096) {
+            float v[16];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + u * 1024 + tid * 4;
+                f32x4 x = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+                if (i + 3 < c1) {
+                    x = __builtin_nontemporal_load((const f32x4*)(z + i));
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        if (i + k < c1) x[k] = z[i + k];
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) v[4 * u + k] = x[k];
+            }
+            mst_add_batch<16>(acc, v);
+        }
+    } else {
+        for (int base = c0; base < c1; base += 1024) {
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + u * 256 + tid;
+                v[u] = i < c1 ? z[i] : -INFINITY;
+            }
+            mst_add_batch<4>(acc, v);
+        }
+    }
+    acc = mst_wave_reduce(acc);
+    if ((tid & 63) == 0) red[tid >> 6] = acc;
+    __syncthreads();
+    if (tid == 0) {
+        Mst r = mst_merge(mst_merge(red[0], red[1]), mst_merge(red[2], red[3]));
+        float* o = p.partials + ((int64_t)blockIdx.y * p.n_chunks + blockIdx.x) * 3;
+        o[0] = r.m;
+        o[1] = r.s;
+        o[2] = r.t;
+    }
+}
+
+// One wavefront per row merges its chunk partials and writes H.
+__global__ __launch_bounds__(64) void entropy_finish_kernel(EntropyParams p) {
+    const int row = blockIdx.x;
+    const int lane = threadIdx.x;
+    Mst acc = {-INFINITY, 0.f, 0.f};
+    for (int c = lane; c < p.n_chunks; c += 64) {
+        const float* o = p.partials + ((int64_t)row * p.n_chunks + c) * 3;
+        Mst b = {o[0], o[1], o[2]};
+        acc = mst_merge(acc, b);
+    }
+    acc = mst_wave_reduce(acc);
+    if (lane == 0) {
+        float h;
+        if (acc.m == -INFINITY || acc.m == INFINITY) h = NAN;  // no finite logit, or a +inf logit
+        else h = logf(acc.s) - acc.t / acc.s;                 // NaN sums propagate
+        p.out[row] = h;
+    }
+}
+
+hipError_t launch_entropy(const EntropyParams& p, hipStream_t stream) {
+    dim3 grid((unsigned)p.n_chunks, (unsigned)p.n_rows);
+    const bool vec = (((uintptr_t)p.logits & 15u) == 0) && (p.row_stride % 4 == 0);
+    if (vec)
+        hipLaunchKernelGGL(entropy_chunk_kernel<true>, grid, dim3(256), 0, stream, p);
+    else
+        hipLaunchKernelGGL(entropy_chunk_kernel<false>, grid, dim3(256), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(entropy_finish_kernel, dim3((unsigned)p.n_rows), dim3(64), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace adapshot

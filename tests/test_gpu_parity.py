@@ -1,0 +1,247 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs.  Bars: indexing bit-exact; fp32 re-encode 1e-5 relative per rotation pair;
+bf16 keys >= 99 % identical to the oracle's rounding and each within
+half a bf16 spacing + 1e-5 relative of the exact key; attention 2e-2 max-abs and
+1e-2 relative Frobenius (bf16), 1e-4 / 1e-5 (fp32 path); entropy 1e-4."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_03644_amd import workloads as wl
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ad():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2605_03644_amd import binding
+    binding.load_library()          # raises if the HIP library is not built: no fallback
+    return binding
+
+
+def _pool_numpy(k, v):
+    return H.to_storage(k), H.to_storage(v)
+
+
+def _run_assemble_case(ad, oracle_mod, w, key_state, pos0, splits, n_layers=None, ids=None, order=None):
+    """Assemble on the GPU (possibly as several appends) and with the oracle; compare everything."""
+    dev = "cuda"
+    L = w.n_layers if n_layers is None else n_layers
+    k_pool, v_pool, off = wl.make_pool(w, dev, n_layers=L)
+    if ids is None:
+        ids, order = wl.selection(w)
+    ctx = ad.Context.for_workload(w, key_state=key_state, n_layers=L)
+    ctx.pool_register(k_pool, v_pool, off)
+    seq = [int(ids[o]) for o in order] if order is not None else [int(i) for i in ids]
+    total = int(sum(off[s + 1] - off[s] for s in seq))
+    cap = total + 5
+    cache = ad.Cache(ctx, cap)
+    canary_k = cache.k[:, total:].clone()
+    # appends: the first uses (ids, order) sliced through `order`; later ones pass explicit id lists
+    bounds = [0] + [int(len(seq) * f) for f in splits] + [len(seq)]
+    for a, b in zip(bounds[:-1], bounds[1:]):
+        if a == 0 and b == len(seq) and order is not None:
+            ctx.assemble(cache, ids, order, pos0=pos0)
+        else:
+            ctx.assemble(cache, seq[a:b], None, pos0=pos0)
+    torch.cuda.synchronize()
+    assert cache.len == total
+
+    kp, vp = _pool_numpy(k_pool, v_pool)
+    pl = oracle_mod.plan(off, ids, order, slot0=0, pos0=pos0)
+    assert pl["n"] == total
+    ko, vo, kx = oracle_mod.assemble(kp, vp, w.dtype, w.rope_theta, key_state, pl, 0, cap, want_exact=True)
+
+    # indexing: bit exact
+    assert np.array_equal(cache.slot_shot[:total].cpu().numpy(), pl["slot_shot"])
+    assert np.array_equal(cache.slot_tok[:total].cpu().numpy(), pl["slot_tok"])
+    assert np.array_equal(cache.slot_pos[:total].cpu().numpy(), pl["slot_pos"])
+    assert (cache.slot_shot[total:] == -1).all() and (cache.slot_pos[total:] == -1).all()
+    # V: bit copy; nothing written past the end
+    kg, vg = H.to_storage(cache.k), H.to_storage(cache.v)
+    assert np.array_equal(vg[:, :total], vo[:, :total])
+    assert not vg[:, total:].any()
+    assert torch.equal(cache.k[:, total:], canary_k)
+    # K
+    if w.dtype == "f32":
+        src = kp[:, pl["slot_src"]]
+        worst = H.check_reencode_f32(kg[:, :total], kx, src, rel=1e-5)
+        return dict(worst_rel=worst, total=total)
+    frac = H.check_reencode_bf16(kg[:, :total], ko[:, :total], kx, kp[:, pl["slot_src"]])
+    ctx.close()
+    return dict(frac_equal=frac, total=total)
+
+
+@pytest.mark.parametrize("key_state", [0, 1])
+@pytest.mark.parametrize("pos0,splits", [(0, []), (11, [0.4]), (100000, [0.25, 0.5])])
+def test_assemble_tiny_fp32(ad, oracle_mod, key_state, pos0, splits):
+    w = wl.WORKLOADS["tiny_fp32"]
+    _run_assemble_case(ad, oracle_mod, w, key_state, pos0, splits)
+
+
+def test_assemble_tiny_fp32_multilayer_duplicates(ad, oracle_mod):
+    w = wl.WORKLOADS["tiny_fp32"]
+    ids = np.array([3, 3, 15, 0, 7, 3], np.int32)
+    order = np.array([5, 0, 2, 1, 4, 3], np.int32)
+    _run_assemble_case(ad, oracle_mod, w, 0, 7, [], n_layers=3, ids=ids, order=order)
+
+
+@pytest.mark.parametrize("key_state", [0, 1])
+def test_assemble_llama8b_bf16_full(ad, oracle_mod, key_state):
+    """Config 2 at full size (256 of 2000 shots, ~26k tokens), the launch shape the benchmark times."""
+    w = wl.WORKLOADS["llama8b_1layer"]
+    r = _run_assemble_case(ad, oracle_mod, w, key_state, 0, [])
+    assert r["total"] > 20000
+
+
+def test_assemble_qwen_shape_bf16_two_layers(ad, oracle_mod):
+    """4 KV heads (half a wavefront per token row), theta 1e6, two layers, three appends."""
+    w = wl.WORKLOADS["qwen7b_decode"]
+    _run_assemble_case(ad, oracle_mod, w, 0, 3, [0.3, 0.9], n_layers=2)
+
+
+def test_assemble_errors_write_nothing(ad):
+    w = wl.WORKLOADS["tiny_fp32"]
+    k_pool, v_pool, off = wl.make_pool(w, "cuda")
+    ctx = ad.Context.for_workload(w, max_position=4096)
+    cache = ad.Cache(ctx, 64)
+    with pytest.raises(ad.AdapshotError) as e:
+        ctx.assemble(cache, [0, 1])
+    assert e.value.status == ad.ESTATE
+    ctx.pool_register(k_pool, v_pool, off)
+    for ids, order, pos0, status in [([0, 16], None, 0, ad.ESHOT), ([-1], None, 0, ad.ESHOT),
+                                     ([0, 1], [0, 2], 0, ad.ESHOT), ([0, 1, 2, 3], None, 0, ad.ECAPACITY),
+                                     ([0], None, 4090, ad.ECAPACITY), ([0], None, -1, ad.EINVAL)]:
+        with pytest.raises(ad.AdapshotError) as e:
+            ctx.assemble(cache, ids, order, pos0=pos0)
+        assert e.value.status == status, (ids, e.value)
+        assert ctx.last_error()
+    torch.cuda.synchronize()
+    assert cache.len == 0 and not cache.k.any() and not cache.v.any() and (cache.slot_shot == -1).all()
+    ctx.assemble(cache, [], None)          # m = 0 is a no-op
+    assert cache.len == 0
+    ctx.assemble(cache, [2])
+    assert cache.len == int(off[3] - off[2]) and ctx.last_error() == ""
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------ entropy
+
+def _entropy_case(ad, oracle_mod, z: torch.Tensor, tol=1e-4):
+    ctx = ad.Context(1, 4, 2, 64, 1.0e4, ad.F32)
+    got = ctx.probe_entropy(z).cpu().numpy().astype(np.float64)
+    want = oracle_mod.entropy(z.cpu().numpy())
+    ctx.close()
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    if (~nan).any():
+        err = np.abs(got[~nan] - want[~nan]).max()
+        assert err <= tol, f"entropy error {err:.3e}"
+    return got, want
+
+
+def test_entropy_workloads(ad, oracle_mod):
+    for name in ("tiny_fp32", "llama8b_1layer"):
+        w = wl.WORKLOADS[name]
+        z = wl.make_logits(w, "cuda")
+        got, want = _entropy_case(ad, oracle_mod, z)
+        assert abs(want.mean() - (math.log(w.vocab) - 1.0)) < 0.2
+
+
+@pytest.mark.parametrize("rows,vocab", [(1, 128256), (48, 128256), (3, 1), (5, 7), (2, 1023), (2, 1025), (7, 4099),
+                                        (2, 152064), (300, 333)])
+def test_entropy_shapes(ad, oracle_mod, rows, vocab):
+    g = torch.Generator(device="cuda"); g.manual_seed(rows * 1000003 + vocab)
+    z = torch.randn(rows, vocab, device="cuda", generator=g) * 3.0
+    _entropy_case(ad, oracle_mod, z)
+
+
+def test_entropy_strided_and_unaligned_rows(ad, oracle_mod):
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    big = torch.randn(6, 5003, device="cuda", generator=g)
+    _entropy_case(ad, oracle_mod, big[:, :5001])           # row stride 5003: rows not 16-byte aligned
+    _entropy_case(ad, oracle_mod, big[:, 1:4097])          # base pointer off by 4 bytes
+    big2 = torch.randn(4, 8192, device="cuda", generator=g)
+    _entropy_case(ad, oracle_mod, big2[:, :8000])          # aligned rows, stride > vocab
+
+
+def test_entropy_closed_forms_and_degenerate_rows(ad, oracle_mod):
+    V = 128256
+    z = torch.zeros(8, V, device="cuda")
+    z[1] = 3.25
+    z[2, 77] = 1.0e4                      # one-hot: H = 0
+    z[3] = -float("inf"); z[3, 5] = 0.0   # single finite logit: H = 0
+    z[4, 100] = float("nan")
+    z[5, V - 1] = float("inf")
+    z[6] = -float("inf")
+    z[7, :40000] = -float("inf")          # -inf entries contribute 0
+    got, want = _entropy_case(ad, oracle_mod, z)
+    assert abs(got[0] - math.log(V)) < 1e-4 and abs(got[1] - math.log(V)) < 1e-4
+    assert got[2] == 0.0 and got[3] == 0.0
+    assert abs(got[7] - math.log(V - 40000)) < 1e-4
+    ctx = ad.Context(1, 4, 2, 64, 1.0e4, ad.F32)
+    with pytest.raises(ad.AdapshotError):
+        ctx.lib.adapshot_probe_entropy.restype  # keep linters quiet
+        ctx._check(ctx.lib.adapshot_probe_entropy(ctx._h, z.data_ptr(), 10, 1, 100, z.data_ptr(), None))
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------ attention
+
+def _attention_case(ad, oracle_mod, w, n_shots_sel, t_q, pos0=0, q_pos0=None, n_ctx=None, max_abs=2e-2,
+                    rel_fro=1e-2, mutate=None, pairs=None, seed_q=0):
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=1)
+    ids, order = wl.selection(w)
+    ids, order = ids[:n_shots_sel], np.argsort(np.argsort(order[:n_shots_sel])).astype(np.int32)
+    ctx = ad.Context.for_workload(w, n_layers=1)
+    ctx.pool_register(k_pool, v_pool, off)
+    total = int(sum(off[i + 1] - off[i] for i in ids))
+    cache = ad.Cache(ctx, max(total, 1), with_index=False)
+    ctx.assemble(cache, ids, order, pos0=pos0)
+    n_ctx = total if n_ctx is None else n_ctx
+    q_pos0 = pos0 + n_ctx if q_pos0 is None else q_pos0
+    q, ks, vs = wl.make_query(w, "cuda", query=seed_q, t_q=t_q)
+    if mutate is not None:
+        mutate(cache, q, ks, vs, q_pos0)
+    out = ctx.query_attn(cache, 0, n_ctx, q, ks, vs, q_pos0)
+    torch.cuda.synchronize()
+    # the oracle attends over the GPU-assembled cache (assemble parity is tested on its own)
+    kc, vc = H.to_storage(cache.k[0]), H.to_storage(cache.v[0])
+    ref = oracle_mod.query_attn(kc, vc, w.dtype, n_ctx, H.to_storage(q), H.to_storage(ks), H.to_storage(vs),
+                                w.rope_theta, q_pos0, pairs=pairs)
+    got = out.float().cpu().numpy()
+    if pairs is not None:
+        got = np.stack([got[j, h] for j, h in pairs])
+    res = H.check_attention(got, ref, max_abs=max_abs, rel_fro=rel_fro)
+    ctx.close()
+    return res, got, ref
+
+
+def test_attention_tiny_fp32(ad, oracle_mod):
+    w = wl.WORKLOADS["tiny_fp32"]
+    _attention_case(ad, oracle_mod, w, 8, 16, max_abs=1e-4, rel_fro=1e-5)
+    _attention_case(ad, oracle_mod, w, 8, 16, pos0=5000, max_abs=1e-4, rel_fro=1e-5)
+    _attention_case(ad, oracle_mod, w, 3, 1, max_abs=1e-4, rel_fro=1e-5)
+
+
+def test_attention_tiny_fp32_no_context_and_prefix(ad, oracle_mod):
+    w = wl.WORKLOADS["tiny_fp32"]
+    _attention_case(ad, oracle_mod, w, 8, 16, n_ctx=0, q_pos0=0, max_abs=1e-4, rel_fro=1e-5)
+    _attention_case(ad, oracle_mod, w, 8, 5, n_ctx=77, max_abs=1e-4, rel_fro=1e-5)   # a prefix of the cache
+
+
+def test_attention_needle_tiny(ad, oracle_mod):
+    """One context key made parallel to a rotated query and scaled x50: the output is that key's value row."""
+    w = wl.WORKLOADS["tiny_fp32"]
+
+    def mutate(cache, q, ks, vs, q_pos0):
+        qr = oracle_mod.rot(q[0, 0].double().cpu().numpy(), w.rope_theta, q_pos0)   # row 0 sits at q_pos0
+        cache.k[0, 100, 0, :] = torch.from_numpy(50.0 * qr / np.linalg.norm(qr)).to(cache.k.dtype).cuda()
+
+    (_, _), got, ref = _attention_case(ad, oracle_mod, w, 8, 4, max_abs=1e-4, rel_fro=1e-5, mutate=mutate)
+    assert np.abs(ref).max() > 0.5          # outputs are O(1) somewhere, so the max-abs bar has teeth
