@@ -245,3 +245,57 @@ def test_attention_needle_tiny(ad, oracle_mod):
 
     (_, _), got, ref = _attention_case(ad, oracle_mod, w, 8, 4, max_abs=1e-4, rel_fro=1e-5, mutate=mutate)
     assert np.abs(ref).max() > 0.5          # outputs are O(1) somewhere, so the max-abs bar has teeth
+
+
+# ------------------------------------------------------------------------------ bf16 MFMA attention
+
+@pytest.mark.parametrize("name,n_sel,t_q", [("llama8b_1layer", 3, 16), ("llama8b_1layer", 9, 128), ("llama8b_1layer", 5, 37),
+                                            ("llama8b_1layer", 1, 1), ("qwen7b_decode", 7, 1), ("qwen7b_decode", 4, 19),
+                                            ("llama70b_128k", 6, 40)])
+def test_attention_bf16_small(ad, oracle_mod, name, n_sel, t_q):
+    """A few shots (several 64-key tiles plus a ragged tail), ragged row tiles, g = 4, 7 and 8."""
+    w = wl.WORKLOADS[name]
+    _attention_case(ad, oracle_mod, w, n_sel, t_q)
+
+
+def test_attention_bf16_no_context_prefix_and_shift(ad, oracle_mod):
+    w = wl.WORKLOADS["llama8b_1layer"]
+    _attention_case(ad, oracle_mod, w, 4, 70, n_ctx=0, q_pos0=0)           # causal self part only
+    _attention_case(ad, oracle_mod, w, 6, 33, n_ctx=129)                    # prefix of the cache
+    _attention_case(ad, oracle_mod, w, 6, 33, pos0=90000)                   # far positions
+
+
+def test_attention_bf16_needle(ad, oracle_mod):
+    w = wl.WORKLOADS["llama8b_1layer"]
+
+    def mutate(cache, q, ks, vs, q_pos0):
+        for j, slot in ((0, 200), (5, 3)):
+            qr = oracle_mod.rot(q[j, 2].double().cpu().numpy(), w.rope_theta, q_pos0 + j)
+            cache.k[0, slot, 0, :] = torch.from_numpy(50.0 * qr / np.linalg.norm(qr)).to(cache.k.dtype).cuda()
+
+    (_, _), got, ref = _attention_case(ad, oracle_mod, w, 8, 8, mutate=mutate)
+    assert np.abs(ref).max() > 0.5
+
+
+def test_attention_bf16_zero_keys_mean_of_values(ad, oracle_mod):
+    """K = 0 everywhere: every visible key gets the same weight, so O is the mean of the visible V rows
+    (closed form, independent of the oracle) -- checks the causal counts n_ctx + j + 1."""
+    w = wl.WORKLOADS["llama8b_1layer"]
+
+    def mutate(cache, q, ks, vs, q_pos0):
+        cache.k.zero_(); ks.zero_()
+        mutate.v = cache.v[0, :cache.len].double().cpu().numpy(); mutate.vs = vs.double().cpu().numpy()
+
+    (_, _), got, ref = _attention_case(ad, oracle_mod, w, 5, 21, mutate=mutate)
+    n_ctx = mutate.v.shape[0]
+    for j in (0, 7, 20):
+        for h in (0, 13, 31):
+            want = (mutate.v[:, h // 4].sum(0) + mutate.vs[: j + 1, h // 4].sum(0)) / (n_ctx + j + 1)
+            assert np.abs(got[j, h] - want).max() < 2e-3
+
+
+def test_attention_llama8b_bf16_full(ad, oracle_mod):
+    """Config 2 at full size: 128 query tokens x 32 heads over ~26k assembled tokens, every output checked."""
+    w = wl.WORKLOADS["llama8b_1layer"]
+    (mx, fro), got, ref = _attention_case(ad, oracle_mod, w, w.m_select, w.t_q)
+    assert np.linalg.norm(ref) > 0
