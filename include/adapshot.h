@@ -140,6 +140,23 @@ adapshot_status adapshot_probe_entropy(adapshot_ctx* ctx, const float* logits, i
                                        int32_t n_rows, int32_t vocab, float* entropy_out,
                                        void* hip_stream);
 
+/* Measurement aid (not a step of the method).  While enabled, every kernel the context
+ * launches is bracketed by two HIP events on the launch stream.  adapshot_profile_read
+ * waits for the recorded launches of one kernel kind, returns their summed duration in
+ * milliseconds and their count, and forgets them.  Event records cost a few microseconds
+ * per launch, so whole-path throughput is measured with profiling off. */
+typedef enum {
+    ADAPSHOT_KERNEL_ASSEMBLE = 0,       /* fused gather + re-encode */
+    ADAPSHOT_KERNEL_ROPE_ROWS = 1,      /* rotation of the query rows and their own keys */
+    ADAPSHOT_KERNEL_ATTN = 2,           /* split-K attention proper */
+    ADAPSHOT_KERNEL_ATTN_COMBINE = 3,   /* merge of the split partials */
+    ADAPSHOT_KERNEL_ENTROPY_CHUNK = 4,  /* vocabulary pass */
+    ADAPSHOT_KERNEL_ENTROPY_FINISH = 5, /* merge of the chunk partials */
+    ADAPSHOT_KERNEL_KINDS = 6
+} adapshot_kernel_kind;
+adapshot_status adapshot_profile_enable(adapshot_ctx* ctx, int32_t enable);
+adapshot_status adapshot_profile_read(adapshot_ctx* ctx, int32_t kind, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

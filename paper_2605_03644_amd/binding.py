@@ -15,7 +15,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libadapshot.so")
+LIB_PATH = os.environ.get("ADAPSHOT_LIB", os.path.join(_HERE, "libadapshot.so"))
 
 OK, EINVAL, ESHOT, ECAPACITY, ESTATE, EDEVICE = range(6)
 STATUS_NAMES = {OK: "OK", EINVAL: "EINVAL", ESHOT: "ESHOT", ECAPACITY: "ECAPACITY", ESTATE: "ESTATE",
@@ -25,7 +25,9 @@ KEYS_UNROTATED, KEYS_ROTATED_LOCAL = 0, 1
 
 # every symbol declared in include/adapshot.h
 EXPORTS = ["adapshot_create", "adapshot_destroy", "adapshot_last_error", "adapshot_version",
-           "adapshot_pool_register", "adapshot_assemble", "adapshot_query_attn", "adapshot_probe_entropy"]
+           "adapshot_pool_register", "adapshot_assemble", "adapshot_query_attn", "adapshot_probe_entropy",
+           "adapshot_profile_enable", "adapshot_profile_read"]
+KERNEL_KINDS = ["assemble_reencode", "rope_rows", "query_attn", "attn_combine", "entropy_chunk", "entropy_finish"]
 
 
 class ModelDesc(ctypes.Structure):
@@ -75,6 +77,10 @@ def load_library() -> ctypes.CDLL:
     L.adapshot_query_attn.argtypes = [vp, ctypes.POINTER(CacheStruct), i32, i64, vp, vp, vp, i32, i64, vp, vp]
     L.adapshot_probe_entropy.restype = ctypes.c_int
     L.adapshot_probe_entropy.argtypes = [vp, vp, i64, i32, i32, vp, vp]
+    L.adapshot_profile_enable.restype = ctypes.c_int
+    L.adapshot_profile_enable.argtypes = [vp, i32]
+    L.adapshot_profile_read.restype = ctypes.c_int
+    L.adapshot_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
     _lib = L
     return L
 
@@ -194,4 +200,17 @@ class Context:
             out = torch.empty(rows, dtype=torch.float32, device=logits.device)
         self._check(self.lib.adapshot_probe_entropy(self._h, logits.data_ptr(), logits.stride(0) if rows > 1 else vocab,
                                                     rows, vocab, out.data_ptr(), _stream_ptr(stream)))
+        return out
+
+    # -- adapshot_profile_enable / adapshot_profile_read
+    def profile_enable(self, on: bool) -> None:
+        self._check(self.lib.adapshot_profile_enable(self._h, 1 if on else 0))
+
+    def profile_read(self) -> dict:
+        """{kernel kind: (total_ms, launches)} of the launches recorded since the last read."""
+        out = {}
+        for kind, name in enumerate(KERNEL_KINDS):
+            ms, n = ctypes.c_double(), ctypes.c_int64()
+            self._check(self.lib.adapshot_profile_read(self._h, kind, ctypes.byref(ms), ctypes.byref(n)))
+            out[name] = (ms.value, n.value)
         return out

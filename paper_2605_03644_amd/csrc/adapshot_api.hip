@@ -87,7 +87,50 @@ void PinnedRing::release() {
     }
 }
 
+hipError_t Profiler::begin(int kind, hipStream_t stream) {
+    if (!on) return hipSuccess;
+    Rec r;
+    r.kind = kind;
+    hipEvent_t* ev[2] = {&r.start, &r.stop};
+    for (auto e : ev) {
+        if (!free_events.empty()) {
+            *e = free_events.back();
+            free_events.pop_back();
+        } else {
+            hipError_t err = hipEventCreate(e);
+            if (err != hipSuccess) return err;
+        }
+    }
+    recs.push_back(r);
+    return hipEventRecord(r.start, stream);
+}
+
+hipError_t Profiler::end(hipStream_t stream) {
+    if (!on || recs.empty()) return hipSuccess;
+    return hipEventRecord(recs.back().stop, stream);
+}
+
+void Profiler::release() {
+    for (auto& r : recs) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    for (auto e : free_events) (void)hipEventDestroy(e);
+    recs.clear();
+    free_events.clear();
+}
+
 }  // namespace adapshot
+
+// Launch one kernel, bracketed by timing events when profiling is on.
+template <typename F>
+static hipError_t timed_launch(adapshot_ctx* ctx, int kind, hipStream_t stream, F&& launch) {
+    hipError_t e = ctx->prof.begin(kind, stream);
+    if (e != hipSuccess) return e;
+    e = launch();
+    if (e != hipSuccess) return e;
+    return ctx->prof.end(stream);
+}
 
 static adapshot_status fail(adapshot_ctx* ctx, adapshot_status st, const char* fmt, ...) {
     if (ctx) {
@@ -187,6 +230,7 @@ extern "C" adapshot_status adapshot_create(const adapshot_model_desc* desc, adap
 extern "C" void adapshot_destroy(adapshot_ctx* ctx) {
     if (!ctx) return;
     (void)hipDeviceSynchronize();
+    ctx->prof.release();
     ctx->tile_ring.release();
     ctx->q_rot.release();
     ctx->k_rot.release();
@@ -310,7 +354,7 @@ extern "C" adapshot_status adapshot_assemble(adapshot_ctx* ctx, adapshot_cache* 
     p.n_kv_heads = ctx->desc.n_kv_heads;
     p.head_dim = ctx->desc.head_dim;
     p.dtype = ctx->desc.dtype;
-    e = launch_assemble(p, stream);
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ASSEMBLE, stream, [&] { return launch_assemble(p, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "assemble: launch", e);
     e = ctx->tile_ring.mark_in_use(slot, stream);
     if (e != hipSuccess) return fail_hip(ctx, "assemble: event record", e);
@@ -344,19 +388,18 @@ extern "C" adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot
     const int64_t rows = (int64_t)t_q * g;
     const bool mfma = attn_mfma_supported(d);
 
-    // Split the context so that (kv heads x row tiles x splits) covers the chip about twice;
-    // keys per split is a multiple of the 64-key tile.
-    const int64_t row_tile = mfma ? 128 : 1;
-    const int64_t row_tiles = (rows + row_tile - 1) / row_tile;
-    const int64_t units = d.n_kv_heads * row_tiles * (mfma ? 1 : 1);
-    int64_t key_tiles = (n_ctx + 63) / 64;
+    // Split the context so that (kv heads x row tiles x splits) fills the chip: once for the MFMA
+    // kernel (one 8-wave workgroup per compute unit), several times for the one-wave generic kernel.
+    // Keys per split is a multiple of the 64-key tile.
+    const int64_t row_tile = mfma ? kAttnRowTile : 1;
+    const int64_t units = d.n_kv_heads * ((rows + row_tile - 1) / row_tile);
+    const int64_t key_tiles = (n_ctx + 63) / 64;
     int64_t n_split = 0, keys_per_split = 64;
     if (key_tiles > 0) {
-        int64_t target = mfma ? std::max<int64_t>(1, ((int64_t)ctx->n_cu * 2 + units - 1) / units)
-                              : std::max<int64_t>(1, ((int64_t)ctx->n_cu * 8 + units - 1) / units);
+        const int64_t want = (int64_t)ctx->n_cu * (mfma ? 1 : 8);
+        const int64_t target = std::max<int64_t>(1, want / units);
         n_split = std::min<int64_t>(std::min<int64_t>(target, key_tiles), 64);
-        int64_t tiles_per_split = (key_tiles + n_split - 1) / n_split;
-        keys_per_split = tiles_per_split * 64;
+        keys_per_split = ((key_tiles + n_split - 1) / n_split) * 64;
         n_split = (n_ctx + keys_per_split - 1) / keys_per_split;
     }
 
@@ -382,7 +425,7 @@ extern "C" adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot
     rp.head_dim = d.head_dim;
     rp.dtype = d.dtype;
     rp.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
-    e = launch_rope_rows(rp, stream);
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ROPE_ROWS, stream, [&] { return launch_rope_rows(rp, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "query_attn: rope launch", e);
 
     AttnParams ap;
@@ -403,9 +446,10 @@ extern "C" adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot
     ap.n_kv_heads = d.n_kv_heads;
     ap.head_dim = d.head_dim;
     ap.dtype = d.dtype;
-    e = mfma ? launch_attn_mfma(ap, stream) : launch_attn_generic(ap, stream);
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream,
+                     [&] { return mfma ? launch_attn_mfma(ap, stream) : launch_attn_generic(ap, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "query_attn: attention launch", e);
-    e = launch_attn_combine(ap, stream);
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(ap, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "query_attn: combine launch", e);
     ctx->last_error.clear();
     return ADAPSHOT_OK;
@@ -440,8 +484,44 @@ extern "C" adapshot_status adapshot_probe_entropy(adapshot_ctx* ctx, const float
     hipError_t e = ctx->ent_part.reserve((size_t)n_rows * p.n_chunks * 3 * sizeof(float));
     if (e != hipSuccess) return fail_hip(ctx, "probe_entropy: workspace", e);
     p.partials = (float*)ctx->ent_part.p;
-    e = launch_entropy(p, (hipStream_t)hip_stream);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ENTROPY_CHUNK, stream, [&] { return launch_entropy_chunk(p, stream); });
+    if (e == hipSuccess)
+        e = timed_launch(ctx, ADAPSHOT_KERNEL_ENTROPY_FINISH, stream, [&] { return launch_entropy_finish(p, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "probe_entropy: launch", e);
     ctx->last_error.clear();
+    return ADAPSHOT_OK;
+}
+
+extern "C" adapshot_status adapshot_profile_enable(adapshot_ctx* ctx, int32_t enable) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    ctx->prof.on = enable != 0;
+    return ADAPSHOT_OK;
+}
+
+extern "C" adapshot_status adapshot_profile_read(adapshot_ctx* ctx, int32_t kind, double* total_ms, int64_t* launches) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    if (kind < 0 || kind >= ADAPSHOT_KERNEL_KINDS || !total_ms || !launches)
+        return fail(ctx, ADAPSHOT_EINVAL, "profile_read: bad kind or null pointer");
+    double tot = 0.0;
+    int64_t n = 0;
+    std::vector<Profiler::Rec> keep;
+    for (auto& r : ctx->prof.recs) {
+        if (r.kind != kind) {
+            keep.push_back(r);
+            continue;
+        }
+        hipError_t e = hipEventSynchronize(r.stop);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.start, r.stop);
+        if (e != hipSuccess) return fail_hip(ctx, "profile_read", e);
+        tot += ms;
+        ++n;
+        ctx->prof.free_events.push_back(r.start);
+        ctx->prof.free_events.push_back(r.stop);
+    }
+    ctx->prof.recs.swap(keep);
+    *total_ms = tot;
+    *launches = n;
     return ADAPSHOT_OK;
 }

@@ -87,6 +87,7 @@ struct AttnParams {
     int32_t n_split;
     int32_t t_q, n_q_heads, n_kv_heads, head_dim, dtype;
 };
+constexpr int kAttnRowTile = 256;  // query rows per workgroup of the MFMA kernel
 hipError_t launch_attn_generic(const AttnParams& p, hipStream_t stream);
 hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream);
 bool attn_mfma_supported(const adapshot_model_desc& d);
@@ -100,7 +101,8 @@ struct EntropyParams {
     int64_t row_stride;
     int32_t n_rows, vocab, chunk, n_chunks;
 };
-hipError_t launch_entropy(const EntropyParams& p, hipStream_t stream);
+hipError_t launch_entropy_chunk(const EntropyParams& p, hipStream_t stream);
+hipError_t launch_entropy_finish(const EntropyParams& p, hipStream_t stream);
 
 // ---- host-side helpers -----------------------------------------------------------------
 struct DevBuf {
@@ -120,6 +122,20 @@ struct PinnedRing {
     // Returns a pinned buffer of at least `need` bytes that no enqueued kernel still reads.
     hipError_t acquire(size_t need, int* slot, void** ptr);
     hipError_t mark_in_use(int slot, hipStream_t stream);
+    void release();
+};
+
+// Optional per-kernel timing with HIP events on the launch stream (measurement aid).
+struct Profiler {
+    struct Rec {
+        int kind;
+        hipEvent_t start, stop;
+    };
+    bool on = false;
+    std::vector<Rec> recs;
+    std::vector<hipEvent_t> free_events;
+    hipError_t begin(int kind, hipStream_t stream);
+    hipError_t end(hipStream_t stream);
     void release();
 };
 
@@ -143,6 +159,7 @@ struct adapshot_ctx {
     // scratch
     adapshot::PinnedRing tile_ring;
     adapshot::DevBuf q_rot, k_rot, part_o, part_ml, ent_part;
+    adapshot::Profiler prof;
     int n_cu = 256;
     std::string last_error;
 };

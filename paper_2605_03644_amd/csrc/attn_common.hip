@@ -156,51 +156,65 @@ hipError_t launch_attn_generic(const AttnParams& p, hipStream_t stream) {
 }
 
 // ---- combine --------------------------------------------------------------------------------
-// One workgroup of 64 lanes per (kv head, row).  out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
-// The self split always holds at least one visible key, so the denominator is > 0.
+// out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s with M = max_s m_s.  A workgroup of 256 lanes
+// handles 8 (kv head, row) pairs: 32 lanes per pair, one float4 of the head dimension per lane and
+// step, all splits' loads independent of each other.  The self split always holds at least one
+// visible key, so the denominator is > 0.
 template <int DTYPE>
-__global__ __launch_bounds__(64) void attn_combine_kernel(AttnParams p) {
-    const int lane = threadIdx.x;
+__global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
     const int d = p.head_dim;
     const int g = p.n_q_heads / p.n_kv_heads;
     const int64_t rows = (int64_t)p.t_q * g;
-    const int hk = blockIdx.x / rows;
-    const int64_t row = blockIdx.x - (int64_t)hk * rows;
+    const int64_t n_pairs = rows * p.n_kv_heads;
+    const int64_t pair = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);
+    if (pair >= n_pairs) return;
+    const int c = threadIdx.x & 31;
+    const int hk = (int)(pair / rows);
+    const int64_t row = pair - (int64_t)hk * rows;
     const int j = (int)(row / g);
     const int h = hk * g + (int)(row - (int64_t)j * g);
     const int ns = p.n_split + 1;
+    const int64_t split_stride = (int64_t)p.n_kv_heads * rows;  // pairs per split
 
     float M = -INFINITY;
-    for (int s = 0; s < ns; ++s) M = fmaxf(M, p.part_ml[((int64_t)s * p.n_kv_heads + hk) * rows + row].x);
+    for (int s = 0; s < ns; ++s) M = fmaxf(M, p.part_ml[s * split_stride + pair].x);
     float L = 0.f;
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll 4
     for (int s = 0; s < ns; ++s) {
-        const int64_t pr = ((int64_t)s * p.n_kv_heads + hk) * rows + row;
+        const int64_t pr = s * split_stride + pair;
         const float2 ml = p.part_ml[pr];
-        const float w = exp2f(ml.x - M);
-        if (w == 0.f) continue;  // empty or negligible split; also skips uninitialised garbage times 0
+        const float w = exp2f(ml.x - M);  // empty split: m = -inf -> 0
         L += w * ml.y;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int e = lane + 64 * c;
-            if (e < d) acc[c] += w * p.part_o[pr * d + e];
+        for (int u = 0; u < 2; ++u) {
+            const int e = 4 * (c + 32 * u);
+            if (e < d) {
+                const f32x4 o = *(const f32x4*)(p.part_o + pr * d + e);
+                acc[u] += w * o;
+            }
         }
     }
     const float inv = 1.0f / L;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const int e = lane + 64 * c;
-        if (e < d) store_elem<DTYPE>(p.out, ((int64_t)j * p.n_q_heads + h) * d + e, acc[c] * inv);
+    for (int u = 0; u < 2; ++u) {
+        const int e = 4 * (c + 32 * u);
+        if (e < d) {
+            const int64_t o = ((int64_t)j * p.n_q_heads + h) * d + e;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) store_elem<DTYPE>(p.out, o + k, acc[u][k] * inv);
+        }
     }
 }
 
 hipError_t launch_attn_combine(const AttnParams& p, hipStream_t stream) {
     const int g = p.n_q_heads / p.n_kv_heads;
-    dim3 grid((unsigned)((int64_t)p.n_kv_heads * p.t_q * g));
+    const int64_t n_pairs = (int64_t)p.n_kv_heads * p.t_q * g;
+    dim3 grid((unsigned)((n_pairs + 7) / 8));
     if (p.dtype == ADAPSHOT_BF16)
-        hipLaunchKernelGGL(attn_combine_kernel<ADAPSHOT_BF16>, grid, dim3(64), 0, stream, p);
+        hipLaunchKernelGGL(attn_combine_kernel<ADAPSHOT_BF16>, grid, dim3(256), 0, stream, p);
     else
-        hipLaunchKernelGGL(attn_combine_kernel<ADAPSHOT_F32>, grid, dim3(64), 0, stream, p);
+        hipLaunchKernelGGL(attn_combine_kernel<ADAPSHOT_F32>, grid, dim3(256), 0, stream, p);
     return hipGetLastError();
 }
 

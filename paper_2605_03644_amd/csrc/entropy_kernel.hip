@@ -153,15 +153,17 @@ __global__ __launch_bounds__(64) void entropy_finish_kernel(EntropyParams p) {
     }
 }
 
-hipError_t launch_entropy(const EntropyParams& p, hipStream_t stream) {
+hipError_t launch_entropy_chunk(const EntropyParams& p, hipStream_t stream) {
     dim3 grid((unsigned)p.n_chunks, (unsigned)p.n_rows);
     const bool vec = (((uintptr_t)p.logits & 15u) == 0) && (p.row_stride % 4 == 0);
     if (vec)
         hipLaunchKernelGGL(entropy_chunk_kernel<true>, grid, dim3(256), 0, stream, p);
     else
         hipLaunchKernelGGL(entropy_chunk_kernel<false>, grid, dim3(256), 0, stream, p);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+hipError_t launch_entropy_finish(const EntropyParams& p, hipStream_t stream) {
     hipLaunchKernelGGL(entropy_finish_kernel, dim3((unsigned)p.n_rows), dim3(64), 0, stream, p);
     return hipGetLastError();
 }
