@@ -382,6 +382,9 @@ extern "C" adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot
         !aligned16(cache->v))
         return fail(ctx, ADAPSHOT_EINVAL, "query_attn: pointers must be 16-byte aligned");
 
+    if ((uint64_t)std::max<int64_t>(n_ctx, t_q) * (uint64_t)ctx->row_bytes > 0xffffffffull)
+        return fail(ctx, ADAPSHOT_EINVAL, "query_attn: context rows span more than 4 GiB per layer");
+
     hipStream_t stream = (hipStream_t)hip_stream;
     const adapshot_model_desc& d = ctx->desc;
     const int g = d.n_q_heads / d.n_kv_heads;
@@ -396,7 +399,8 @@ extern "C" adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot
     const int64_t key_tiles = (n_ctx + 63) / 64;
     int64_t n_split = 0, keys_per_split = 64;
     if (key_tiles > 0) {
-        const int64_t want = (int64_t)ctx->n_cu * (mfma ? 1 : 8);
+        // MFMA kernel: one workgroup per compute unit including the self-part workgroups (one per unit)
+        const int64_t want = mfma ? std::max<int64_t>(units, (int64_t)ctx->n_cu - units) : (int64_t)ctx->n_cu * 8;
         const int64_t target = std::max<int64_t>(1, want / units);
         n_split = std::min<int64_t>(std::min<int64_t>(target, key_tiles), 64);
         keys_per_split = ((key_tiles + n_split - 1) / n_split) * 64;

@@ -5,8 +5,9 @@
 // 1/sqrt(d) scale, folded with log2(e) into q by rope_rows, so p = 2^(s - m).
 //
 // Work decomposition: workgroup = (kv head, tile of 256 rows, split of the context);
-// 8 wavefronts, each owning 32 rows for the whole key loop.  The extra split index
-// n_split is the causal part over the query's own tokens.
+// 8 wavefronts (two per SIMD), each owning 32 rows for the whole key loop.  The extra split
+// index n_split is the causal part over the query's own tokens.  The host picks the split count
+// so that all workgroups, self parts included, fit the compute units in one round.
 //
 // Everything is computed TRANSPOSED so that a query row lives in one lane column:
 //   S^T = K . Q^T   A = K tile from LDS (16-byte reads), B = Q fragments held in registers;
@@ -17,7 +18,16 @@
 //                   from the row-major V tile in LDS with the transposing ds_read_b64_tr_b16.
 // The k-slot order of the second product is the key order the S^T registers already have:
 // slot 8*(l/32)+e of 16-key step ks  <->  key 16*ks + 8*(e/4) + 4*(l/32) + e%4.
-#include <stdio.h>
+//
+// The two wavefronts of a SIMD run the same three phases per 64-key tile -- S^T (matrix core),
+// softmax (VALU), O^T accumulation (matrix core) -- but rotated against each other: wavefronts 0-3 go
+// S(t), softmax(t), PV(t); wavefronts 4-7 go PV(t-1), S(t), softmax(t).  While one of them runs
+// its exponentials the other one feeds the matrix core, with one workgroup barrier per tile.
+//
+// K/V tiles go from global memory straight into LDS (global_load_lds, 16 bytes per lane), four
+// tiles deep for K and for V, with an XOR swizzle of the 16-byte chunks instead of row padding:
+//   K row r keeps chunk c at position c ^ (r & 15)      (16 rows of a 16-byte read: 16 bank groups)
+//   V row r keeps chunk c at position c ^ ((r & 3) << 2) (4 rows x 64 B of a transposing read: 64 banks)
 
 #include "adapshot_internal.h"
 
@@ -32,85 +42,91 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kD = 128;             // head_dim
+constexpr int kD = 128;  // head_dim
 constexpr int kTileKeys = 64;
-constexpr int kKStride = 272;       // bytes per K row in LDS: 256 + 16 (16-byte reads of 16 rows hit 16 bank groups)
-constexpr int kVStride = 320;       // bytes per V row in LDS: 4 rows x 64 B of a transposing read tile all 64 banks
-constexpr int kKBytes = kTileKeys * kKStride;
-constexpr int kVBytes = kTileKeys * kVStride;
+constexpr int kRowBytes = kD * 2;
+constexpr int kTileBytes = kTileKeys * kRowBytes;  // 16 KB, no padding
+constexpr int kNBuf = 4;                           // tiles in LDS per operand
+constexpr int kAttnWaves = 8;                      // wavefronts per workgroup, two per SIMD, 32 rows each
+constexpr int kPD = 4;                             // LDS fragment reads in flight ahead of the MFMAs
+
+// s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
+constexpr int kWaitVm0 = 0x0f70;  // vmcnt(0), other counters untouched
 
 bool attn_mfma_supported(const adapshot_model_desc& d) { return d.dtype == ADAPSHOT_BF16 && d.head_dim == kD; }
 
-__device__ __forceinline__ float xchg32(float v) {
-    // value held by lane ^ 32
-    return __shfl_xor(v, 32, 64);
+// max / sum over the two lanes l and l^32 without going through LDS
+__device__ __forceinline__ float max_xhalf(float v) {
+    const unsigned u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_xhalf(float v) {
+    const unsigned u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 __device__ __forceinline__ unsigned pack2_bf16(float lo, float hi) {
     f32x2 f = {lo, hi};
-    bf16x2 b = __builtin_convertvector(f, bf16x2);
+    bf16x2 b = __builtin_convertvector(f, bf16x2);  // v_cvt_pk_bf16_f32, round to nearest even
     return __builtin_bit_cast(unsigned, b);
 }
 
-// ---- LDS fragment reads --------------------------------------------------------------------
-// K fragment (A operand of S^T): key row 32*kb + l32, 16 bytes at d = 16*kk + 8*hh.
-__device__ __forceinline__ bf16x8 k_frag(const char* kt, int l32, int hh, int kb, int kk) {
-    const u32x4 w = *(const u32x4*)(kt + (32 * kb + l32) * kKStride + 32 * kk + 16 * hh);
-    return __builtin_bit_cast(bf16x8, w);
-}
-// V^T fragment (A operand of O^T): two transposing reads.  In a 16-lane group, lane i addresses row
-// kbase + i/4, 4 columns at dbase + 4*(i%4), and receives column dbase + i of rows kbase .. kbase+3.
-__device__ __forceinline__ bf16x8 v_frag(const char* vt, int lane, int hh, int ks, int db) {
-#ifdef ADAPSHOT_EXPERIMENT_VT
-    const u32x4 w = *(const u32x4*)(vt + ks * 4096 + (32 * db + (lane & 31)) * 32 + hh * 16);
-    return __builtin_bit_cast(bf16x8, w);
-#endif
-    const int i16 = lane & 15;
-    const int krow = 16 * ks + 4 * hh + (i16 >> 2);
-    const int dcol = 32 * db + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
-    const char* va = vt + krow * kVStride + dcol * 2;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(va));
-    const s16x4 hi =
-        __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(va + 8 * kVStride));
-    const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, av);
+// max of three in one instruction.  fmaxf() chains compile to twice as many instructions because every
+// input is first canonicalised; the scores here are MFMA outputs or -inf, never signalling NaNs.
+__device__ __forceinline__ float max3(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
 }
 
-// 8 wavefronts of 32 rows each, two per SIMD, run as two groups (waves 0-3 and 4-7) that are kept
-// one phase apart: a wave alternates an MFMA phase M_t = { O^T += V^T P^T of tile t-1 ; S^T of tile t }
-// with a softmax phase V_t on the VALU, with a workgroup barrier after every phase, and group B
-// starts one barrier late -- so while one wave of a SIMD feeds the matrix core the other one runs
-// its exponentials.  K and V tiles are double buffered in LDS; M_t also moves K(t+1) and V(t) from
-// registers into LDS and starts the global loads of K(t+2) and V(t+1).
-#ifdef ADAPSHOT_EXPERIMENT_TIMING
-#define TSTAMP(slot)                                                                      \
-    do {                                                                                  \
-        if (blockIdx.x == 40 && lane == 0 && (wave == 0 || wave == 4) && (slot) < 256)     \
-            dbg[(wave ? 256 : 0) + (slot)] = __builtin_readcyclecounter();                \
-    } while (0)
-#else
-#define TSTAMP(slot)
-#endif
+// 16 bytes per lane from global memory straight into LDS: lane l's data lands at lds_base + 16*l
+// (lds_base is wave-uniform and goes through M0; the source is a uniform base plus a 32-bit lane offset).
+// Issued as inline assembly so that the key loop keeps control of the wait counters: the loads complete
+// in order and are awaited with vmcnt in barrier_keep_one_group(), tiles after they were issued.
+__device__ __forceinline__ void load_lds_16(const char* gbase, unsigned goff, unsigned lds_base) {
+    unsigned saved_m0;
+    asm volatile(
+        "s_mov_b32 %0, m0\n\t"
+        "s_mov_b32 m0, %3\n\t"
+        "global_load_lds_dwordx4 %1, %2\n\t"
+        "s_mov_b32 m0, %0"
+        : "=&s"(saved_m0)
+        : "v"(goff), "s"(gbase), "s"(lds_base)
+        : "memory");
+}
+__device__ __forceinline__ unsigned lds_addr(const void* p) {
+    return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
 
-template <int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int n_row_tiles
-#ifdef ADAPSHOT_EXPERIMENT_TIMING
-                                                               , unsigned long long* dbg
-#endif
-) {
-    constexpr int THREADS = WAVES * 64;
-    constexpr int PASSES = (kTileKeys * 16) / THREADS;  // 16-byte chunks of a tile per thread
-    static_assert(PASSES * THREADS == kTileKeys * 16, "tile must divide over the threads");
-    __shared__ __attribute__((aligned(16))) char k_s[2][kKBytes];
-    __shared__ __attribute__((aligned(16))) char v_s[2][kVBytes];
+// Workgroup barrier of the key loop.  __syncthreads() would drain every tile load still in flight
+// (they write LDS); here only the group issued two tiles ago must have landed (the younger
+// group stays outstanding), this wave's own LDS reads must be complete, and the
+// compiler may not move memory operations across.
+template <int LOADS_PER_GROUP>
+__device__ __forceinline__ void barrier_keep_one_group() {
+    static_assert(LOADS_PER_GROUP == 4 || LOADS_PER_GROUP == 8, "vmcnt immediate");
+    if (LOADS_PER_GROUP == 4)
+        asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// WAVES wavefronts, each owning NR blocks of 32 rows for the whole key loop.
+template <int WAVES, int NR>
+__global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int n_row_tiles) {
+    constexpr int PASSES = (kTileKeys * 16) / (WAVES * 64);  // 1 KB blocks of a tile per wavefront
+    static_assert(PASSES * WAVES * 64 == kTileKeys * 16, "tile must divide over the threads");
+    static_assert(WAVES * NR * 32 == kAttnRowTile && NR == 1, "row tile");
+    __shared__ __attribute__((aligned(65536))) char k_s[kNBuf][kTileBytes];
+    __shared__ __attribute__((aligned(65536))) char v_s[kNBuf][kTileBytes];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31;
     const int hh = lane >> 5;
-    TSTAMP(240);
-    const bool group_b = wave >= WAVES / 2;
 
     // blockIdx.x -> (kv head fastest: workgroups round-robin over the 8 XCDs, so with 8 kv heads every
     // XCD's L2 sees the K/V of one head only), row tile, split
@@ -122,32 +138,134 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int
 
     const int g = p.n_q_heads / p.n_kv_heads;
     const int rows = p.t_q * g;
-    const int row = row_tile * (32 * WAVES) + wave * 32 + l32;
-    const bool row_valid = row < rows;
-    const int jrow = row_valid ? row / g : 0x7fffffff;
+    int row[NR], jrow[NR];
+#pragma unroll
+    for (int rb = 0; rb < NR; ++rb) {
+        row[rb] = row_tile * kAttnRowTile + (wave * NR + rb) * 32 + l32;
+        jrow[rb] = row[rb] < rows ? row[rb] / g : 0x7fffffff;
+    }
+
+    // ---- key range of this split
+    const char* kbase = (const char*)(self ? p.k_self_rot : p.k_cache) + hk * kRowBytes;
+    const char* vbase = (const char*)(self ? p.v_self : p.v_cache) + hk * kRowBytes;
+    const int64_t kv_stride = (int64_t)p.n_kv_heads * kRowBytes;
+    const int64_t k0 = self ? 0 : (int64_t)split * p.keys_per_split;
+    const int64_t k1 = self ? (int64_t)p.t_q : (k0 + p.keys_per_split < p.n_ctx ? k0 + p.keys_per_split : p.n_ctx);
+    const int n_tiles = (int)((k1 - k0 + kTileKeys - 1) / kTileKeys);  // >= 1
+
+    // ---- tile loads: wavefront w moves the 1 KB blocks (4 rows) w, w+WAVES, ...; lane = (row in block, chunk).
+    // Every lane keeps the byte offset of its chunk in the next K and V tile and advances it by one tile
+    // per load.  The last tile (whose rows may run past the end of the split) and the tiles past the end
+    // (loaded anyway so that the number of loads in flight stays the same in every iteration; they land
+    // in buffers nobody reads any more) take their offsets with the row clamped to the last valid key.
+    const unsigned tile_step = (unsigned)(kTileKeys * kv_stride);
+    unsigned k_goff[PASSES], v_goff[PASSES];  // offsets from kbase / vbase of this lane's chunks in the next tile
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) {
+        const int r = 4 * (ps * WAVES + wave) + (lane >> 4);
+        const unsigned row_off = (unsigned)((k0 + r) * kv_stride);
+        k_goff[ps] = row_off + (((lane & 15) ^ (r & 15)) << 4);
+        v_goff[ps] = row_off + (((lane & 15) ^ ((r & 3) << 2)) << 4);
+    }
+    auto clamped_off = [&](int ps, bool is_v) __attribute__((always_inline)) -> unsigned {
+        const int r = 4 * (ps * WAVES + wave) + (lane >> 4);
+        int64_t key = k0 + (int64_t)(n_tiles - 1) * kTileKeys + r;
+        key = key < k1 ? key : k1 - 1;
+        const unsigned sw = is_v ? ((lane & 15) ^ ((r & 3) << 2)) : ((lane & 15) ^ (r & 15));
+        return (unsigned)(key * kv_stride) + (sw << 4);
+    };
+    int next_k_tile = 0, next_v_tile = 0;
+    auto issue_k = [&](int buf) __attribute__((always_inline)) {
+        if (next_k_tile >= n_tiles - 1) {
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps)
+                load_lds_16(kbase, clamped_off(ps, false),
+                            __builtin_amdgcn_readfirstlane(lds_addr(k_s[buf] + (ps * WAVES + wave) * 1024)));
+        } else {
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps) {
+                load_lds_16(kbase, k_goff[ps],
+                            __builtin_amdgcn_readfirstlane(lds_addr(k_s[buf] + (ps * WAVES + wave) * 1024)));
+                k_goff[ps] += tile_step;
+            }
+        }
+        ++next_k_tile;
+    };
+    auto issue_v = [&](int buf) __attribute__((always_inline)) {
+        if (next_v_tile >= n_tiles - 1) {
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps)
+                load_lds_16(vbase, clamped_off(ps, true),
+                            __builtin_amdgcn_readfirstlane(lds_addr(v_s[buf] + (ps * WAVES + wave) * 1024)));
+        } else {
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps) {
+                load_lds_16(vbase, v_goff[ps],
+                            __builtin_amdgcn_readfirstlane(lds_addr(v_s[buf] + (ps * WAVES + wave) * 1024)));
+                v_goff[ps] += tile_step;
+            }
+        }
+        ++next_v_tile;
+    };
+    // K(0..3) and V(0..2) start now
+    for (int t = 0; t < 4; ++t) issue_k(t);
+    for (int t = 0; t < 3; ++t) issue_v(t);
 
     // ---- Q fragments (B operand): lane holds row l32, d = 16*kk + 8*hh .. +7
     bf16x8 qf[8];
     {
-        const int j = row_valid ? jrow : 0;
-        const int gq = row_valid ? row - j * g : 0;
+        const bool valid = row[0] < rows;
+        const int j = valid ? jrow[0] : 0;
+        const int gq = valid ? row[0] - j * g : 0;
         const char* qrow = (const char*)p.q_rot + ((int64_t)(j * p.n_q_heads + hk * g + gq) * kD) * 2;
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
             u32x4 w = {0u, 0u, 0u, 0u};
-            if (row_valid) w = *(const u32x4*)(qrow + (16 * kk + 8 * hh) * 2);
+            if (valid) w = *(const u32x4*)(qrow + (16 * kk + 8 * hh) * 2);
             qf[kk] = __builtin_bit_cast(bf16x8, w);
         }
     }
 
-    TSTAMP(241);
-    // ---- key range of this split
-    const char* kbase = (const char*)(self ? p.k_self_rot : p.k_cache) + hk * (kD * 2);
-    const char* vbase = (const char*)(self ? p.v_self : p.v_cache) + hk * (kD * 2);
-    const int64_t kv_stride = (int64_t)p.n_kv_heads * (kD * 2);
-    const int64_t k0 = self ? 0 : (int64_t)split * p.keys_per_split;
-    const int64_t k1 = self ? (int64_t)p.t_q : (k0 + p.keys_per_split < p.n_ctx ? k0 + p.keys_per_split : p.n_ctx);
-    const int n_tiles = (int)((k1 - k0 + kTileKeys - 1) / kTileKeys);  // >= 1
+    // ---- per-lane LDS read addresses.  The K tiles occupy LDS bytes [0, 64K) and the V tiles
+    // [64K, 128K), four 16 KB buffers each; an address moves to the next buffer by +16K modulo 64K.
+    // K fragment kk of key block kb: row 32*kb + l32, chunk (2*kk + hh) ^ (l32 & 15)
+    unsigned ka[8];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+        ka[kk] = lds_addr(&k_s[0][0]) + (unsigned)(l32 * kRowBytes + (((2 * kk + hh) ^ (l32 & 15)) << 4));
+    // V^T fragment (db, ks): two transposing reads.  In a 16-lane group, lane i addresses row
+    // kbase + i/4, 8 bytes at element column dbase + 4*(i%4), and receives column dbase + i of rows
+    // kbase .. kbase+3.  Row = 16*ks + 4*hh + i/4 (+8), so (row & 3) = i/4.
+    unsigned va[4];
+    {
+        const int i16 = lane & 15;
+        const int r3 = i16 >> 2;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+            va[db] = lds_addr(&v_s[0][0]) + (unsigned)((4 * hh + r3) * kRowBytes + ((db ^ r3) << 6) +
+                                                       (((lane >> 4) & 1) << 5) + ((i16 & 3) << 3));
+    }
+    const unsigned k_region = lds_addr(&k_s[0][0]), v_region = lds_addr(&v_s[0][0]);
+    auto next_k_buffer = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) ka[kk] = k_region | ((ka[kk] - k_region + kTileBytes) & (kNBuf * kTileBytes - 1));
+    };
+    auto next_v_buffer = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int db = 0; db < 4; ++db) va[db] = v_region | ((va[db] - v_region + kTileBytes) & (kNBuf * kTileBytes - 1));
+    };
+    auto k_frag = [&](int kb, int kk) __attribute__((always_inline)) -> bf16x8 {
+        const u32x4 w = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(ka[kk] + kb * (32 * kRowBytes));
+        return __builtin_bit_cast(bf16x8, w);
+    };
+    auto v_frag = [&](int ks, int db) __attribute__((always_inline)) -> bf16x8 {
+        const unsigned a = va[db] + ks * (16 * kRowBytes);
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)a);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(uintptr_t)(a + 8 * kRowBytes));
+        const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, av);
+    };
 
     f32x16 o[4];
 #pragma unroll
@@ -156,56 +274,52 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int
         for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
     float m_run = -INFINITY;  // reference maximum of the exponentials (log2 units); may lag the true maximum by < 8
     float l_run = 0.f;        // this lane's share of the row sum
+    f32x16 s[2];              // S^T of the current tile, key blocks 0 and 1
+    u32x4 pb[4];              // P^T of the current tile (packed bf16), one B operand per 16-key step
 
-    // ---- global -> register -> LDS staging of 64-key tiles (rows clamped to the last valid key)
-    u32x4 kreg[PASSES], vreg[PASSES];
-    auto gload = [&](const char* base, int t, u32x4(&reg)[PASSES]) {
+    // S^T(t) = K(t) . Q^T from the buffer ka points at: 16 MFMAs, fragments read kPD steps ahead
+    auto s_phase = [&]() __attribute__((always_inline)) {
+        bf16x8 fr[kPD];
 #pragma unroll
-        for (int ps = 0; ps < PASSES; ++ps) {
-            const int c = ps * THREADS + tid;
-            int64_t key = k0 + (int64_t)t * kTileKeys + (c >> 4);
-            key = key < k1 ? key : k1 - 1;
-            reg[ps] = *(const u32x4*)(base + key * kv_stride + (c & 15) * 16);
+        for (int i = 0; i < kPD; ++i) fr[i] = k_frag(i & 1, i >> 1);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {  // kk = i/2, kb = i%2
+            const bf16x8 a = fr[i % kPD];
+            if (i + kPD < 16) fr[i % kPD] = k_frag((i + kPD) & 1, (i + kPD) >> 1);
+            if (i < 2) {
+                const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0], zero, 0, 0, 0);
+            } else {
+                s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[i >> 1], s[i & 1], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, kPD, 0);  // the first kPD fragment reads, then MFMA / read pairs
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i + kPD < 16) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
     };
-    auto stage = [&](char* buf, int stride, const u32x4(&reg)[PASSES]) {
+    // O^T += V^T . P^T from the buffer va points at: 16 MFMAs, 2 transposing reads per fragment
+    auto pv_phase = [&]() __attribute__((always_inline)) {
+        bf16x8 fr[kPD];
 #pragma unroll
-        for (int ps = 0; ps < PASSES; ++ps) {
-            const int c = ps * THREADS + tid;
-            *(u32x4*)(buf + (c >> 4) * stride + (c & 15) * 16) = reg[ps];
+        for (int i = 0; i < kPD; ++i) fr[i] = v_frag(i >> 2, i & 3);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {  // ks = i/4, db = i%4
+            const bf16x8 a = fr[i % kPD];
+            if (i + kPD < 16) fr[i % kPD] = v_frag((i + kPD) >> 2, (i + kPD) & 3);
+            o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, pb[i >> 2]), o[i & 3], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * kPD, 0);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i + kPD < 16) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
     };
-
-    gload(kbase, 0, kreg);
-    stage(k_s[0], kKStride, kreg);
-    gload(vbase, 0, vreg);
-    if (n_tiles > 1) gload(kbase, 1, kreg);
-    TSTAMP(242);
-    __syncthreads();
-    TSTAMP(243);
-    if (group_b) __syncthreads();  // group B runs one phase behind group A
-
-    f32x16 s[2];
-    bf16x8 pb[4];  // P^T of the previous tile, one B operand per 16-key step
-
-    // K(t+1) and V(t) move from registers to the buffers nobody reads in this or the next phase;
-    // then the loads of K(t+2) and V(t+1) start (two phases of latency cover)
-    auto stage_and_load = [&](int t) {
-        if (t + 1 < n_tiles) stage(k_s[(t + 1) & 1], kKStride, kreg);
-        stage(v_s[t & 1], kVStride, vreg);
-#ifndef ADAPSHOT_EXPERIMENT_NO_GLOAD
-        if (t + 2 < n_tiles) gload(kbase, t + 2, kreg);
-        if (t + 1 < n_tiles) gload(vbase, t + 1, vreg);
-#endif
-    };
-    auto zero_s = [&]() {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-    };
-    // V_t: masks and online softmax on the VALU; leaves P^T(t) in pb
-    auto softmax_phase = [&](int t) {
+    // masks + online softmax of tile t with a lazily updated reference maximum; leaves P^T(t) in pb
+    auto softmax_phase = [&](int t) __attribute__((always_inline)) {
         const int64_t tile_k0 = k0 + (int64_t)t * kTileKeys;
         if (self || tile_k0 + kTileKeys > k1) {
 #pragma unroll
@@ -213,14 +327,14 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int64_t key = tile_k0 + 32 * kb + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    const bool vis = key < k1 && (!self || key <= (int64_t)jrow);
+                    const bool vis = key < k1 && (!self || key <= (int64_t)jrow[0]);
                     if (!vis) s[kb][r] = -INFINITY;
                 }
         }
-        float mx = fmaxf(s[0][0], s[1][0]);
+        float mx = max3(s[0][0], s[1][0], s[0][1]);
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s[0][r], s[1][r]));
-        mx = fmaxf(mx, xchg32(mx));
+        for (int r = 1; r < 15; ++r) mx = max3(mx, s[1][r], s[0][r + 1]);
+        mx = max_xhalf(fmaxf(mx, s[1][15]));
         if (__builtin_amdgcn_ballot_w64(mx > m_run + 8.0f || (m_run == -INFINITY && mx > -INFINITY))) {
             const float m_new = fmaxf(m_run, mx);
             const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);
@@ -234,103 +348,60 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int
         const float m_use = m_run == -INFINITY ? 0.f : m_run;  // nothing visible yet: p = 2^(-inf) = 0
         float sum = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            u32x4 w;
+        for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float e0 = __builtin_amdgcn_exp2f(s[ks >> 1][8 * (ks & 1) + 2 * e] - m_use);
                 const float e1 = __builtin_amdgcn_exp2f(s[ks >> 1][8 * (ks & 1) + 2 * e + 1] - m_use);
                 sum += e0 + e1;
-                w[e] = pack2_bf16(e0, e1);
+                pb[ks][e] = pack2_bf16(e0, e1);
             }
-            pb[ks] = __builtin_bit_cast(bf16x8, w);
-        }
         l_run += sum;
     };
+    // End of tile t: K(t+1) and V(t+1) have landed (the younger group may stay in flight); the buffers of
+    // K(t) and V(t-1), which every wave has finished reading, are refilled with K(t+4) and V(t+3).
+    auto end_of_tile = [&](int t) __attribute__((always_inline)) {
+        barrier_keep_one_group<2 * PASSES>();
+        issue_k(t & 3);        // K(t+4)
+        issue_v((t + 3) & 3);  // V(t+3)
+    };
 
-    // =========================== M_0: S(0) only
-    {
-        const char* kt = k_s[0];
-        zero_s();
-        bf16x8 fr[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) fr[i] = k_frag(kt, l32, hh, i & 1, i >> 1);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const bf16x8 a = fr[i & 3];
-            if (i + 4 < 16) fr[i & 3] = k_frag(kt, l32, hh, (i + 4) & 1, (i + 4) >> 1);
-            s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[i >> 1], s[i & 1], 0, 0, 0);
+    // ---- prologue: everything issued so far has landed
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    __syncthreads();
+
+    if (wave < WAVES / 2) {
+        // order A: S(t), softmax(t), PV(t)
+        for (int t = 0; t < n_tiles; ++t) {
+            s_phase();
+            next_k_buffer();
+            softmax_phase(t);
+            pv_phase();
+            next_v_buffer();
+            end_of_tile(t);
         }
-        stage_and_load(0);
-        __syncthreads();
+    } else {
+        // order B: PV(t-1), S(t), softmax(t); the same number of barriers as order A
+        s_phase();
+        next_k_buffer();
         softmax_phase(0);
-        __syncthreads();
-    }
-    TSTAMP(0);
-
-    for (int t = 1; t < n_tiles; ++t) {
-        // =========================== M_t: PV(t-1) and S(t) on the matrix core: 32 MFMAs alternating the
-        // two products; operand fragments are read from LDS 4 steps ahead
-        const char* kt = k_s[t & 1];
-        const char* vt = v_s[(t + 1) & 1];  // tile t-1
-        {
-            f32x16 sn[2];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sn[kb][r] = 0.f;
-            bf16x8 fr[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                fr[i] = (i & 1) ? k_frag(kt, l32, hh, (i >> 1) & 1, i >> 2) : v_frag(vt, lane, hh, i >> 3, (i >> 1) & 3);
-#pragma unroll
-            for (int i = 0; i < 32; ++i) {
-                const int u = i >> 1;  // PV: ks = u/4, db = u%4;  S: kk = u/2, kb = u%2
-                const bf16x8 a = fr[i & 3];
-                if (i + 4 < 32) {
-                    const int n = i + 4, un = n >> 1;
-                    fr[i & 3] = (n & 1) ? k_frag(kt, l32, hh, un & 1, un >> 1) : v_frag(vt, lane, hh, un >> 2, un & 3);
-                }
-                if (i & 1)
-                    sn[u & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[u >> 1], sn[u & 1], 0, 0, 0);
-                else
-                    o[u & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[u >> 2], o[u & 3], 0, 0, 0);
-            }
-            s[0] = sn[0];
-            s[1] = sn[1];
+        end_of_tile(0);
+        for (int t = 1; t < n_tiles; ++t) {
+            pv_phase();
+            next_v_buffer();
+            s_phase();
+            next_k_buffer();
+            softmax_phase(t);
+            end_of_tile(t);
         }
-        TSTAMP(4 * t + 0);
-        stage_and_load(t);
-        TSTAMP(4 * t + 1);
-        __syncthreads();
-        TSTAMP(4 * t + 2);
-        softmax_phase(t);
-        TSTAMP(4 * t + 3);
-        __syncthreads();
-        TSTAMP(4 * t + 4);
+        pv_phase();
     }
-
-    // =========================== M_n: PV(n-1) only
-    {
-        const char* vt = v_s[(n_tiles + 1) & 1];
-        bf16x8 fr[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) fr[i] = v_frag(vt, lane, hh, i >> 2, i & 3);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const bf16x8 a = fr[i & 3];
-            if (i + 4 < 16) fr[i & 3] = v_frag(vt, lane, hh, (i + 4) >> 2, (i + 4) & 3);
-            o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[i >> 2], o[i & 3], 0, 0, 0);
-        }
-        __syncthreads();
-    }
-    TSTAMP(244);
-    if (!group_b) __syncthreads();  // every wave passes the same number of barriers
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);  // the loads of the tiles past the end must land before LDS is released
 
     // ---- partials: unnormalised O (row-major [row][d]), reference maximum and row sum
-    const float l_tot = l_run + xchg32(l_run);
-    if (row_valid) {
-        const int64_t pr = ((int64_t)split * p.n_kv_heads + hk) * rows + row;
+    const float l_tot = sum_xhalf(l_run);
+    if (row[0] < rows) {
+        const int64_t pr = ((int64_t)split * p.n_kv_heads + hk) * rows + row[0];
         if (hh == 0) p.part_ml[pr] = make_float2(m_run, l_tot);
         float* orow = p.part_o + pr * kD;
 #pragma unroll
@@ -341,10 +412,6 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int
                 *(f32x4*)(orow + 32 * db + 8 * rq + 4 * hh) = w;
             }
     }
-#ifdef ADAPSHOT_EXPERIMENT_TIMING
-    __builtin_amdgcn_s_waitcnt(0);
-#endif
-    TSTAMP(245);
 }
 
 hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream) {
@@ -352,29 +419,8 @@ hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream) {
     const int rows = p.t_q * g;
     const int n_row_tiles = (rows + kAttnRowTile - 1) / kAttnRowTile;
     const unsigned blocks = (unsigned)(p.n_kv_heads * n_row_tiles * (p.n_split + 1));
-#ifdef ADAPSHOT_EXPERIMENT_TIMING
-    static unsigned long long* dbg = nullptr;
-    if (!dbg) { (void)hipMalloc(&dbg, 512 * 8); (void)hipMemset(dbg, 0, 512 * 8); }
-    hipLaunchKernelGGL((attn_mfma_kernel<kAttnRowTile / 32>), dim3(blocks), dim3(kAttnRowTile * 2), 0, stream, p,
-                       n_row_tiles, dbg);
-    (void)hipDeviceSynchronize();
-    unsigned long long h[512];
-    (void)hipMemcpy(h, dbg, sizeof h, hipMemcpyDeviceToHost);
-    static int once = 0;
-    if (!once++) {
-        for (int w = 0; w < 2; ++w) {
-            printf("wave %d:", w * 4);
-            for (int i = 5; i < 14; ++i) printf(" %lld", (long long)(h[w * 256 + i] - h[w * 256 + 4]));
-            printf("\n  coarse: qload %lld  k0stage %lld  barrier %lld  loop %lld  epilogue %lld\n",
-                   (long long)(h[w * 256 + 241] - h[w * 256 + 240]), (long long)(h[w * 256 + 242] - h[w * 256 + 241]),
-                   (long long)(h[w * 256 + 243] - h[w * 256 + 242]), (long long)(h[w * 256 + 244] - h[w * 256 + 243]),
-                   (long long)(h[w * 256 + 245] - h[w * 256 + 244]));
-        }
-    }
-#else
-    hipLaunchKernelGGL((attn_mfma_kernel<kAttnRowTile / 32>), dim3(blocks), dim3(kAttnRowTile * 2), 0, stream, p,
-                       n_row_tiles);
-#endif
+    hipLaunchKernelGGL((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves)>), dim3(blocks),
+                       dim3(kAttnWaves * 64), 0, stream, p, n_row_tiles);
     return hipGetLastError();
 }
 
