@@ -132,6 +132,43 @@ adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot_cache* cac
                                     const void* v_self, int32_t t_q, int64_t q_pos0, void* out,
                                     void* hip_stream);
 
+/* Batched forms (several independent queries per call, e.g. the adaptive probe sweep over nested
+ * prefixes, or the queries of a decode batch).  Every item is validated before anything is launched:
+ * a call that returns an error has written nothing.
+ *
+ * adapshot_assemble_batched: cache b receives shot_ids[b][orders[b][j]], j = 0..m[b]-1, appended at
+ * caches[b].len, first position pos0 + caches[b].len.  shot_ids / orders / m are HOST arrays of n_caches
+ * entries (orders, or any orders[b], may be NULL).  The caches must be distinct buffers. */
+adapshot_status adapshot_assemble_batched(adapshot_ctx* ctx, adapshot_cache* caches, int32_t n_caches,
+                                          const int32_t* const* shot_ids, const int32_t* const* orders,
+                                          const int32_t* m, int64_t pos0, void* hip_stream);
+
+/* One attention problem of a batch: rows of q (t_q tokens at positions q_pos0 + j) over slots [0, n_ctx)
+ * of caches[cache_index] plus their own tokens, as in adapshot_query_attn.  Several items may use the
+ * same cache with different n_ctx: probes over nested prefixes (tree-structured multi-probe of the
+ * Probe-based Dynamic Evaluation section) need no re-assembly because a prefix keeps its positions. */
+typedef struct {
+    const void* q;       /* DEVICE [t_q][n_q_heads][head_dim] */
+    const void* k_self;  /* DEVICE [t_q][n_kv_heads][head_dim] */
+    const void* v_self;  /* DEVICE [t_q][n_kv_heads][head_dim] */
+    void* out;           /* DEVICE [t_q][n_q_heads][head_dim] */
+    int64_t n_ctx;
+    int64_t q_pos0;
+    int32_t t_q;
+    int32_t cache_index;
+} adapshot_attn_item;
+adapshot_status adapshot_query_attn_batched(adapshot_ctx* ctx, const adapshot_cache* caches, int32_t n_caches,
+                                            int32_t layer, const adapshot_attn_item* items, int32_t n_items,
+                                            void* hip_stream);
+
+/* Decode step (final answer generation after the shot count is chosen): append ONE new token to each
+ * cache.  k_new, v_new: DEVICE [n_layers][n_caches][n_kv_heads][head_dim], keys WITHOUT rotation (as the
+ * model produces them before RoPE, whatever desc.key_state says about the pool).  Token b lands in slot
+ * caches[b].len, its key rotated to position pos0 + caches[b].len (Eq. rope_encoding); slot_shot gets -1.
+ * On success every caches[b].len is advanced by one.  Errors: ECAPACITY if any cache is full. */
+adapshot_status adapshot_decode_append(adapshot_ctx* ctx, adapshot_cache* caches, int32_t n_caches,
+                                       const void* k_new, const void* v_new, int64_t pos0, void* hip_stream);
+
 /* Entropy of softmax(logits) per row, natural log (step 4; Eq. entropy taken over
  * the whole output vocabulary).  logits: DEVICE fp32, row r at logits + r*row_stride
  * (row_stride >= vocab, in elements); entropy_out: DEVICE fp32[n_rows].  A logit of

@@ -51,6 +51,8 @@ def lib() -> ctypes.CDLL:
         L.adapshot_oracle_plan.argtypes = [vp, i32, vp, vp, i32, i64, i64, vp, vp, vp, vp]
         L.adapshot_oracle_rot.restype = None
         L.adapshot_oracle_rot.argtypes = [vp, i32, f64, f64, vp]
+        L.adapshot_oracle_rot_rows.restype = None
+        L.adapshot_oracle_rot_rows.argtypes = [vp, ctypes.c_int, i64, i32, f64, vp, vp, vp]
         L.adapshot_oracle_assemble.restype = ctypes.c_int
         L.adapshot_oracle_assemble.argtypes = [vp, vp, ctypes.c_int, i32, i64, i32, i32, f64, ctypes.c_int,
                                                vp, vp, vp, i64, i64, vp, vp, i64, vp]
@@ -109,6 +111,21 @@ def rot(x: np.ndarray, base: float, a: float) -> np.ndarray:
     y = np.empty_like(x)
     lib().adapshot_oracle_rot(_p(x), x.shape[-1], float(base), float(a), _p(y))
     return y
+
+
+def rot_rows(x: np.ndarray, dtype: str, base: float, angles, want_exact: bool = False):
+    """x: [..., d] in storage type; angles: one angle multiplier per row.  Returns rows rotated and
+    rounded to the storage type (and the fp64 rows before rounding if want_exact)."""
+    x = _chk(x, _NP[dtype])
+    d = x.shape[-1]
+    n = x.size // d
+    a = _chk(np.ascontiguousarray(angles, dtype=np.float64).reshape(-1), np.float64)
+    if a.shape[0] != n:
+        raise ValueError("one angle per row expected")
+    y = np.empty_like(x)
+    ex = np.empty(x.shape, np.float64) if want_exact else None
+    lib().adapshot_oracle_rot_rows(_p(x), _DT[dtype], n, d, float(base), _p(a), _p(y), _p(ex))
+    return (y, ex) if want_exact else y
 
 
 def assemble(k_pool: np.ndarray, v_pool: np.ndarray, dtype: str, base: float, key_state: int,

@@ -27,6 +27,7 @@
  *                context plus their own tokens (causal).
  *   entropy   -- Eq. (entropy), H = -sum p log p, here over the whole vocabulary
  *                of one output distribution, natural log.
+ *   rot_rows  -- rot applied row by row with stored input/output (decode-step append).
  *
  * Parity pins for every function live in tests/test_oracle_*.py; none of the
  * functions below is "parity unpinned".
@@ -137,6 +138,25 @@ void adapshot_oracle_rot(const double* x, int32_t d, double base, double a, doub
         double x1 = x[i], x2 = x[i + h];
         y[i] = x1 * c + (-x2) * s;
         y[i + h] = x2 * c + x1 * s;
+    }
+}
+
+/* Rotate n_rows stored rows of length d, row r by angle multiplier a[r] (rot above), and store them
+ * rounded once to the storage type; y_exact (optional, fp64 [n_rows][d]) gets the unrounded rows.
+ * This is the decode-step append: a new token's key from the model, brought to its position
+ * (Eq. rope_encoding with p = position). */
+void adapshot_oracle_rot_rows(const void* x, int dtype, int64_t n_rows, int32_t d, double base,
+                              const double* a, void* y, double* y_exact) {
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < n_rows; ++r) {
+        double xi[1024], yo[1024];
+        if (d > 1024) continue;
+        for (int32_t e = 0; e < d; ++e) xi[e] = load_elem(x, dtype, r * d + e);
+        adapshot_oracle_rot(xi, d, base, a[r], yo);
+        for (int32_t e = 0; e < d; ++e) {
+            store_elem(y, dtype, r * d + e, yo[e]);
+            if (y_exact) y_exact[r * d + e] = yo[e];
+        }
     }
 }
 

@@ -26,7 +26,8 @@ KEYS_UNROTATED, KEYS_ROTATED_LOCAL = 0, 1
 # every symbol declared in include/adapshot.h
 EXPORTS = ["adapshot_create", "adapshot_destroy", "adapshot_last_error", "adapshot_version",
            "adapshot_pool_register", "adapshot_assemble", "adapshot_query_attn", "adapshot_probe_entropy",
-           "adapshot_profile_enable", "adapshot_profile_read"]
+           "adapshot_profile_enable", "adapshot_profile_read", "adapshot_assemble_batched",
+           "adapshot_query_attn_batched", "adapshot_decode_append"]
 KERNEL_KINDS = ["assemble_reencode", "rope_rows", "query_attn", "attn_combine", "entropy_chunk", "entropy_finish"]
 
 
@@ -40,6 +41,12 @@ class CacheStruct(ctypes.Structure):
     _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p), ("capacity", ctypes.c_int64),
                 ("len", ctypes.c_int64), ("slot_shot", ctypes.c_void_p), ("slot_tok", ctypes.c_void_p),
                 ("slot_pos", ctypes.c_void_p)]
+
+
+class AttnItem(ctypes.Structure):
+    _fields_ = [("q", ctypes.c_void_p), ("k_self", ctypes.c_void_p), ("v_self", ctypes.c_void_p),
+                ("out", ctypes.c_void_p), ("n_ctx", ctypes.c_int64), ("q_pos0", ctypes.c_int64),
+                ("t_q", ctypes.c_int32), ("cache_index", ctypes.c_int32)]
 
 
 class AdapshotError(RuntimeError):
@@ -77,6 +84,12 @@ def load_library() -> ctypes.CDLL:
     L.adapshot_query_attn.argtypes = [vp, ctypes.POINTER(CacheStruct), i32, i64, vp, vp, vp, i32, i64, vp, vp]
     L.adapshot_probe_entropy.restype = ctypes.c_int
     L.adapshot_probe_entropy.argtypes = [vp, vp, i64, i32, i32, vp, vp]
+    L.adapshot_assemble_batched.restype = ctypes.c_int
+    L.adapshot_assemble_batched.argtypes = [vp, ctypes.POINTER(CacheStruct), i32, vp, vp, vp, i64, vp]
+    L.adapshot_query_attn_batched.restype = ctypes.c_int
+    L.adapshot_query_attn_batched.argtypes = [vp, ctypes.POINTER(CacheStruct), i32, i32, ctypes.POINTER(AttnItem), i32, vp]
+    L.adapshot_decode_append.restype = ctypes.c_int
+    L.adapshot_decode_append.argtypes = [vp, ctypes.POINTER(CacheStruct), i32, vp, vp, i64, vp]
     L.adapshot_profile_enable.restype = ctypes.c_int
     L.adapshot_profile_enable.argtypes = [vp, i32]
     L.adapshot_profile_read.restype = ctypes.c_int
@@ -201,6 +214,57 @@ class Context:
         self._check(self.lib.adapshot_probe_entropy(self._h, logits.data_ptr(), logits.stride(0) if rows > 1 else vocab,
                                                     rows, vocab, out.data_ptr(), _stream_ptr(stream)))
         return out
+
+    # -- batched forms: the C structs of several caches are packed into one array for the call and the
+    #    advanced lengths are copied back
+    @staticmethod
+    def _pack_caches(caches):
+        arr = (CacheStruct * len(caches))()
+        for i, c in enumerate(caches):
+            arr[i] = c.c
+        return arr
+
+    @staticmethod
+    def _unpack_lens(caches, arr):
+        for i, c in enumerate(caches):
+            c.c.len = arr[i].len
+
+    # -- adapshot_assemble_batched
+    def assemble_batched(self, caches, shot_ids, orders=None, pos0: int = 0,
+                         stream: Optional[torch.cuda.Stream] = None) -> None:
+        n = len(caches)
+        ids = [np.ascontiguousarray(x, dtype=np.int32) for x in shot_ids]
+        ods = None if orders is None else [None if o is None else np.ascontiguousarray(o, dtype=np.int32) for o in orders]
+        id_ptrs = (ctypes.c_void_p * n)(*[x.ctypes.data for x in ids])
+        od_ptrs = None if ods is None else (ctypes.c_void_p * n)(*[None if o is None else o.ctypes.data for o in ods])
+        m = np.array([x.shape[0] for x in ids], dtype=np.int32)
+        arr = self._pack_caches(caches)
+        st = self.lib.adapshot_assemble_batched(self._h, arr, n, ctypes.cast(id_ptrs, ctypes.c_void_p),
+                                                None if od_ptrs is None else ctypes.cast(od_ptrs, ctypes.c_void_p),
+                                                m.ctypes.data, pos0, _stream_ptr(stream))
+        self._unpack_lens(caches, arr)
+        self._check(st)
+
+    # -- adapshot_query_attn_batched: items = [(cache_index, n_ctx, q, k_self, v_self, q_pos0, out)]
+    def query_attn_batched(self, caches, layer: int, items, stream: Optional[torch.cuda.Stream] = None) -> None:
+        arr = self._pack_caches(caches)
+        its = (AttnItem * len(items))()
+        for i, (ci, n_ctx, q, ks, vs, q_pos0, out) in enumerate(items):
+            assert q.is_contiguous() and ks.is_contiguous() and vs.is_contiguous() and out.is_contiguous()
+            its[i] = AttnItem(q.data_ptr(), ks.data_ptr(), vs.data_ptr(), out.data_ptr(), n_ctx, q_pos0, q.shape[0], ci)
+        self._check(self.lib.adapshot_query_attn_batched(self._h, arr, len(caches), layer, its, len(items),
+                                                         _stream_ptr(stream)))
+
+    # -- adapshot_decode_append: k_new, v_new [L, n_caches, H_kv, d]
+    def decode_append(self, caches, k_new: torch.Tensor, v_new: torch.Tensor, pos0: int = 0,
+                      stream: Optional[torch.cuda.Stream] = None) -> None:
+        assert k_new.is_contiguous() and v_new.is_contiguous() and k_new.shape == v_new.shape
+        assert k_new.shape[1] == len(caches)
+        arr = self._pack_caches(caches)
+        st = self.lib.adapshot_decode_append(self._h, arr, len(caches), k_new.data_ptr(), v_new.data_ptr(), pos0,
+                                             _stream_ptr(stream))
+        self._unpack_lens(caches, arr)
+        self._check(st)
 
     # -- adapshot_profile_enable / adapshot_profile_read
     def profile_enable(self, on: bool) -> None:

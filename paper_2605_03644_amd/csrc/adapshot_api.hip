@@ -268,9 +268,10 @@ extern "C" adapshot_status adapshot_pool_register(adapshot_ctx* ctx, const void*
     return ADAPSHOT_OK;
 }
 
-extern "C" adapshot_status adapshot_assemble(adapshot_ctx* ctx, adapshot_cache* cache, const int32_t* shot_ids,
-                                             const int32_t* order, int32_t m, int64_t pos0, void* hip_stream) {
-    if (!ctx) return ADAPSHOT_EINVAL;
+// Validation + integer plan totals of one assemble call; nothing is launched or written.
+static adapshot_status check_assemble(adapshot_ctx* ctx, const adapshot_cache* cache, const int32_t* shot_ids,
+                                      const int32_t* order, int32_t m, int64_t pos0, int64_t* total_out,
+                                      int64_t* n_tiles_out) {
     if (!cache) return fail(ctx, ADAPSHOT_EINVAL, "assemble: null cache");
     if (m < 0) return fail(ctx, ADAPSHOT_EINVAL, "assemble: m < 0");
     if (m > 0 && !shot_ids) return fail(ctx, ADAPSHOT_EINVAL, "assemble: null shot_ids");
@@ -281,8 +282,6 @@ extern "C" adapshot_status adapshot_assemble(adapshot_ctx* ctx, adapshot_cache* 
     if (cache->capacity < 0 || cache->capacity > INT32_MAX || cache->len < 0 || cache->len > cache->capacity)
         return fail(ctx, ADAPSHOT_EINVAL, "assemble: bad cache capacity/len");
     if (pos0 < 0) return fail(ctx, ADAPSHOT_EINVAL, "assemble: pos0 < 0");
-
-    // Pass 1 (integer plan): validate ids and total length before anything is written.
     int64_t total = 0, n_tiles = 0;
     for (int32_t j = 0; j < m; ++j) {
         int32_t oj = order ? order[j] : j;
@@ -299,19 +298,23 @@ extern "C" adapshot_status adapshot_assemble(adapshot_ctx* ctx, adapshot_cache* 
     if (pos0 + cache->len + total > ctx->max_position)
         return fail(ctx, ADAPSHOT_ECAPACITY, "assemble: position %lld exceeds max_position %lld",
                     (long long)(pos0 + cache->len + total), (long long)ctx->max_position);
-    if (total == 0) {
-        ctx->last_error.clear();
-        return ADAPSHOT_OK;
-    }
     if (n_tiles > INT32_MAX) return fail(ctx, ADAPSHOT_EINVAL, "assemble: too many tiles");
+    *total_out = total;
+    *n_tiles_out = n_tiles;
+    return ADAPSHOT_OK;
+}
 
-    hipStream_t stream = (hipStream_t)hip_stream;
+// Plan (prefix sums -> tile descriptors) and launch of one validated assemble call.
+static adapshot_status run_assemble(adapshot_ctx* ctx, adapshot_cache* cache, const int32_t* shot_ids,
+                                    const int32_t* order, int32_t m, int64_t pos0, int64_t total, int64_t n_tiles,
+                                    hipStream_t stream) {
+    if (total == 0) return ADAPSHOT_OK;
     int slot;
     void* host;
     hipError_t e = ctx->tile_ring.acquire((size_t)n_tiles * sizeof(TileDesc), &slot, &host);
     if (e != hipSuccess) return fail_hip(ctx, "assemble: pinned tile buffer", e);
 
-    // Pass 2: slot j starts at off_j = sum of the lengths before it.
+    // slot group j starts at off_j = sum of the lengths before it
     TileDesc* tiles = (TileDesc*)host;
     const bool local = ctx->desc.key_state == ADAPSHOT_KEYS_ROTATED_LOCAL;
     int64_t slot0 = cache->len, nt = 0;
@@ -359,15 +362,103 @@ extern "C" adapshot_status adapshot_assemble(adapshot_ctx* ctx, adapshot_cache* 
     e = ctx->tile_ring.mark_in_use(slot, stream);
     if (e != hipSuccess) return fail_hip(ctx, "assemble: event record", e);
     cache->len += total;
+    return ADAPSHOT_OK;
+}
+
+extern "C" adapshot_status adapshot_assemble(adapshot_ctx* ctx, adapshot_cache* cache, const int32_t* shot_ids,
+                                             const int32_t* order, int32_t m, int64_t pos0, void* hip_stream) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    int64_t total = 0, n_tiles = 0;
+    adapshot_status st = check_assemble(ctx, cache, shot_ids, order, m, pos0, &total, &n_tiles);
+    if (st != ADAPSHOT_OK) return st;
+    st = run_assemble(ctx, cache, shot_ids, order, m, pos0, total, n_tiles, (hipStream_t)hip_stream);
+    if (st == ADAPSHOT_OK) ctx->last_error.clear();
+    return st;
+}
+
+extern "C" adapshot_status adapshot_assemble_batched(adapshot_ctx* ctx, adapshot_cache* caches, int32_t n_caches,
+                                                     const int32_t* const* shot_ids, const int32_t* const* orders,
+                                                     const int32_t* m, int64_t pos0, void* hip_stream) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    if (n_caches < 0) return fail(ctx, ADAPSHOT_EINVAL, "assemble_batched: n_caches < 0");
+    if (n_caches > 0 && (!caches || !shot_ids || !m)) return fail(ctx, ADAPSHOT_EINVAL, "assemble_batched: null pointer");
+    std::vector<int64_t> total(n_caches), n_tiles(n_caches);
+    for (int32_t b = 0; b < n_caches; ++b) {  // every item is validated before anything is launched
+        for (int32_t c = 0; c < b; ++c)
+            if (caches[c].k == caches[b].k || caches[c].v == caches[b].v)
+                return fail(ctx, ADAPSHOT_EINVAL, "assemble_batched: caches %d and %d share a buffer", c, b);
+        adapshot_status st = check_assemble(ctx, &caches[b], shot_ids[b], orders ? orders[b] : nullptr, m[b], pos0,
+                                            &total[b], &n_tiles[b]);
+        if (st != ADAPSHOT_OK) return st;
+    }
+    for (int32_t b = 0; b < n_caches; ++b) {
+        adapshot_status st = run_assemble(ctx, &caches[b], shot_ids[b], orders ? orders[b] : nullptr, m[b], pos0,
+                                          total[b], n_tiles[b], (hipStream_t)hip_stream);
+        if (st != ADAPSHOT_OK) return st;
+    }
     ctx->last_error.clear();
     return ADAPSHOT_OK;
 }
 
-extern "C" adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot_cache* cache, int32_t layer,
-                                               int64_t n_ctx, const void* q, const void* k_self,
-                                               const void* v_self, int32_t t_q, int64_t q_pos0, void* out,
-                                               void* hip_stream) {
+extern "C" adapshot_status adapshot_decode_append(adapshot_ctx* ctx, adapshot_cache* caches, int32_t n_caches,
+                                                  const void* k_new, const void* v_new, int64_t pos0,
+                                                  void* hip_stream) {
     if (!ctx) return ADAPSHOT_EINVAL;
+    if (n_caches < 0) return fail(ctx, ADAPSHOT_EINVAL, "decode_append: n_caches < 0");
+    if (n_caches == 0) {
+        ctx->last_error.clear();
+        return ADAPSHOT_OK;
+    }
+    if (!caches || !k_new || !v_new) return fail(ctx, ADAPSHOT_EINVAL, "decode_append: null pointer");
+    if (!aligned16(k_new) || !aligned16(v_new))
+        return fail(ctx, ADAPSHOT_EINVAL, "decode_append: k_new / v_new must be 16-byte aligned");
+    if (pos0 < 0) return fail(ctx, ADAPSHOT_EINVAL, "decode_append: pos0 < 0");
+    for (int32_t b = 0; b < n_caches; ++b) {
+        const adapshot_cache& c = caches[b];
+        if (!c.k || !c.v || !aligned16(c.k) || !aligned16(c.v))
+            return fail(ctx, ADAPSHOT_EINVAL, "decode_append: cache %d has null or misaligned buffers", b);
+        if (c.capacity < 0 || c.capacity > INT32_MAX || c.len < 0 || c.len > c.capacity)
+            return fail(ctx, ADAPSHOT_EINVAL, "decode_append: cache %d has bad capacity/len", b);
+        if (c.len + 1 > c.capacity) return fail(ctx, ADAPSHOT_ECAPACITY, "decode_append: cache %d is full", b);
+        if (pos0 + c.len + 1 > ctx->max_position)
+            return fail(ctx, ADAPSHOT_ECAPACITY, "decode_append: position exceeds max_position");
+    }
+    hipStream_t stream = (hipStream_t)hip_stream;
+    for (int32_t b0 = 0; b0 < n_caches; b0 += kDecodeBatch) {
+        DecodeAppendParams p;
+        p.k_new = (const char*)k_new;
+        p.v_new = (const char*)v_new;
+        p.tab_lo = ctx->tab_lo;
+        p.tab_hi = ctx->tab_hi;
+        p.n_layers = ctx->desc.n_layers;
+        p.n_kv_heads = ctx->desc.n_kv_heads;
+        p.head_dim = ctx->desc.head_dim;
+        p.dtype = ctx->desc.dtype;
+        p.n_total = n_caches;
+        p.first = b0;
+        p.count = std::min<int32_t>(kDecodeBatch, n_caches - b0);
+        for (int32_t i = 0; i < p.count; ++i) {
+            const adapshot_cache& c = caches[b0 + i];
+            p.k_out[i] = (char*)c.k;
+            p.v_out[i] = (char*)c.v;
+            p.capacity[i] = (int32_t)c.capacity;
+            p.slot[i] = (int32_t)c.len;
+            p.pos[i] = (int32_t)(pos0 + c.len);
+            p.slot_shot[i] = c.slot_shot;
+            p.slot_tok[i] = c.slot_tok;
+            p.slot_pos[i] = c.slot_pos;
+        }
+        hipError_t e = timed_launch(ctx, ADAPSHOT_KERNEL_ASSEMBLE, stream, [&] { return launch_decode_append(p, stream); });
+        if (e != hipSuccess) return fail_hip(ctx, "decode_append: launch", e);
+    }
+    for (int32_t b = 0; b < n_caches; ++b) caches[b].len += 1;
+    ctx->last_error.clear();
+    return ADAPSHOT_OK;
+}
+
+static adapshot_status check_query_attn(adapshot_ctx* ctx, const adapshot_cache* cache, int32_t layer, int64_t n_ctx,
+                                        const void* q, const void* k_self, const void* v_self, int32_t t_q,
+                                        int64_t q_pos0, const void* out) {
     if (!cache || !q || !k_self || !v_self || !out) return fail(ctx, ADAPSHOT_EINVAL, "query_attn: null pointer");
     if (t_q < 1) return fail(ctx, ADAPSHOT_EINVAL, "query_attn: t_q < 1");
     if (layer < 0 || layer >= ctx->desc.n_layers) return fail(ctx, ADAPSHOT_EINVAL, "query_attn: layer out of range");
@@ -384,8 +475,12 @@ extern "C" adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot
 
     if ((uint64_t)std::max<int64_t>(n_ctx, t_q) * (uint64_t)ctx->row_bytes > 0xffffffffull)
         return fail(ctx, ADAPSHOT_EINVAL, "query_attn: context rows span more than 4 GiB per layer");
+    return ADAPSHOT_OK;
+}
 
-    hipStream_t stream = (hipStream_t)hip_stream;
+static adapshot_status run_query_attn(adapshot_ctx* ctx, const adapshot_cache* cache, int32_t layer, int64_t n_ctx,
+                                      const void* q, const void* k_self, const void* v_self, int32_t t_q,
+                                      int64_t q_pos0, void* out, hipStream_t stream) {
     const adapshot_model_desc& d = ctx->desc;
     const int g = d.n_q_heads / d.n_kv_heads;
     const int64_t rows = (int64_t)t_q * g;
@@ -455,6 +550,42 @@ extern "C" adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot
     if (e != hipSuccess) return fail_hip(ctx, "query_attn: attention launch", e);
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(ap, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "query_attn: combine launch", e);
+    return ADAPSHOT_OK;
+}
+
+extern "C" adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot_cache* cache, int32_t layer,
+                                               int64_t n_ctx, const void* q, const void* k_self,
+                                               const void* v_self, int32_t t_q, int64_t q_pos0, void* out,
+                                               void* hip_stream) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    adapshot_status st = check_query_attn(ctx, cache, layer, n_ctx, q, k_self, v_self, t_q, q_pos0, out);
+    if (st != ADAPSHOT_OK) return st;
+    st = run_query_attn(ctx, cache, layer, n_ctx, q, k_self, v_self, t_q, q_pos0, out, (hipStream_t)hip_stream);
+    if (st == ADAPSHOT_OK) ctx->last_error.clear();
+    return st;
+}
+
+extern "C" adapshot_status adapshot_query_attn_batched(adapshot_ctx* ctx, const adapshot_cache* caches,
+                                                       int32_t n_caches, int32_t layer,
+                                                       const adapshot_attn_item* items, int32_t n_items,
+                                                       void* hip_stream) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    if (n_items < 0 || n_caches < 0) return fail(ctx, ADAPSHOT_EINVAL, "query_attn_batched: negative count");
+    if (n_items > 0 && (!items || !caches)) return fail(ctx, ADAPSHOT_EINVAL, "query_attn_batched: null pointer");
+    for (int32_t i = 0; i < n_items; ++i) {  // every item is validated before anything is launched
+        const adapshot_attn_item& it = items[i];
+        if (it.cache_index < 0 || it.cache_index >= n_caches)
+            return fail(ctx, ADAPSHOT_EINVAL, "query_attn_batched: item %d: cache_index out of range", i);
+        adapshot_status st = check_query_attn(ctx, &caches[it.cache_index], layer, it.n_ctx, it.q, it.k_self, it.v_self,
+                                              it.t_q, it.q_pos0, it.out);
+        if (st != ADAPSHOT_OK) return st;
+    }
+    for (int32_t i = 0; i < n_items; ++i) {
+        const adapshot_attn_item& it = items[i];
+        adapshot_status st = run_query_attn(ctx, &caches[it.cache_index], layer, it.n_ctx, it.q, it.k_self, it.v_self,
+                                            it.t_q, it.q_pos0, it.out, (hipStream_t)hip_stream);
+        if (st != ADAPSHOT_OK) return st;
+    }
     ctx->last_error.clear();
     return ADAPSHOT_OK;
 }

@@ -56,6 +56,27 @@ struct AssembleParams {
 };
 hipError_t launch_assemble(const AssembleParams& p, hipStream_t stream);
 
+// One decode step: cache i of this launch receives token row [layer][first + i] of k_new / v_new at
+// slot[i], the key rotated to pos[i].  Pointer tables travel in the kernel arguments.
+constexpr int kDecodeBatch = 32;
+struct DecodeAppendParams {
+    const char* k_new;  // [n_layers][n_total][h_kv][d], un-rotated
+    const char* v_new;
+    const float2* tab_lo;
+    const float2* tab_hi;
+    char* k_out[kDecodeBatch];
+    char* v_out[kDecodeBatch];
+    int32_t* slot_shot[kDecodeBatch];
+    int32_t* slot_tok[kDecodeBatch];
+    int64_t* slot_pos[kDecodeBatch];
+    int32_t capacity[kDecodeBatch];
+    int32_t slot[kDecodeBatch];
+    int32_t pos[kDecodeBatch];
+    int32_t n_layers, n_kv_heads, head_dim, dtype;
+    int32_t n_total, first, count;
+};
+hipError_t launch_decode_append(const DecodeAppendParams& p, hipStream_t stream);
+
 // ---- attention --------------------------------------------------------------------
 struct RopeRowsParams {
     const void* q;       // [t_q][h_q][d]

@@ -188,4 +188,78 @@ hipError_t launch_assemble(const AssembleParams& p, hipStream_t stream) {
     return hipErrorInvalidValue;
 }
 
+// ---- decode append ------------------------------------------------------------------------------
+// One new token per cache: its key rotated to the token's position (the keys of a decode step come
+// from the model un-rotated, whatever the pool's key state), its value copied.  grid = (caches of this
+// launch, layers); a lane owns one (head, chunk) item exactly as in the tile kernel.
+template <int DTYPE, int CH>
+__global__ __launch_bounds__(128) void decode_append_kernel(DecodeAppendParams p) {
+    constexpr int E = DTYPE == ADAPSHOT_BF16 ? 2 : 4;
+    constexpr int NP = 16 / E;
+    constexpr int HALF = CH * NP;
+    constexpr int HEAD_BYTES = 2 * CH * 16;
+    const int i = blockIdx.x, l = blockIdx.y;
+    const int64_t row_bytes = (int64_t)p.n_kv_heads * HEAD_BYTES;
+    const char* ksrc = p.k_new + ((int64_t)l * p.n_total + p.first + i) * row_bytes;
+    const char* vsrc = p.v_new + ((int64_t)l * p.n_total + p.first + i) * row_bytes;
+    const int64_t dst = ((int64_t)l * p.capacity[i] + p.slot[i]) * row_bytes;
+    char* kdst = p.k_out[i] + dst;
+    char* vdst = p.v_out[i] + dst;
+    const int a = p.pos[i];
+    if (l == 0 && threadIdx.x == 0) {
+        if (p.slot_shot[i]) p.slot_shot[i][p.slot[i]] = -1;  // not a pool shot
+        if (p.slot_tok[i]) p.slot_tok[i][p.slot[i]] = 0;
+        if (p.slot_pos[i]) p.slot_pos[i][p.slot[i]] = a;
+    }
+    const int n_items = p.n_kv_heads * CH;
+    for (int f = threadIdx.x; f < n_items; f += 128) {
+        const int h = f / CH, c = f - h * CH;
+        const int64_t off = (int64_t)h * HEAD_BYTES + c * 16;
+        u32x4 x1 = ld16(ksrc + off), x2 = ld16(ksrc + off + CH * 16);
+        float2 cs[NP];
+#pragma unroll
+        for (int w = 0; w < NP; ++w) {
+            const float2 hi = p.tab_hi[(int64_t)(a >> kRopeLoBits) * HALF + c * NP + w];
+            const float2 lo = p.tab_lo[(a & (kRopeLo - 1)) * HALF + c * NP + w];
+            cs[w] = make_float2(hi.x * lo.x - hi.y * lo.y, hi.y * lo.x + hi.x * lo.y);
+        }
+        rotate_chunks<DTYPE>(x1, x2, cs);
+        st16(kdst + off, x1);
+        st16(kdst + off + CH * 16, x2);
+        st16(vdst + off, ld16(vsrc + off));
+        st16(vdst + off + CH * 16, ld16(vsrc + off + CH * 16));
+    }
+}
+
+template <int DTYPE, int CH>
+static hipError_t launch_decode_t(const DecodeAppendParams& p, hipStream_t stream) {
+    hipLaunchKernelGGL((decode_append_kernel<DTYPE, CH>), dim3((unsigned)p.count, (unsigned)p.n_layers), dim3(128), 0,
+                       stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_append(const DecodeAppendParams& p, hipStream_t stream) {
+    const int e = p.dtype == ADAPSHOT_BF16 ? 2 : 4;
+    const int ch = p.head_dim / 2 * e / 16;
+    if (p.count <= 0) return hipSuccess;
+    if (p.dtype == ADAPSHOT_BF16) {
+        switch (ch) {
+            case 1: return launch_decode_t<ADAPSHOT_BF16, 1>(p, stream);
+            case 2: return launch_decode_t<ADAPSHOT_BF16, 2>(p, stream);
+            case 4: return launch_decode_t<ADAPSHOT_BF16, 4>(p, stream);
+            case 8: return launch_decode_t<ADAPSHOT_BF16, 8>(p, stream);
+            case 16: return launch_decode_t<ADAPSHOT_BF16, 16>(p, stream);
+        }
+    } else {
+        switch (ch) {
+            case 1: return launch_decode_t<ADAPSHOT_F32, 1>(p, stream);
+            case 2: return launch_decode_t<ADAPSHOT_F32, 2>(p, stream);
+            case 4: return launch_decode_t<ADAPSHOT_F32, 4>(p, stream);
+            case 8: return launch_decode_t<ADAPSHOT_F32, 8>(p, stream);
+            case 16: return launch_decode_t<ADAPSHOT_F32, 16>(p, stream);
+        }
+    }
+    return hipErrorInvalidValue;
+}
+
 }  // namespace adapshot

@@ -1,0 +1,178 @@
+"""GPU parity on the multi-query workloads: the nested-prefix probe sweep (config 3), the 128k-token
+context (config 4, sampled outputs) and the decode loop (config 5), all through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_03644_amd import workloads as wl
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ad():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2605_03644_amd import binding
+    binding.load_library()
+    return binding
+
+
+def test_probe_sweep_nested_prefixes_batched(ad, oracle_mod):
+    """Config 3 shape, 2 layers, 3 queries: each query assembles its own 64-shot ordering once
+    (adapshot_assemble_batched); probes at prefixes k = 16, 32, 64 attend over slots [0, off_k) of that cache
+    (adapshot_query_attn_batched) -- a prefix keeps its positions, so this equals re-assembling k shots."""
+    w = wl.WORKLOADS["llama8b_sweep"]
+    L, n_q, ks_list, m_max = 2, 3, (16, 32, 64), 64
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=L)
+    ctx = ad.Context.for_workload(w, n_layers=L)
+    ctx.pool_register(k_pool, v_pool, off)
+    sels = []
+    for qi in range(n_q):
+        ids, order = wl.selection(w, query=qi)
+        ids, order = ids[:m_max], np.argsort(np.argsort(order[:m_max])).astype(np.int32)
+        sels.append((ids, order))
+    totals = [int(sum(off[i + 1] - off[i] for i in ids)) for ids, _ in sels]
+    caches = [ad.Cache(ctx, t) for t in totals]
+    ctx.assemble_batched(caches, [s[0] for s in sels], [s[1] for s in sels])
+    assert [c.len for c in caches] == totals
+    kp, vp = H.to_storage(k_pool), H.to_storage(v_pool)
+
+    for layer in range(L):
+        items, meta = [], []
+        for qi in range(n_q):
+            ids, order = sels[qi]
+            seq = [int(ids[o]) for o in order]
+            q, ks, vs = wl.make_query(w, "cuda", query=qi, layer=layer)
+            for k in ks_list:
+                n_ctx = int(sum(off[s + 1] - off[s] for s in seq[:k]))
+                out = torch.empty_like(q)
+                items.append((qi, n_ctx, q, ks, vs, n_ctx, out))
+                meta.append((qi, k, n_ctx, q, ks, vs, out))
+        ctx.query_attn_batched(caches, layer, items)
+        torch.cuda.synchronize()
+        for qi, k, n_ctx, q, ks, vs, out in meta:
+            ids, order = sels[qi]
+            # oracle: assemble exactly the first k shots from scratch, then attend
+            seq = [int(ids[o]) for o in order][:k]
+            pl = oracle_mod.plan(off, seq, None)
+            assert pl["n"] == n_ctx
+            ko, vo, _ = oracle_mod.assemble(kp[layer:layer + 1], vp[layer:layer + 1], w.dtype, w.rope_theta, 0, pl, 0, n_ctx)
+            pairs = np.array([[j, h] for j in (0, 17, w.t_q - 1) for h in (0, 9, 31)], np.int32)
+            ref = oracle_mod.query_attn(ko[0], vo[0], w.dtype, n_ctx, H.to_storage(q), H.to_storage(ks), H.to_storage(vs),
+                                        w.rope_theta, n_ctx, pairs=pairs)
+            got = np.stack([out.float().cpu().numpy()[j, h] for j, h in pairs])
+            H.check_attention(got, ref)
+            # the prefix of the incrementally assembled cache is bit-identical to the from-scratch assembly
+            assert (H.to_storage(caches[qi].k[layer, :n_ctx]) == ko[0]).mean() > 0.99
+            assert np.array_equal(H.to_storage(caches[qi].v[layer, :n_ctx]), vo[0])
+    # a bad item anywhere fails the whole batch before anything runs
+    out0 = items[0][6].clone()
+    bad = list(items)
+    bad[-1] = (0, totals[0] + 1, *items[-1][2:])
+    with pytest.raises(ad.AdapshotError) as e:
+        ctx.query_attn_batched(caches, 0, bad)
+    assert e.value.status == ad.ESTATE
+    torch.cuda.synchronize()
+    assert torch.equal(items[0][6], out0)
+    ctx.close()
+
+
+def test_llama70b_128k_context_sampled(ad, oracle_mod):
+    """Config 4 at full context size on one layer: 1000 of 4000 shots (~128k tokens), 256 query tokens,
+    64 q heads / 8 kv heads.  Assemble is checked in full for V and on sampled tokens for K; attention
+    on sampled (row, head) outputs."""
+    w = wl.WORKLOADS["llama70b_128k"]
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=1)
+    ids, order = wl.selection(w)
+    ctx = ad.Context.for_workload(w, n_layers=1)
+    ctx.pool_register(k_pool, v_pool, off)
+    total = int(sum(off[i + 1] - off[i] for i in ids))
+    assert total > 120000
+    cache = ad.Cache(ctx, total)
+    ctx.assemble(cache, ids, order)
+    q, ks, vs = wl.make_query(w, "cuda")
+    out = ctx.query_attn(cache, 0, total, q, ks, vs, total)
+    torch.cuda.synchronize()
+    kp, vp = H.to_storage(k_pool), H.to_storage(v_pool)
+    pl = oracle_mod.plan(off, ids, order)
+    assert np.array_equal(cache.slot_pos.cpu().numpy(), pl["slot_pos"])
+    assert np.array_equal(cache.slot_shot.cpu().numpy(), pl["slot_shot"])
+    ko, vo, kx = oracle_mod.assemble(kp, vp, w.dtype, w.rope_theta, 0, pl, 0, total, want_exact=True)
+    kg, vg = H.to_storage(cache.k), H.to_storage(cache.v)
+    assert np.array_equal(vg, vo)
+    H.check_reencode_bf16(kg, ko, kx, kp[:, pl["slot_src"]])
+    rng = np.random.default_rng(4)
+    pairs = np.stack([rng.integers(0, w.t_q, 48), rng.integers(0, w.n_q_heads, 48)], axis=1).astype(np.int32)
+    pairs[0] = (0, 0); pairs[1] = (w.t_q - 1, w.n_q_heads - 1)
+    ref = oracle_mod.query_attn(kg[0], vg[0], w.dtype, total, H.to_storage(q), H.to_storage(ks), H.to_storage(vs),
+                                w.rope_theta, total, pairs=pairs)
+    got = np.stack([out.float().cpu().numpy()[j, h] for j, h in pairs])
+    H.check_attention(got, ref)
+    ctx.close()
+
+
+def test_qwen_decode_loop(ad, oracle_mod):
+    """Config 5 shape, 2 layers, 4 queries with their own 12-shot orderings, 5 decode steps: every step appends
+    one token per query (adapshot_decode_append) and attends with a single query token (g = 7 rows per kv head)."""
+    w = wl.WORKLOADS["qwen7b_decode"]
+    L, n_q, steps, m = 2, 4, 5, 12
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=L)
+    ctx = ad.Context.for_workload(w, n_layers=L)
+    ctx.pool_register(k_pool, v_pool, off)
+    sels = [wl.selection(w, query=qi) for qi in range(n_q)]
+    sels = [(ids[:m], np.argsort(np.argsort(order[:m])).astype(np.int32)) for ids, order in sels]
+    totals = [int(sum(off[i + 1] - off[i] for i in ids)) for ids, _ in sels]
+    caches = [ad.Cache(ctx, t + steps) for t in totals]
+    ctx.assemble_batched(caches, [s[0] for s in sels], [s[1] for s in sels])
+    kp, vp = H.to_storage(k_pool), H.to_storage(v_pool)
+    # oracle caches
+    ref_k, ref_v = [], []
+    for qi in range(n_q):
+        pl = oracle_mod.plan(off, sels[qi][0], sels[qi][1])
+        ko, vo, _ = oracle_mod.assemble(kp, vp, w.dtype, w.rope_theta, 0, pl, 0, totals[qi] + steps)
+        ref_k.append(ko); ref_v.append(vo)
+    g = torch.Generator(device="cuda"); g.manual_seed(w.seed + 77)
+    for s in range(steps):
+        k_new = torch.randn(L, n_q, w.n_kv_heads, w.head_dim, device="cuda", generator=g).to(torch.bfloat16)
+        v_new = torch.randn(L, n_q, w.n_kv_heads, w.head_dim, device="cuda", generator=g).to(torch.bfloat16)
+        lens = [c.len for c in caches]
+        ctx.decode_append(caches, k_new, v_new)
+        assert [c.len for c in caches] == [n + 1 for n in lens]
+        # oracle append: rotate the new key of query qi to position lens[qi]
+        kn, vn = H.to_storage(k_new), H.to_storage(v_new)
+        for qi in range(n_q):
+            rot = oracle_mod.rot_rows(kn[:, qi], w.dtype, w.rope_theta, np.full(L * w.n_kv_heads, float(lens[qi])))
+            ref_k[qi][:, lens[qi]] = rot
+            ref_v[qi][:, lens[qi]] = vn[:, qi]
+        # one query token per query attends over its whole cache (the token it just appended included)
+        for layer in range(L):
+            items, meta = [], []
+            for qi in range(n_q):
+                q, ks, vs = wl.make_query(w, "cuda", query=qi * 100 + s, layer=layer)
+                out = torch.empty_like(q)
+                n_ctx = caches[qi].len
+                items.append((qi, n_ctx, q, ks, vs, n_ctx, out))
+                meta.append((qi, n_ctx, q, ks, vs, out))
+            ctx.query_attn_batched(caches, layer, items)
+            torch.cuda.synchronize()
+            for qi, n_ctx, q, ks, vs, out in meta:
+                kc, vc = H.to_storage(caches[qi].k[layer]), H.to_storage(caches[qi].v[layer])
+                ref = oracle_mod.query_attn(kc, vc, w.dtype, n_ctx, H.to_storage(q), H.to_storage(ks), H.to_storage(vs),
+                                            w.rope_theta, n_ctx)
+                H.check_attention(out.float().cpu().numpy(), ref)
+    torch.cuda.synchronize()
+    for qi in range(n_q):
+        n = caches[qi].len
+        kg, vg = H.to_storage(caches[qi].k), H.to_storage(caches[qi].v)
+        assert np.array_equal(vg[:, :n], ref_v[qi][:, :n])
+        assert (kg[:, :n] == ref_k[qi][:, :n]).mean() > 0.99
+        assert np.array_equal(caches[qi].slot_pos[:n].cpu().numpy(), np.arange(n))
+        assert (caches[qi].slot_shot[totals[qi]:n] == -1).all()
+    # a full cache is refused and nothing is appended anywhere
+    lens = [c.len for c in caches]
+    with pytest.raises(ad.AdapshotError) as e:
+        ctx.decode_append(caches, k_new, v_new)
+    assert e.value.status == ad.ECAPACITY and [c.len for c in caches] == lens
+    ctx.close()

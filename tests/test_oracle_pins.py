@@ -161,6 +161,21 @@ def test_rot_invariants(oracle_mod):
     assert abs(s0 - s1) < 1e-9
 
 
+def test_rot_rows_bruteforce_and_rounding(oracle_mod):
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((3, 4, 16)).astype(np.float32)
+    ang = np.arange(12, dtype=np.float64) * 977 + 3
+    y, ex = oracle_mod.rot_rows(x, "f32", 5.0e5, ang, want_exact=True)
+    for r in range(12):
+        want = _rot_complex(x.reshape(12, 16)[r].astype(np.float64), 5.0e5, ang[r])
+        assert np.allclose(ex.reshape(12, 16)[r], want, atol=1e-11)
+        assert np.array_equal(y.reshape(12, 16)[r], want.astype(np.float32))
+    xb = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    yb, exb = oracle_mod.rot_rows(xb, "bf16", 5.0e5, ang, want_exact=True)
+    assert np.all(np.abs(oracle_mod.bf16_bits_to_f64(yb) - exb) <= 2.0 ** -8 * np.abs(exb) + 1e-40)
+    assert np.array_equal(oracle_mod.rot_rows(xb, "bf16", 5.0e5, np.zeros(12)), xb)      # angle 0: identity
+
+
 # ---------------------------------------------------------------- assemble
 
 def _tiny_pool(rng, L, n_shots, hkv, d, lo=2, hi=7):
