@@ -66,6 +66,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--workload", default="llama8b_1layer")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy 4 times (reference kernel of known traffic for "
+                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -174,6 +177,13 @@ def main() -> int:
         result["check"] = dict(attn_max_abs=float(np.abs(o - o_ref).max()), entropy_max_abs=float(np.abs(h - h_ref).max()))
     else:
         result["cpu_baseline"] = None
+    if args.copy_calibration:
+        src = torch.empty(128 << 20, dtype=torch.bfloat16, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        result["copy_calibration"] = {"bytes_read": src.numel() * 2, "bytes_written": src.numel() * 2, "launches": 4}
     print(json.dumps(result))
     ctx.close()
     return 0

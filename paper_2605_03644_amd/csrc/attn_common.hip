@@ -156,12 +156,13 @@ hipError_t launch_attn_generic(const AttnParams& p, hipStream_t stream) {
 }
 
 // ---- combine --------------------------------------------------------------------------------
-// out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s with M = max_s m_s.  A workgroup of 256 lanes
-// handles 8 (kv head, row) pairs: 32 lanes per pair, one float4 of the head dimension per lane and
-// step, all splits' loads independent of each other.  The self split always holds at least one
-// visible key, so the denominator is > 0.
+// out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s with M = max_s m_s.  HBM-bound on the partials.
+// A workgroup of 256 lanes handles 8 (kv head, row) pairs: 32 lanes per pair, one float4 of the head
+// dimension per lane; the partial rows of 8 splits are requested together before any is used.  The
+// self split always holds at least one visible key, so the denominator is > 0.
 template <int DTYPE>
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
+    constexpr int SB = 8;  // splits in flight
     const int d = p.head_dim;
     const int g = p.n_q_heads / p.n_kv_heads;
     const int64_t rows = (int64_t)p.t_q * g;
@@ -175,34 +176,55 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
     const int h = hk * g + (int)(row - (int64_t)j * g);
     const int ns = p.n_split + 1;
     const int64_t split_stride = (int64_t)p.n_kv_heads * rows;  // pairs per split
+    const float2* ml = p.part_ml + pair;
+    const float* po = p.part_o + pair * d;
 
     float M = -INFINITY;
-    for (int s = 0; s < ns; ++s) M = fmaxf(M, p.part_ml[s * split_stride + pair].x);
+    for (int s0 = 0; s0 < ns; s0 += SB) {
+        float m[SB];
+#pragma unroll
+        for (int u = 0; u < SB; ++u) m[u] = s0 + u < ns ? ml[(s0 + u) * split_stride].x : -INFINITY;
+#pragma unroll
+        for (int u = 0; u < SB; ++u) M = fmaxf(M, m[u]);
+    }
     float L = 0.f;
     f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-#pragma unroll 4
-    for (int s = 0; s < ns; ++s) {
-        const int64_t pr = s * split_stride + pair;
-        const float2 ml = p.part_ml[pr];
-        const float w = exp2f(ml.x - M);  // empty split: m = -inf -> 0
-        L += w * ml.y;
+    for (int s0 = 0; s0 < ns; s0 += SB) {
+        float2 mlv[SB];
+        f32x4 o[SB][2];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int e = 4 * (c + 32 * u);
-            if (e < d) {
-                const f32x4 o = *(const f32x4*)(p.part_o + pr * d + e);
-                acc[u] += w * o;
+        for (int u = 0; u < SB; ++u) {
+            const bool on = s0 + u < ns;
+            const int64_t so = (int64_t)(s0 + u) * split_stride;
+            mlv[u] = on ? ml[so] : make_float2(-INFINITY, 0.f);
+#pragma unroll
+            for (int v = 0; v < 2; ++v) {
+                const int e = 4 * (c + 32 * v);
+                o[u][v] = (on && e < d) ? __builtin_nontemporal_load((const f32x4*)(po + so * d + e))
+                                        : f32x4{0.f, 0.f, 0.f, 0.f};
             }
+        }
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+            const float w = exp2f(mlv[u].x - M);  // empty or absent split: m = -inf -> 0
+            L += w * mlv[u].y;
+            acc[0] += w * o[u][0];
+            acc[1] += w * o[u][1];
         }
     }
     const float inv = 1.0f / L;
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        const int e = 4 * (c + 32 * u);
+    for (int v = 0; v < 2; ++v) {
+        const int e = 4 * (c + 32 * v);
         if (e < d) {
-            const int64_t o = ((int64_t)j * p.n_q_heads + h) * d + e;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) store_elem<DTYPE>(p.out, o + k, acc[u][k] * inv);
+            const int64_t oo = ((int64_t)j * p.n_q_heads + h) * d + e;
+            if (DTYPE == ADAPSHOT_BF16) {
+                typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+                const f32x4 r = acc[v] * inv;
+                *(bf16x4*)((unsigned short*)p.out + oo) = __builtin_convertvector(r, bf16x4);
+            } else {
+                *(f32x4*)((float*)p.out + oo) = acc[v] * inv;
+            }
         }
     }
 }
