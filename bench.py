@@ -30,6 +30,13 @@ from paper_2605_03644_amd import workloads as wl  # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+# HBM bytes per launch (read + written) from two rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE),
+# each scaled by what the same counter reads for a plain 256 MiB device copy; the summary with the commands and
+# the raw counter values is profiles/bench_llama8b_1layer_hbm_traffic.txt.  Counters cannot be read from inside
+# this process, so the figures are carried here and hold for the default workload only.
+MEASURED_TRAFFIC_BYTES = {
+    "llama8b_1layer": {"assemble_reencode": 221.9e6, "query_attn": 146.2e6, "entropy_chunk": 65.8e6},
+}
 METRIC = "re-encoded KV tokens/s (HBM GB/s) + query-over-cache attn TFLOP/s at 26k ctx"
 
 
@@ -142,8 +149,9 @@ def main() -> int:
         "entropy_chunk": dict(bound="hbm", achieved=ent_bytes / ent_us * 1e-3, peak=HBM_PEAK_GBPS, unit="GB/s",
                               traffic=None, avg_us=ent_us, algorithmic_bytes=ent_bytes),
     }
-    for r in rl.values():
+    for name, r in rl.items():
         r["frac"] = r["achieved"] / r["peak"]
+        r["traffic"] = MEASURED_TRAFFIC_BYTES.get(w.name, {}).get(name)
     dominant = max(rl, key=lambda k: rl[k]["avg_us"])
     roofline = dict(kernel=dominant, **{k: rl[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")})
 
