@@ -24,6 +24,13 @@
 // S(t), softmax(t), PV(t); wavefronts 4-7 go PV(t-1), S(t), softmax(t).  While one of them runs
 // its exponentials the other one feeds the matrix core, with one workgroup barrier per tile.
 //
+// The S^T accumulators start from -m (m = the row's reference maximum, in registers) instead of zero,
+// so the scores leave the matrix core already shifted and the exponentials need no subtraction; the
+// reference moves only when a score exceeds it by more than 8 (log2 units), then O^T, the row sum and
+// the current scores are rescaled.  The key loop is unrolled four times so that every LDS buffer
+// offset is an instruction immediate and the tile pointers advance in scalar registers: the per-tile
+// vector ALU work is the maxima, the exponentials, the row sums and the bf16 packing only.
+//
 // K/V tiles go from global memory straight into LDS (global_load_lds, 16 bytes per lane), four
 // tiles deep for K and for V, with an XOR swizzle of the 16-byte chunks instead of row padding:
 //   K row r keeps chunk c at position c ^ (r & 15)      (16 rows of a 16-byte read: 16 bank groups)
@@ -154,19 +161,22 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int
     const int n_tiles = (int)((k1 - k0 + kTileKeys - 1) / kTileKeys);  // >= 1
 
     // ---- tile loads: wavefront w moves the 1 KB blocks (4 rows) w, w+WAVES, ...; lane = (row in block, chunk).
-    // Every lane keeps the byte offset of its chunk in the next K and V tile and advances it by one tile
-    // per load.  The last tile (whose rows may run past the end of the split) and the tiles past the end
-    // (loaded anyway so that the number of loads in flight stays the same in every iteration; they land
-    // in buffers nobody reads any more) take their offsets with the row clamped to the last valid key.
+    // Every lane keeps the byte offset of its chunks inside a tile; the tile itself is addressed by a
+    // wave-uniform pointer that advances by one tile per load.  The last tile (whose rows may run past the
+    // end of the split) and the tiles past the end (loaded anyway so that the number of loads in flight
+    // stays the same in every iteration; they land in buffers nobody reads any more) take their offsets
+    // from the start of the cache with the row clamped to the last valid key.
     const unsigned tile_step = (unsigned)(kTileKeys * kv_stride);
-    unsigned k_goff[PASSES], v_goff[PASSES];  // offsets from kbase / vbase of this lane's chunks in the next tile
+    unsigned k_loff[PASSES], v_loff[PASSES];
 #pragma unroll
     for (int ps = 0; ps < PASSES; ++ps) {
         const int r = 4 * (ps * WAVES + wave) + (lane >> 4);
-        const unsigned row_off = (unsigned)((k0 + r) * kv_stride);
-        k_goff[ps] = row_off + (((lane & 15) ^ (r & 15)) << 4);
-        v_goff[ps] = row_off + (((lane & 15) ^ ((r & 3) << 2)) << 4);
+        const unsigned row_off = (unsigned)(r * kv_stride);
+        k_loff[ps] = row_off + (((lane & 15) ^ (r & 15)) << 4);
+        v_loff[ps] = row_off + (((lane & 15) ^ ((r & 3) << 2)) << 4);
     }
+    const char* k_tile = kbase + k0 * kv_stride;  // next K tile to load
+    const char* v_tile = vbase + k0 * kv_stride;  // next V tile to load
     auto clamped_off = [&](int ps, bool is_v) __attribute__((always_inline)) -> unsigned {
         const int r = 4 * (ps * WAVES + wave) + (lane >> 4);
         int64_t key = k0 + (int64_t)(n_tiles - 1) * kTileKeys + r;
@@ -175,6 +185,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int
         return (unsigned)(key * kv_stride) + (sw << 4);
     };
     int next_k_tile = 0, next_v_tile = 0;
+    // buf is a compile-time constant at every call site, so the LDS destination is an immediate
     auto issue_k = [&](int buf) __attribute__((always_inline)) {
         if (next_k_tile >= n_tiles - 1) {
 #pragma unroll
@@ -183,11 +194,10 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int
                             __builtin_amdgcn_readfirstlane(lds_addr(k_s[buf] + (ps * WAVES + wave) * 1024)));
         } else {
 #pragma unroll
-            for (int ps = 0; ps < PASSES; ++ps) {
-                load_lds_16(kbase, k_goff[ps],
+            for (int ps = 0; ps < PASSES; ++ps)
+                load_lds_16(k_tile, k_loff[ps],
                             __builtin_amdgcn_readfirstlane(lds_addr(k_s[buf] + (ps * WAVES + wave) * 1024)));
-                k_goff[ps] += tile_step;
-            }
+            k_tile += tile_step;
         }
         ++next_k_tile;
     };
@@ -199,17 +209,16 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int
                             __builtin_amdgcn_readfirstlane(lds_addr(v_s[buf] + (ps * WAVES + wave) * 1024)));
         } else {
 #pragma unroll
-            for (int ps = 0; ps < PASSES; ++ps) {
-                load_lds_16(vbase, v_goff[ps],
+            for (int ps = 0; ps < PASSES; ++ps)
+                load_lds_16(v_tile, v_loff[ps],
                             __builtin_amdgcn_readfirstlane(lds_addr(v_s[buf] + (ps * WAVES + wave) * 1024)));
-                v_goff[ps] += tile_step;
-            }
+            v_tile += tile_step;
         }
         ++next_v_tile;
     };
-    // K(0..3) and V(0..2) start now
-    for (int t = 0; t < 4; ++t) issue_k(t);
-    for (int t = 0; t < 3; ++t) issue_v(t);
+    // K(0) and V(0) start now; the other tiles of the pipeline follow once these have landed
+    issue_k(0);
+    issue_v(0);
 
     // ---- Q fragments (B operand): lane holds row l32, d = 16*kk + 8*hh .. +7
     bf16x8 qf[8];
@@ -227,7 +236,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int
     }
 
     // ---- per-lane LDS read addresses.  The K tiles occupy LDS bytes [0, 64K) and the V tiles
-    // [64K, 128K), four 16 KB buffers each; an address moves to the next buffer by +16K modulo 64K.
+    // [64K, 128K), four 16 KB buffers each.
     // K fragment kk of key block kb: row 32*kb + l32, chunk (2*kk + hh) ^ (l32 & 15)
     unsigned ka[8];
 #pragma unroll
@@ -245,24 +254,23 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int
             va[db] = lds_addr(&v_s[0][0]) + (unsigned)((4 * hh + r3) * kRowBytes + ((db ^ r3) << 6) +
                                                        (((lane >> 4) & 1) << 5) + ((i16 & 3) << 3));
     }
-    const unsigned k_region = lds_addr(&k_s[0][0]), v_region = lds_addr(&v_s[0][0]);
-    auto next_k_buffer = [&]() __attribute__((always_inline)) {
+    typedef __attribute__((address_space(3))) char lds_char;
+    lds_char* kp[8];
+    lds_char* vp[4];
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) ka[kk] = k_region | ((ka[kk] - k_region + kTileBytes) & (kNBuf * kTileBytes - 1));
-    };
-    auto next_v_buffer = [&]() __attribute__((always_inline)) {
+    for (int kk = 0; kk < 8; ++kk) kp[kk] = (lds_char*)(uintptr_t)ka[kk];
 #pragma unroll
-        for (int db = 0; db < 4; ++db) va[db] = v_region | ((va[db] - v_region + kTileBytes) & (kNBuf * kTileBytes - 1));
-    };
-    auto k_frag = [&](int kb, int kk) __attribute__((always_inline)) -> bf16x8 {
-        const u32x4 w = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(ka[kk] + kb * (32 * kRowBytes));
+    for (int db = 0; db < 4; ++db) vp[db] = (lds_char*)(uintptr_t)va[db];
+    // buf and the block indices are compile-time constants at every call site: they fold into the
+    // 16-bit offset field of the LDS instruction, so the address registers never change.
+    auto k_frag = [&](int buf, int kb, int kk) __attribute__((always_inline)) -> bf16x8 {
+        const u32x4 w = *(const __attribute__((address_space(3))) u32x4*)(kp[kk] + buf * kTileBytes + kb * (32 * kRowBytes));
         return __builtin_bit_cast(bf16x8, w);
     };
-    auto v_frag = [&](int ks, int db) __attribute__((always_inline)) -> bf16x8 {
-        const unsigned a = va[db] + ks * (16 * kRowBytes);
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)a);
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4*)(uintptr_t)(a + 8 * kRowBytes));
+    auto v_frag = [&](int buf, int ks, int db) __attribute__((always_inline)) -> bf16x8 {
+        lds_char* a = vp[db] + buf * kTileBytes + ks * (16 * kRowBytes);
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)a);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a + 8 * kRowBytes));
         const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         return __builtin_bit_cast(bf16x8, av);
     };
@@ -274,24 +282,24 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int
         for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
     float m_run = -INFINITY;  // reference maximum of the exponentials (log2 units); may lag the true maximum by < 8
     float l_run = 0.f;        // this lane's share of the row sum
-    f32x16 s[2];              // S^T of the current tile, key blocks 0 and 1
+    f32x16 s[2];              // S^T of the current tile minus the reference maximum, key blocks 0 and 1
+    f32x16 negm;              // -(reference maximum): the value the S^T accumulators start from, so that the
+                              // exponentials need no subtraction; rewritten only when the reference moves
+#pragma unroll
+    for (int r = 0; r < 16; ++r) negm[r] = 0.f;
     u32x4 pb[4];              // P^T of the current tile (packed bf16), one B operand per 16-key step
 
-    // S^T(t) = K(t) . Q^T from the buffer ka points at: 16 MFMAs, fragments read kPD steps ahead
-    auto s_phase = [&]() __attribute__((always_inline)) {
+    // S^T(t) - m = K(t) . Q^T - m from K buffer `buf`: 16 MFMAs, fragments read kPD steps ahead
+    auto s_phase = [&](int buf) __attribute__((always_inline)) {
         bf16x8 fr[kPD];
 #pragma unroll
-        for (int i = 0; i < kPD; ++i) fr[i] = k_frag(i & 1, i >> 1);
+        for (int i = 0; i < kPD; ++i) fr[i] = k_frag(buf, i & 1, i >> 1);
 #pragma unroll
         for (int i = 0; i < 16; ++i) {  // kk = i/2, kb = i%2
             const bf16x8 a = fr[i % kPD];
-            if (i + kPD < 16) fr[i % kPD] = k_frag((i + kPD) & 1, (i + kPD) >> 1);
-            if (i < 2) {
-                const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0], zero, 0, 0, 0);
-            } else {
-                s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[i >> 1], s[i & 1], 0, 0, 0);
-            }
+            if (i + kPD < 16) fr[i % kPD] = k_frag(buf, (i + kPD) & 1, (i + kPD) >> 1);
+            if (i < 2) s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0], negm, 0, 0, 0);
+            else s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[i >> 1], s[i & 1], 0, 0, 0);
         }
         __builtin_amdgcn_sched_group_barrier(0x100, kPD, 0);  // the first kPD fragment reads, then MFMA / read pairs
 #pragma unroll
@@ -300,15 +308,15 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int
             if (i + kPD < 16) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
     };
-    // O^T += V^T . P^T from the buffer va points at: 16 MFMAs, 2 transposing reads per fragment
-    auto pv_phase = [&]() __attribute__((always_inline)) {
+    // O^T += V^T . P^T from V buffer `buf`: 16 MFMAs, 2 transposing reads per fragment
+    auto pv_phase = [&](int buf) __attribute__((always_inline)) {
         bf16x8 fr[kPD];
 #pragma unroll
-        for (int i = 0; i < kPD; ++i) fr[i] = v_frag(i >> 2, i & 3);
+        for (int i = 0; i < kPD; ++i) fr[i] = v_frag(buf, i >> 2, i & 3);
 #pragma unroll
         for (int i = 0; i < 16; ++i) {  // ks = i/4, db = i%4
             const bf16x8 a = fr[i % kPD];
-            if (i + kPD < 16) fr[i % kPD] = v_frag((i + kPD) >> 2, (i + kPD) & 3);
+            if (i + kPD < 16) fr[i % kPD] = v_frag(buf, (i + kPD) >> 2, (i + kPD) & 3);
             o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, pb[i >> 2]), o[i & 3], 0, 0, 0);
         }
         __builtin_amdgcn_sched_group_barrier(0x100, 2 * kPD, 0);
@@ -319,82 +327,117 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int
         }
     };
     // masks + online softmax of tile t with a lazily updated reference maximum; leaves P^T(t) in pb
+    // Key visibility in 32-bit arithmetic relative to k0: a key of this lane is visible while its index
+    // 64*t + 32*kb + 8*(r/4) + (r%4) stays below lim (the 4*hh of the lane is folded into lim).
+    const int n_keys = (int)(k1 - k0);
+    const int lim = (self ? (jrow[0] < n_keys ? jrow[0] + 1 : n_keys) : n_keys) - 4 * hh;
     auto softmax_phase = [&](int t) __attribute__((always_inline)) {
-        const int64_t tile_k0 = k0 + (int64_t)t * kTileKeys;
-        if (self || tile_k0 + kTileKeys > k1) {
+        if (self || (t + 1) * kTileKeys > n_keys) {
+            const int lim_t = lim - t * kTileKeys;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t key = tile_k0 + 32 * kb + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    const bool vis = key < k1 && (!self || key <= (int64_t)jrow[0]);
-                    if (!vis) s[kb][r] = -INFINITY;
-                }
+                for (int r = 0; r < 16; ++r)
+                    if (32 * kb + 8 * (r >> 2) + (r & 3) >= lim_t) s[kb][r] = -INFINITY;
         }
+        // s holds S - m_use; mx is relative to the reference
         float mx = max3(s[0][0], s[1][0], s[0][1]);
 #pragma unroll
         for (int r = 1; r < 15; ++r) mx = max3(mx, s[1][r], s[0][r + 1]);
         mx = max_xhalf(fmaxf(mx, s[1][15]));
-        if (__builtin_amdgcn_ballot_w64(mx > m_run + 8.0f || (m_run == -INFINITY && mx > -INFINITY))) {
-            const float m_new = fmaxf(m_run, mx);
+        if (__builtin_amdgcn_ballot_w64(mx > 8.0f || (m_run == -INFINITY && mx > -INFINITY))) {
+            const float m_use_old = m_run == -INFINITY ? 0.f : m_run;  // nothing visible yet: the reference is 0
+            const float m_new = fmaxf(m_run, mx + m_use_old);
             const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);
+            const float m_use_new = m_new == -INFINITY ? 0.f : m_new;
+            const float delta = m_use_new - m_use_old;
             m_run = m_new;
             l_run *= alpha;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[kb][r] -= delta;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) negm[r] = -m_use_new;
         }
-        const float m_use = m_run == -INFINITY ? 0.f : m_run;  // nothing visible yet: p = 2^(-inf) = 0
         float sum = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float e0 = __builtin_amdgcn_exp2f(s[ks >> 1][8 * (ks & 1) + 2 * e] - m_use);
-                const float e1 = __builtin_amdgcn_exp2f(s[ks >> 1][8 * (ks & 1) + 2 * e + 1] - m_use);
+                const float e0 = __builtin_amdgcn_exp2f(s[ks >> 1][8 * (ks & 1) + 2 * e]);
+                const float e1 = __builtin_amdgcn_exp2f(s[ks >> 1][8 * (ks & 1) + 2 * e + 1]);
                 sum += e0 + e1;
                 pb[ks][e] = pack2_bf16(e0, e1);
             }
         l_run += sum;
     };
-    // End of tile t: K(t+1) and V(t+1) have landed (the younger group may stay in flight); the buffers of
-    // K(t) and V(t-1), which every wave has finished reading, are refilled with K(t+4) and V(t+3).
-    auto end_of_tile = [&](int t) __attribute__((always_inline)) {
+    // End of tile t (b = t % 4): K(t+1) and V(t+1) have landed (the younger group may stay in flight); the buffers
+    // of K(t) and V(t-1), which every wave has finished reading, are refilled with K(t+4) and V(t+3).
+    auto end_of_tile = [&](int b) __attribute__((always_inline)) {
         barrier_keep_one_group<2 * PASSES>();
-        issue_k(t & 3);        // K(t+4)
-        issue_v((t + 3) & 3);  // V(t+3)
+        issue_k(b);            // K(t+4)
+        issue_v((b + 3) & 3);  // V(t+3)
     };
 
-    // ---- prologue: everything issued so far has landed
-    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    // ---- prologue: K(0), V(0) and the Q fragments have landed.  The Q registers pass through the wait
+    // statement so that the compiler places no counter wait of its own after the loads below, which it
+    // cannot see (it would drain them).  Then the rest of the pipeline starts: K(1) V(1) K(2) V(2) K(3),
+    // in the order the tiles are needed, so that "all but the youngest four loads" covers K(t+1) and
+    // V(t+1) at the end of every tile t from the first one on.
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3]), "+v"(qf[4]), "+v"(qf[5]), "+v"(qf[6]), "+v"(qf[7])
+                 :
+                 : "memory");
     __syncthreads();
+    issue_k(1);
+    issue_v(1);
+    issue_k(2);
+    issue_v(2);
+    issue_k(3);
 
+    // The key loop is unrolled four times so that the LDS buffer of every access is a compile-time constant;
+    // the last n_tiles % 4 tiles take the buffer index at run time.
     if (wave < WAVES / 2) {
         // order A: S(t), softmax(t), PV(t)
-        for (int t = 0; t < n_tiles; ++t) {
-            s_phase();
-            next_k_buffer();
+        auto tile_a = [&](int t, int b) __attribute__((always_inline)) {
+            s_phase(b);
             softmax_phase(t);
-            pv_phase();
-            next_v_buffer();
-            end_of_tile(t);
+            pv_phase(b);
+            end_of_tile(b);
+        };
+        int t = 0;
+        for (; t + 4 <= n_tiles; t += 4) {
+            tile_a(t, 0);
+            tile_a(t + 1, 1);
+            tile_a(t + 2, 2);
+            tile_a(t + 3, 3);
         }
+        for (; t < n_tiles; ++t) tile_a(t, t & 3);
     } else {
         // order B: PV(t-1), S(t), softmax(t); the same number of barriers as order A
-        s_phase();
-        next_k_buffer();
+        auto tile_b = [&](int t, int b) __attribute__((always_inline)) {
+            pv_phase((b + 3) & 3);
+            s_phase(b);
+            softmax_phase(t);
+            end_of_tile(b);
+        };
+        s_phase(0);
         softmax_phase(0);
         end_of_tile(0);
-        for (int t = 1; t < n_tiles; ++t) {
-            pv_phase();
-            next_v_buffer();
-            s_phase();
-            next_k_buffer();
-            softmax_phase(t);
-            end_of_tile(t);
+        int t = 1;
+        for (; t + 4 <= n_tiles; t += 4) {
+            tile_b(t, 1);
+            tile_b(t + 1, 2);
+            tile_b(t + 2, 3);
+            tile_b(t + 3, 0);
         }
-        pv_phase();
+        for (; t < n_tiles; ++t) tile_b(t, t & 3);
+        pv_phase((n_tiles - 1) & 3);
     }
     __builtin_amdgcn_s_waitcnt(kWaitVm0);  // the loads of the tiles past the end must land before LDS is released
 
