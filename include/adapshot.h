@@ -146,7 +146,12 @@ adapshot_status adapshot_assemble_batched(adapshot_ctx* ctx, adapshot_cache* cac
 /* One attention problem of a batch: rows of q (t_q tokens at positions q_pos0 + j) over slots [0, n_ctx)
  * of caches[cache_index] plus their own tokens, as in adapshot_query_attn.  Several items may use the
  * same cache with different n_ctx: probes over nested prefixes (tree-structured multi-probe of the
- * Probe-based Dynamic Evaluation section) need no re-assembly because a prefix keeps its positions. */
+ * Probe-based Dynamic Evaluation section) need no re-assembly because a prefix keeps its positions.
+ * For bf16 models with head_dim 128 the whole batch runs as three launches (rotation of all items' rows,
+ * one attention grid over all items, one combine grid): the context splits have one common length, so
+ * probes over nested prefixes of one cache read identical leading slices, and those workgroups are
+ * scheduled next to each other.  Other shapes run item by item.  The outputs of distinct items must not
+ * overlap; inputs may be shared between items. */
 typedef struct {
     const void* q;       /* DEVICE [t_q][n_q_heads][head_dim] */
     const void* k_self;  /* DEVICE [t_q][n_kv_heads][head_dim] */

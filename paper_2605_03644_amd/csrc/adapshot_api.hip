@@ -237,6 +237,7 @@ extern "C" void adapshot_destroy(adapshot_ctx* ctx) {
     ctx->part_o.release();
     ctx->part_ml.release();
     ctx->ent_part.release();
+    ctx->batch_tab.release();
     if (ctx->tab_lo) (void)hipFree(ctx->tab_lo);
     if (ctx->tab_hi) (void)hipFree(ctx->tab_hi);
     delete ctx;
@@ -553,6 +554,173 @@ static adapshot_status run_query_attn(adapshot_ctx* ctx, const adapshot_cache* c
     return ADAPSHOT_OK;
 }
 
+// All items of a batch in three launches: rotate every item's rows, one MFMA attention grid over the
+// work list of all (item, kv head, row tile, split) workgroups, one combine grid.  Items are validated
+// by the caller.  The context is cut into splits of one common length, chosen so that the whole batch
+// makes about two rounds of workgroups over the chip (long splits keep the partial traffic low, two
+// rounds even out items of different length); the work list is ordered longest first.
+static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_cache* caches, int32_t layer,
+                                            const adapshot_attn_item* items, int32_t n_items, hipStream_t stream) {
+    const adapshot_model_desc& d = ctx->desc;
+    const int g = d.n_q_heads / d.n_kv_heads;
+    const size_t esz = (size_t)ctx->elem_bytes;
+
+    // ---- split plan
+    int64_t tile_units = 0;
+    for (int32_t i = 0; i < n_items; ++i) {
+        const int64_t rows = (int64_t)items[i].t_q * g;
+        const int64_t units = d.n_kv_heads * ((rows + kAttnRowTile - 1) / kAttnRowTile);
+        tile_units += units * ((items[i].n_ctx + 63) / 64);
+    }
+    const int64_t target_wgs = (int64_t)ctx->n_cu * 2;
+    const int64_t split_tiles_common = std::max<int64_t>(8, (tile_units + target_wgs - 1) / target_wgs);
+
+    struct Plan {
+        int64_t rows, n_row_tiles, n_split, keys_per_split;
+        size_t q_off, k_off, po_off, pml_off;
+    };
+    std::vector<Plan> plan((size_t)n_items);
+    size_t q_bytes = 0, k_bytes = 0, po_bytes = 0, pml_bytes = 0;
+    int64_t n_attn = 0, n_comb = 0, n_rope = 0;
+    for (int32_t i = 0; i < n_items; ++i) {
+        const adapshot_attn_item& it = items[i];
+        Plan& pl = plan[(size_t)i];
+        pl.rows = (int64_t)it.t_q * g;
+        pl.n_row_tiles = (pl.rows + kAttnRowTile - 1) / kAttnRowTile;
+        const int64_t key_tiles = (it.n_ctx + 63) / 64;
+        pl.n_split = 0;
+        pl.keys_per_split = 64;
+        if (key_tiles > 0) {
+            int64_t st = split_tiles_common;
+            if ((key_tiles + st - 1) / st > 64) st = (key_tiles + 63) / 64;  // at most 64 context splits per item
+            pl.keys_per_split = st * 64;
+            pl.n_split = (it.n_ctx + pl.keys_per_split - 1) / pl.keys_per_split;
+        }
+        auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
+        pl.q_off = q_bytes;
+        q_bytes += up((size_t)it.t_q * d.n_q_heads * d.head_dim * esz);
+        pl.k_off = k_bytes;
+        k_bytes += up((size_t)it.t_q * d.n_kv_heads * d.head_dim * esz);
+        pl.po_off = po_bytes;
+        po_bytes += up((size_t)(pl.n_split + 1) * d.n_kv_heads * pl.rows * d.head_dim * sizeof(float));
+        pl.pml_off = pml_bytes;
+        pml_bytes += up((size_t)(pl.n_split + 1) * d.n_kv_heads * pl.rows * sizeof(float2));
+        n_attn += d.n_kv_heads * pl.n_row_tiles * (pl.n_split + 1);
+        n_comb += (d.n_kv_heads * pl.rows + 7) / 8;
+        n_rope += ((int64_t)it.t_q * (d.n_q_heads + d.n_kv_heads) * (d.head_dim / 2) + 255) / 256;
+    }
+    if (n_attn > INT32_MAX || n_comb > INT32_MAX || n_rope > INT32_MAX)
+        return fail(ctx, ADAPSHOT_EINVAL, "query_attn_batched: batch too large for one launch");
+
+    // ---- workspace and tables
+    hipError_t e = ctx->q_rot.reserve(q_bytes);
+    if (e == hipSuccess) e = ctx->k_rot.reserve(k_bytes);
+    if (e == hipSuccess) e = ctx->part_o.reserve(po_bytes);
+    if (e == hipSuccess) e = ctx->part_ml.reserve(pml_bytes);
+    const size_t items_bytes = (size_t)n_items * sizeof(AttnBatchItem);
+    const size_t attn_off = (items_bytes + 255) & ~(size_t)255;
+    const size_t comb_off = (attn_off + (size_t)n_attn * sizeof(AttnWork) + 255) & ~(size_t)255;
+    const size_t rope_off = (comb_off + (size_t)n_comb * sizeof(CombineWork) + 255) & ~(size_t)255;
+    const size_t tab_bytes = rope_off + (size_t)n_rope * sizeof(RopeWork);
+    if (e == hipSuccess) e = ctx->batch_tab.reserve(tab_bytes);
+    if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: workspace", e);
+    int slot = -1;
+    void* host = nullptr;
+    e = ctx->tile_ring.acquire(tab_bytes, &slot, &host);
+    if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: pinned tables", e);
+
+    AttnBatchItem* hit = (AttnBatchItem*)host;
+    AttnWork* haw = (AttnWork*)((char*)host + attn_off);
+    CombineWork* hcw = (CombineWork*)((char*)host + comb_off);
+    RopeWork* hrw = (RopeWork*)((char*)host + rope_off);
+    struct Key {
+        int64_t tiles;
+        int32_t cache;
+        AttnWork w;
+    };
+    std::vector<Key> keys;
+    keys.reserve((size_t)n_attn);
+    int64_t ic = 0, ir = 0;
+    for (int32_t i = 0; i < n_items; ++i) {
+        const adapshot_attn_item& it = items[i];
+        const adapshot_cache& c = caches[it.cache_index];
+        const Plan& pl = plan[(size_t)i];
+        AttnBatchItem& b = hit[i];
+        b.rope.q = it.q;
+        b.rope.k_self = it.k_self;
+        b.rope.q_rot = (char*)ctx->q_rot.p + pl.q_off;
+        b.rope.k_rot = (char*)ctx->k_rot.p + pl.k_off;
+        b.rope.tab_lo = ctx->tab_lo;
+        b.rope.tab_hi = ctx->tab_hi;
+        b.rope.q_pos0 = it.q_pos0;
+        b.rope.t_q = it.t_q;
+        b.rope.n_q_heads = d.n_q_heads;
+        b.rope.n_kv_heads = d.n_kv_heads;
+        b.rope.head_dim = d.head_dim;
+        b.rope.dtype = d.dtype;
+        b.rope.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
+        const int64_t layer_off = (int64_t)layer * c.capacity * ctx->row_bytes;
+        b.attn.k_cache = (const char*)c.k + layer_off;
+        b.attn.v_cache = (const char*)c.v + layer_off;
+        b.attn.q_rot = b.rope.q_rot;
+        b.attn.k_self_rot = b.rope.k_rot;
+        b.attn.v_self = it.v_self;
+        b.attn.part_o = (float*)((char*)ctx->part_o.p + pl.po_off);
+        b.attn.part_ml = (float2*)((char*)ctx->part_ml.p + pl.pml_off);
+        b.attn.out = it.out;
+        b.attn.n_ctx = it.n_ctx;
+        b.attn.keys_per_split = pl.keys_per_split;
+        b.attn.n_split = (int32_t)pl.n_split;
+        b.attn.t_q = it.t_q;
+        b.attn.n_q_heads = d.n_q_heads;
+        b.attn.n_kv_heads = d.n_kv_heads;
+        b.attn.head_dim = d.head_dim;
+        b.attn.dtype = d.dtype;
+        for (int64_t sp = 0; sp <= pl.n_split; ++sp) {
+            int64_t tiles;
+            if (sp == pl.n_split) tiles = (it.t_q + 63) / 64;
+            else tiles = (std::min<int64_t>(it.n_ctx, (sp + 1) * pl.keys_per_split) - sp * pl.keys_per_split + 63) / 64;
+            for (int64_t rt = 0; rt < pl.n_row_tiles; ++rt)
+                for (int32_t hk = 0; hk < d.n_kv_heads; ++hk)
+                    keys.push_back(Key{tiles, sp == pl.n_split ? -1 : it.cache_index, AttnWork{i, hk, (int32_t)rt, (int32_t)sp}});
+        }
+        const int64_t pairs = d.n_kv_heads * pl.rows;
+        for (int64_t p0 = 0; p0 < pairs; p0 += 8) hcw[ic++] = CombineWork{i, (int32_t)p0};
+        const int64_t rb = ((int64_t)it.t_q * (d.n_q_heads + d.n_kv_heads) * (d.head_dim / 2) + 255) / 256;
+        for (int64_t bk = 0; bk < rb; ++bk) hrw[ir++] = RopeWork{i, (int32_t)bk};
+    }
+    // Longest workgroups first.  Among equal lengths, the workgroups that read the same slice of the same
+    // cache (probes over nested prefixes of one ordering share their leading splits, because the split
+    // length is common) are adjacent, kv head fastest: they start together on the XCD that serves that head
+    // and the later ones find the slice in its L2 -- the shared prefix of a probe tree is fetched once.
+    std::stable_sort(keys.begin(), keys.end(), [](const Key& a, const Key& b) {
+        if (a.tiles != b.tiles) return a.tiles > b.tiles;
+        if (a.cache != b.cache) return a.cache < b.cache;
+        if (a.cache >= 0 && a.w.split != b.w.split) return a.w.split < b.w.split;
+        return false;
+    });
+    for (size_t k = 0; k < keys.size(); ++k) haw[k] = keys[k].w;
+
+    e = hipMemcpyAsync(ctx->batch_tab.p, host, tab_bytes, hipMemcpyHostToDevice, stream);
+    if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: table copy", e);
+    e = ctx->tile_ring.mark_in_use(slot, stream);
+    if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: event record", e);
+    const AttnBatchItem* dit = (const AttnBatchItem*)ctx->batch_tab.p;
+    const AttnWork* daw = (const AttnWork*)((const char*)ctx->batch_tab.p + attn_off);
+    const CombineWork* dcw = (const CombineWork*)((const char*)ctx->batch_tab.p + comb_off);
+    const RopeWork* drw = (const RopeWork*)((const char*)ctx->batch_tab.p + rope_off);
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ROPE_ROWS, stream,
+                     [&] { return launch_rope_rows_batched(dit, drw, (int)n_rope, d.dtype, stream); });
+    if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: rope launch", e);
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream,
+                     [&] { return launch_attn_mfma_batched(dit, daw, (int)n_attn, stream); });
+    if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: attention launch", e);
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream,
+                     [&] { return launch_attn_combine_batched(dit, dcw, (int)n_comb, d.dtype, stream); });
+    if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: combine launch", e);
+    return ADAPSHOT_OK;
+}
+
 extern "C" adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot_cache* cache, int32_t layer,
                                                int64_t n_ctx, const void* q, const void* k_self,
                                                const void* v_self, int32_t t_q, int64_t q_pos0, void* out,
@@ -580,11 +748,16 @@ extern "C" adapshot_status adapshot_query_attn_batched(adapshot_ctx* ctx, const 
                                               it.t_q, it.q_pos0, it.out);
         if (st != ADAPSHOT_OK) return st;
     }
-    for (int32_t i = 0; i < n_items; ++i) {
-        const adapshot_attn_item& it = items[i];
-        adapshot_status st = run_query_attn(ctx, &caches[it.cache_index], layer, it.n_ctx, it.q, it.k_self, it.v_self,
-                                            it.t_q, it.q_pos0, it.out, (hipStream_t)hip_stream);
+    if (n_items > 0 && attn_mfma_supported(ctx->desc)) {
+        adapshot_status st = run_query_attn_batch(ctx, caches, layer, items, n_items, (hipStream_t)hip_stream);
         if (st != ADAPSHOT_OK) return st;
+    } else {
+        for (int32_t i = 0; i < n_items; ++i) {
+            const adapshot_attn_item& it = items[i];
+            adapshot_status st = run_query_attn(ctx, &caches[it.cache_index], layer, it.n_ctx, it.q, it.k_self,
+                                                it.v_self, it.t_q, it.q_pos0, it.out, (hipStream_t)hip_stream);
+            if (st != ADAPSHOT_OK) return st;
+        }
     }
     ctx->last_error.clear();
     return ADAPSHOT_OK;

@@ -114,6 +114,29 @@ hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream);
 bool attn_mfma_supported(const adapshot_model_desc& d);
 hipError_t launch_attn_combine(const AttnParams& p, hipStream_t stream);
 
+// ---- a batch of attention problems in three launches (rotate, attend, combine) -------------
+// The tables live in device memory for the duration of the launches; every workgroup reads its own
+// entry.  The probes of one query over nested prefixes of one cache, the queries of a decode step and
+// the queries of a probe sweep are all such batches (Probe-based Dynamic Evaluation).
+struct AttnBatchItem {
+    RopeRowsParams rope;
+    AttnParams attn;
+};
+struct AttnWork {  // one workgroup of the batched MFMA kernel
+    int32_t item, hk, row_tile, split;
+};
+struct CombineWork {  // one workgroup of the batched combine kernel: 8 (kv head, row) pairs from pair0 on
+    int32_t item, pair0;
+};
+struct RopeWork {  // one workgroup of the batched rotation kernel: 256 rotation pairs from pair0 on
+    int32_t item, block;
+};
+hipError_t launch_rope_rows_batched(const AttnBatchItem* items, const RopeWork* work, int n_work, int dtype,
+                                    hipStream_t stream);
+hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, hipStream_t stream);
+hipError_t launch_attn_combine_batched(const AttnBatchItem* items, const CombineWork* work, int n_work, int dtype,
+                                       hipStream_t stream);
+
 // ---- entropy ------------------------------------------------------------------------
 struct EntropyParams {
     const float* logits;
@@ -179,7 +202,7 @@ struct adapshot_ctx {
     float2* tab_hi = nullptr;
     // scratch
     adapshot::PinnedRing tile_ring;
-    adapshot::DevBuf q_rot, k_rot, part_o, part_ml, ent_part;
+    adapshot::DevBuf q_rot, k_rot, part_o, part_ml, ent_part, batch_tab;
     adapshot::Profiler prof;
     int n_cu = 256;
     std::string last_error;

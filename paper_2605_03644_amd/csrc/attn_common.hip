@@ -32,11 +32,11 @@ __device__ __forceinline__ void store_elem(void* base, int64_t i, float v) {
 // ---- rope_rows ----------------------------------------------------------------------
 // One thread per rotation pair.  Rows 0..t_q*h_q-1 are query rows, the rest self-key rows.
 template <int DTYPE>
-__global__ __launch_bounds__(256) void rope_rows_kernel(RopeRowsParams p) {
+__device__ __forceinline__ void rope_rows_block(const RopeRowsParams& p, int64_t block) {
     const int half = p.head_dim >> 1;
     const int64_t n_q = (int64_t)p.t_q * p.n_q_heads;
     const int64_t n_k = (int64_t)p.t_q * p.n_kv_heads;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t idx = block * 256 + threadIdx.x;
     if (idx >= (n_q + n_k) * half) return;
     const int64_t row = idx / half;
     const int i = (int)(idx - row * half);
@@ -57,6 +57,17 @@ __global__ __launch_bounds__(256) void rope_rows_kernel(RopeRowsParams p) {
     store_elem<DTYPE>(dst, o + half, (x2 * c + x1 * s) * sc);
 }
 
+template <int DTYPE>
+__global__ __launch_bounds__(256) void rope_rows_kernel(RopeRowsParams p) {
+    rope_rows_block<DTYPE>(p, blockIdx.x);
+}
+
+template <int DTYPE>
+__global__ __launch_bounds__(256) void rope_rows_batched_kernel(const AttnBatchItem* items, const RopeWork* work) {
+    const RopeWork w = work[blockIdx.x];
+    rope_rows_block<DTYPE>(items[w.item].rope, w.block);
+}
+
 hipError_t launch_rope_rows(const RopeRowsParams& p, hipStream_t stream) {
     const int64_t n = (int64_t)p.t_q * (p.n_q_heads + p.n_kv_heads) * (p.head_dim / 2);
     const unsigned blocks = (unsigned)((n + 255) / 256);
@@ -64,6 +75,16 @@ hipError_t launch_rope_rows(const RopeRowsParams& p, hipStream_t stream) {
         hipLaunchKernelGGL(rope_rows_kernel<ADAPSHOT_BF16>, dim3(blocks), dim3(256), 0, stream, p);
     else
         hipLaunchKernelGGL(rope_rows_kernel<ADAPSHOT_F32>, dim3(blocks), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_rope_rows_batched(const AttnBatchItem* items, const RopeWork* work, int n_work, int dtype,
+                                    hipStream_t stream) {
+    if (n_work <= 0) return hipSuccess;
+    if (dtype == ADAPSHOT_BF16)
+        hipLaunchKernelGGL(rope_rows_batched_kernel<ADAPSHOT_BF16>, dim3((unsigned)n_work), dim3(256), 0, stream, items, work);
+    else
+        hipLaunchKernelGGL(rope_rows_batched_kernel<ADAPSHOT_F32>, dim3((unsigned)n_work), dim3(256), 0, stream, items, work);
     return hipGetLastError();
 }
 
@@ -161,13 +182,13 @@ hipError_t launch_attn_generic(const AttnParams& p, hipStream_t stream) {
 // dimension per lane; the partial rows of 8 splits are requested together before any is used.  The
 // self split always holds at least one visible key, so the denominator is > 0.
 template <int DTYPE>
-__global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
+__device__ __forceinline__ void attn_combine_block(const AttnParams& p, int64_t pair0) {
     constexpr int SB = 8;  // splits in flight
     const int d = p.head_dim;
     const int g = p.n_q_heads / p.n_kv_heads;
     const int64_t rows = (int64_t)p.t_q * g;
     const int64_t n_pairs = rows * p.n_kv_heads;
-    const int64_t pair = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);
+    const int64_t pair = pair0 + (threadIdx.x >> 5);
     if (pair >= n_pairs) return;
     const int c = threadIdx.x & 31;
     const int hk = (int)(pair / rows);
@@ -229,6 +250,17 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
     }
 }
 
+template <int DTYPE>
+__global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
+    attn_combine_block<DTYPE>(p, (int64_t)blockIdx.x * 8);
+}
+
+template <int DTYPE>
+__global__ __launch_bounds__(256) void attn_combine_batched_kernel(const AttnBatchItem* items, const CombineWork* work) {
+    const CombineWork w = work[blockIdx.x];
+    attn_combine_block<DTYPE>(items[w.item].attn, w.pair0);
+}
+
 hipError_t launch_attn_combine(const AttnParams& p, hipStream_t stream) {
     const int g = p.n_q_heads / p.n_kv_heads;
     const int64_t n_pairs = (int64_t)p.n_kv_heads * p.t_q * g;
@@ -237,6 +269,16 @@ hipError_t launch_attn_combine(const AttnParams& p, hipStream_t stream) {
         hipLaunchKernelGGL(attn_combine_kernel<ADAPSHOT_BF16>, grid, dim3(256), 0, stream, p);
     else
         hipLaunchKernelGGL(attn_combine_kernel<ADAPSHOT_F32>, grid, dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_combine_batched(const AttnBatchItem* items, const CombineWork* work, int n_work, int dtype,
+                                       hipStream_t stream) {
+    if (n_work <= 0) return hipSuccess;
+    if (dtype == ADAPSHOT_BF16)
+        hipLaunchKernelGGL(attn_combine_batched_kernel<ADAPSHOT_BF16>, dim3((unsigned)n_work), dim3(256), 0, stream, items, work);
+    else
+        hipLaunchKernelGGL(attn_combine_batched_kernel<ADAPSHOT_F32>, dim3((unsigned)n_work), dim3(256), 0, stream, items, work);
     return hipGetLastError();
 }
 

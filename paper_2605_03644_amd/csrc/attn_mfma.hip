@@ -120,9 +120,23 @@ __device__ __forceinline__ void barrier_keep_one_group() {
         asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// WAVES wavefronts, each owning NR blocks of 32 rows for the whole key loop.
-template <int WAVES, int NR>
-__global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int n_row_tiles) {
+// A wave-uniform record from device memory into scalar registers.
+template <typename T>
+__device__ __forceinline__ T load_uniform(const T* ptr) {
+    static_assert(sizeof(T) % 4 == 0, "whole dwords");
+    T out;
+    const unsigned* src = (const unsigned*)ptr;
+    unsigned* dst = (unsigned*)&out;
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(T) / 4); ++i) dst[i] = __builtin_amdgcn_readfirstlane(src[i]);
+    return out;
+}
+
+// WAVES wavefronts, each owning NR blocks of 32 rows for the whole key loop.  BATCHED: the workgroup takes
+// its problem and its (kv head, row tile, split) from the work list instead of the launch arguments.
+template <int WAVES, int NR, bool BATCHED>
+__global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg, int n_row_tiles_arg,
+                                                               const AttnBatchItem* items, const AttnWork* work) {
     constexpr int PASSES = (kTileKeys * 16) / (WAVES * 64);  // 1 KB blocks of a tile per wavefront
     static_assert(PASSES * WAVES * 64 == kTileKeys * 16, "tile must divide over the threads");
     static_assert(WAVES * NR * 32 == kAttnRowTile && NR == 1, "row tile");
@@ -135,12 +149,23 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int
     const int l32 = lane & 31;
     const int hh = lane >> 5;
 
-    // blockIdx.x -> (kv head fastest: workgroups round-robin over the 8 XCDs, so with 8 kv heads every
-    // XCD's L2 sees the K/V of one head only), row tile, split
-    const int hk = blockIdx.x % p.n_kv_heads;
-    const int rest = blockIdx.x / p.n_kv_heads;
-    const int row_tile = rest % n_row_tiles;
-    const int split = rest / n_row_tiles;
+    AttnParams p;
+    int hk, row_tile, split;
+    if (BATCHED) {
+        const AttnWork w = load_uniform(work + blockIdx.x);
+        p = load_uniform(&items[w.item].attn);
+        hk = w.hk;
+        row_tile = w.row_tile;
+        split = w.split;
+    } else {
+        // blockIdx.x -> (kv head fastest: workgroups round-robin over the 8 XCDs, so with 8 kv heads every
+        // XCD's L2 sees the K/V of one head only), row tile, split
+        p = p_arg;
+        hk = blockIdx.x % p.n_kv_heads;
+        const int rest = blockIdx.x / p.n_kv_heads;
+        row_tile = rest % n_row_tiles_arg;
+        split = rest / n_row_tiles_arg;
+    }
     const bool self = split == p.n_split;
 
     const int g = p.n_q_heads / p.n_kv_heads;
@@ -402,7 +427,12 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p, int
 
     // The key loop is unrolled four times so that the LDS buffer of every access is a compile-time constant;
     // the last n_tiles % 4 tiles take the buffer index at run time.
-    if (wave < WAVES / 2) {
+    // A wavefront whose 32 rows all lie past the last query row (a decode step has fewer rows than one
+    // wavefront owns) only moves tiles and keeps the barriers.
+    const bool wave_idle = row_tile * kAttnRowTile + wave * NR * 32 >= rows;
+    if (wave_idle) {
+        for (int t = 0; t < n_tiles; ++t) end_of_tile(t & 3);
+    } else if (wave < WAVES / 2) {
         // order A: S(t), softmax(t), PV(t)
         auto tile_a = [&](int t, int b) __attribute__((always_inline)) {
             s_phase(b);
@@ -462,8 +492,16 @@ hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream) {
     const int rows = p.t_q * g;
     const int n_row_tiles = (rows + kAttnRowTile - 1) / kAttnRowTile;
     const unsigned blocks = (unsigned)(p.n_kv_heads * n_row_tiles * (p.n_split + 1));
-    hipLaunchKernelGGL((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves)>), dim3(blocks),
-                       dim3(kAttnWaves * 64), 0, stream, p, n_row_tiles);
+    hipLaunchKernelGGL((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false>), dim3(blocks),
+                       dim3(kAttnWaves * 64), 0, stream, p, n_row_tiles, (const AttnBatchItem*)nullptr,
+                       (const AttnWork*)nullptr);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, hipStream_t stream) {
+    if (n_work <= 0) return hipSuccess;
+    hipLaunchKernelGGL((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), true>), dim3((unsigned)n_work),
+                       dim3(kAttnWaves * 64), 0, stream, AttnParams{}, 0, items, work);
     return hipGetLastError();
 }
 
