@@ -61,6 +61,10 @@ def lib() -> ctypes.CDLL:
                                                  f64, i64, vp, i64, vp]
         L.adapshot_oracle_entropy.restype = None
         L.adapshot_oracle_entropy.argtypes = [vp, i64, i32, i32, vp]
+        L.adapshot_oracle_entropy_subset.restype = None
+        L.adapshot_oracle_entropy_subset.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp]
+        L.adapshot_oracle_pick_shots.restype = i32
+        L.adapshot_oracle_pick_shots.argtypes = [vp, vp, i32, f64]
         _lib = L
     return _lib
 
@@ -184,3 +188,28 @@ def entropy(logits: np.ndarray) -> np.ndarray:
     out = np.empty(rows, np.float64)
     lib().adapshot_oracle_entropy(_p(logits), logits.strides[0] // 4, rows, vocab, _p(out))
     return out
+
+
+ENTROPY_FULL_P, ENTROPY_RENORMALISED = 0, 1
+
+
+def entropy_subset(logits: np.ndarray, ids, mode: int) -> np.ndarray:
+    """Eq. (entropy) summed over the answer tokens `ids` only; mode ENTROPY_FULL_P or ENTROPY_RENORMALISED."""
+    if logits.dtype != np.float32 or logits.ndim != 2 or logits.strides[1] != 4:
+        raise TypeError("logits must be float32 [rows, vocab] with a contiguous vocab axis")
+    rows, vocab = logits.shape
+    ids = _chk(np.asarray(ids, dtype=np.int32), np.int32)
+    if ids.ndim != 1 or len(set(ids.tolist())) != ids.size or ids.min() < 0 or ids.max() >= vocab:
+        raise ValueError("ids must be distinct token indices inside the vocabulary")
+    out = np.empty(rows, np.float64)
+    lib().adapshot_oracle_entropy_subset(_p(logits), logits.strides[0] // 4, rows, vocab, _p(ids), ids.size, int(mode), _p(out))
+    return out
+
+
+def pick_shots(h, counts, tau: float) -> int:
+    """Smallest candidate count whose probe entropy is <= tau, or -1."""
+    h = _chk(np.asarray(h, dtype=np.float64), np.float64)
+    counts = _chk(np.asarray(counts, dtype=np.int32), np.int32)
+    if h.shape != counts.shape or h.ndim != 1:
+        raise ValueError("h and counts must be 1-D of equal length")
+    return int(lib().adapshot_oracle_pick_shots(_p(h), _p(counts), h.size, float(tau)))

@@ -28,6 +28,11 @@
  *   entropy   -- Eq. (entropy), H = -sum p log p, here over the whole vocabulary
  *                of one output distribution, natural log.
  *   rot_rows  -- rot applied row by row with stored input/output (decode-step append).
+ *   entropy_subset -- Eq. (entropy) as printed: the sum runs over a set C of answer
+ *                tokens only (Yes / No), in two readings of p (see the function).
+ *   pick_shots -- the stopping rule of the probe iteration: the smallest candidate
+ *                shot count whose probe entropy is <= tau (Probe-based Dynamic
+ *                Evaluation; parallel multi-probe selects the minimum passing count).
  *
  * Parity pins for every function live in tests/test_oracle_*.py; none of the
  * functions below is "parity unpinned".
@@ -325,4 +330,73 @@ void adapshot_oracle_entropy(const float* logits, int64_t row_stride, int32_t n_
         }
         entropy_out[r] = log(s) - t / s;
     }
+}
+
+/* ---- Eq. (entropy) over a set C of answer tokens ------------------------------------ */
+
+/* H = -sum_{c in C} p_c ln p_c.
+ * mode 0: p_c is the probability of token c under the softmax over the WHOLE vocabulary
+ *         (the sum simply leaves the other tokens' terms out; it can reach 2/e for |C| = 2,
+ *         which is what the values above ln 2 printed in the case study need);
+ * mode 1: p is renormalised over C, p_c = e^{z_c} / sum_{c' in C} e^{z_c'} (a proper
+ *         |C|-class entropy, at most ln |C|).
+ * ids are distinct token indices in [0, vocab).  A row holding a NaN, +infinity or only
+ * -infinity yields NaN; in mode 1 a row whose C-logits are all -infinity yields NaN too. */
+void adapshot_oracle_entropy_subset(const float* logits, int64_t row_stride, int32_t n_rows,
+                                    int32_t vocab, const int32_t* ids, int32_t n_ids, int32_t mode,
+                                    double* entropy_out) {
+    for (int32_t r = 0; r < n_rows; ++r) {
+        const float* z = logits + (int64_t)r * row_stride;
+        double m = -INFINITY;
+        int bad = (vocab <= 0);
+        for (int32_t v = 0; v < vocab; ++v) {
+            double zv = (double)z[v];
+            if (isnan(zv) || zv == INFINITY) bad = 1;
+            if (zv > m) m = zv;
+        }
+        if (bad || m == -INFINITY) {
+            entropy_out[r] = NAN;
+            continue;
+        }
+        double h = 0.0;
+        if (mode == 0) {
+            double s = 0.0;
+            for (int32_t v = 0; v < vocab; ++v) s += exp((double)z[v] - m);
+            const double lse = m + log(s);
+            for (int32_t c = 0; c < n_ids; ++c) {
+                const double lp = (double)z[ids[c]] - lse; /* ln p_c */
+                const double pc = exp(lp);
+                if (pc > 0.0) h -= pc * lp;
+            }
+        } else {
+            double mc = -INFINITY;
+            for (int32_t c = 0; c < n_ids; ++c)
+                if ((double)z[ids[c]] > mc) mc = (double)z[ids[c]];
+            if (mc == -INFINITY) {
+                entropy_out[r] = NAN;
+                continue;
+            }
+            double s = 0.0;
+            for (int32_t c = 0; c < n_ids; ++c) s += exp((double)z[ids[c]] - mc);
+            const double lse = mc + log(s);
+            for (int32_t c = 0; c < n_ids; ++c) {
+                const double lp = (double)z[ids[c]] - lse;
+                const double pc = exp(lp);
+                if (pc > 0.0) h -= pc * lp;
+            }
+        }
+        entropy_out[r] = h;
+    }
+}
+
+/* ---- stopping rule of the probe iteration ----------------------------------------- */
+
+/* counts[i] shots gave probe entropy h[i].  A candidate passes when h[i] <= tau; the
+ * answer is the smallest passing count, or -1 when none passes (the caller then probes
+ * larger counts).  A NaN entropy never passes. */
+int32_t adapshot_oracle_pick_shots(const double* h, const int32_t* counts, int32_t n, double tau) {
+    int32_t best = -1;
+    for (int32_t i = 0; i < n; ++i)
+        if (h[i] <= tau && (best < 0 || counts[i] < best)) best = counts[i];
+    return best;
 }

@@ -436,3 +436,103 @@ def test_entropy_gaussian_logits_statistic(oracle_mod):
     z = wl.make_logits(w, "cpu", n_rows=8).numpy()
     h = oracle_mod.entropy(z)
     assert abs(h.mean() - (math.log(w.vocab) - 1.0)) < 0.05
+
+
+# ---- Eq. (entropy) over the answer tokens, and the stopping rule -------------------------------
+
+def _case_study():
+    rounds, tau, picked = {}, None, None
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "case_study_probe_rounds.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        a = line.split()
+        if a[0] == "tau":
+            tau, picked = float(a[1]), int(a[2])
+        else:
+            rounds.setdefault(int(a[0]), []).append((int(a[1]), float(a[2])))
+    return rounds, tau, picked
+
+
+def test_pick_shots_reproduces_the_case_study(oracle_mod):
+    """The paper's worked example: no first-round probe passes, the second round selects 28 of {28, 32}."""
+    rounds, tau, picked = _case_study()
+    k1, h1 = zip(*rounds[1])
+    k2, h2 = zip(*rounds[2])
+    assert oracle_mod.pick_shots(h1, k1, tau) == -1
+    assert oracle_mod.pick_shots(h2, k2, tau) == picked == 28
+    # the order in which the candidates are listed does not matter, NaN never passes, equality passes
+    assert oracle_mod.pick_shots(h2[::-1], k2[::-1], tau) == 28
+    assert oracle_mod.pick_shots([float("nan"), 0.7], [4, 8], tau) == -1
+    assert oracle_mod.pick_shots([0.65, 0.1], [8, 16], 0.65) == 8
+
+
+def test_case_study_values_need_the_full_vocabulary_reading(oracle_mod):
+    """Two printed entropies exceed ln 2, the ceiling of a renormalised two-class entropy in nats; the sum of
+    two terms of a larger distribution can reach 2/e.  Both ceilings are attained by the oracle."""
+    rounds, _, _ = _case_study()
+    hs = [h for r in rounds.values() for _, h in r]
+    assert max(hs) > math.log(2.0) and max(hs) < 2.0 / math.e
+    V = 1000
+    # full-vocabulary reading: p_yes = p_no = 1/e, the rest spread evenly
+    z = np.full((1, V), math.log((1.0 - 2.0 / math.e) / (V - 2)), np.float32)
+    z[0, 3] = z[0, 7] = -1.0
+    h = oracle_mod.entropy_subset(z, [3, 7], oracle_mod.ENTROPY_FULL_P)[0]
+    assert abs(h - 2.0 / math.e) < 1e-6
+    # any other split of the same mass gives less
+    z2 = z.copy(); z2[0, 3] = math.log(0.5); z2[0, 7] = math.log(2.0 / math.e - 0.5)
+    assert oracle_mod.entropy_subset(z2, [3, 7], oracle_mod.ENTROPY_FULL_P)[0] < h
+    # renormalised reading: equal logits give ln 2 whatever the rest of the vocabulary holds
+    assert abs(oracle_mod.entropy_subset(z, [3, 7], oracle_mod.ENTROPY_RENORMALISED)[0] - math.log(2.0)) < 1e-12
+
+
+def test_entropy_subset_closed_forms(oracle_mod):
+    V = 512
+    rng = np.random.default_rng(11)
+    # uniform logits: p_c = 1/V, so the full-vocabulary reading gives |C| ln(V) / V
+    z = np.full((2, V), 0.37, np.float32)
+    ids = [5, 100, 511]
+    h = oracle_mod.entropy_subset(z, ids, oracle_mod.ENTROPY_FULL_P)
+    assert np.allclose(h, 3 * math.log(V) / V, rtol=1e-12)
+    assert np.allclose(oracle_mod.entropy_subset(z, ids, oracle_mod.ENTROPY_RENORMALISED), math.log(3), rtol=1e-12)
+    # C = whole vocabulary: both readings are the full entropy
+    z = (rng.standard_normal((3, 64)) * 2).astype(np.float32)
+    full = oracle_mod.entropy(z)
+    for mode in (oracle_mod.ENTROPY_FULL_P, oracle_mod.ENTROPY_RENORMALISED):
+        assert np.allclose(oracle_mod.entropy_subset(z, np.arange(64), mode), full, rtol=1e-12)
+    # all mass on C (the other logits are -inf): both readings equal the binary entropy of sigmoid(z_a - z_b)
+    z = np.full((1, V), -np.inf, np.float32)
+    z[0, 10], z[0, 20] = 1.25, -0.5
+    p = 1.0 / (1.0 + math.exp(-1.75))
+    hb = -(p * math.log(p) + (1 - p) * math.log(1 - p))
+    for mode in (oracle_mod.ENTROPY_FULL_P, oracle_mod.ENTROPY_RENORMALISED):
+        assert abs(oracle_mod.entropy_subset(z, [10, 20], mode)[0] - hb) < 1e-12
+
+
+def test_entropy_subset_against_library_softmax(oracle_mod):
+    """Random rows against scipy's log-softmax, written out term by term."""
+    from scipy.special import log_softmax
+    rng = np.random.default_rng(12)
+    z = (rng.standard_normal((5, 3000)) * math.sqrt(2.0)).astype(np.float32)
+    z[2, 17] = -np.inf
+    ids = np.array([17, 2999, 0, 1234], np.int32)
+    lp = log_softmax(z.astype(np.float64), axis=1)[:, ids]
+    with np.errstate(invalid="ignore"):
+        ref_full = -np.where(np.isfinite(lp), np.exp(lp) * lp, 0.0).sum(1)
+    lq = log_softmax(z.astype(np.float64)[:, ids], axis=1)
+    with np.errstate(invalid="ignore"):
+        ref_ren = -np.where(np.isfinite(lq), np.exp(lq) * lq, 0.0).sum(1)
+    assert np.allclose(oracle_mod.entropy_subset(z, ids, oracle_mod.ENTROPY_FULL_P), ref_full, rtol=1e-11, atol=1e-14)
+    assert np.allclose(oracle_mod.entropy_subset(z, ids, oracle_mod.ENTROPY_RENORMALISED), ref_ren, rtol=1e-11, atol=1e-14)
+
+
+def test_entropy_subset_degenerate_rows(oracle_mod):
+    z = np.zeros((4, 16), np.float32)
+    z[0, 3] = np.nan
+    z[1, 4] = np.inf
+    z[2, :] = -np.inf
+    z[3, [1, 2]] = -np.inf
+    for mode in (oracle_mod.ENTROPY_FULL_P, oracle_mod.ENTROPY_RENORMALISED):
+        h = oracle_mod.entropy_subset(z, [1, 2], mode)
+        assert np.isnan(h[0]) and np.isnan(h[1]) and np.isnan(h[2])
+    assert oracle_mod.entropy_subset(z, [1, 2], oracle_mod.ENTROPY_FULL_P)[3] == 0.0       # both terms vanish
+    assert np.isnan(oracle_mod.entropy_subset(z, [1, 2], oracle_mod.ENTROPY_RENORMALISED)[3])  # nothing to renormalise
