@@ -182,6 +182,27 @@ adapshot_status adapshot_probe_entropy(adapshot_ctx* ctx, const float* logits, i
                                        int32_t n_rows, int32_t vocab, float* entropy_out,
                                        void* hip_stream);
 
+/* Eq. (entropy) as printed: H = -sum_{c in C} p_c ln p_c over a set C of answer tokens (the probe's
+ * "Yes" / "No").  Two readings of p are offered, because the case study prints entropies above ln 2:
+ *   ADAPSHOT_ENTROPY_FULL_P        p_c is token c's probability under the softmax over the whole
+ *                                  vocabulary (the other tokens' terms are left out; at most |C|/e);
+ *   ADAPSHOT_ENTROPY_RENORMALISED  p is renormalised over C (at most ln |C|).
+ * token_ids: HOST, n_tokens distinct indices in [0, vocab), 1 <= n_tokens <= 16.  logits and entropy_out
+ * as in adapshot_probe_entropy.  A term with p_c = 0 contributes 0; a row with a NaN, a +inf or no
+ * finite logit gives NaN, and so does, in the renormalised reading, a row whose C-logits are all -inf. */
+typedef enum { ADAPSHOT_ENTROPY_FULL_P = 0, ADAPSHOT_ENTROPY_RENORMALISED = 1 } adapshot_entropy_mode;
+adapshot_status adapshot_probe_entropy_tokens(adapshot_ctx* ctx, const float* logits, int64_t row_stride,
+                                              int32_t n_rows, int32_t vocab, const int32_t* token_ids,
+                                              int32_t n_tokens, int32_t mode, float* entropy_out,
+                                              void* hip_stream);
+
+/* Stopping rule of the probe iteration (Probe-based Dynamic Evaluation): candidate i activates
+ * shot_counts[i] shots and its probe gave entropy[i]; it passes when entropy[i] <= tau.  *picked receives
+ * the smallest passing shot count, or -1 when no candidate passes (probe larger counts next).  A NaN
+ * entropy never passes.  Host arrays, host logic: nothing is launched.  ctx may be NULL. */
+adapshot_status adapshot_pick_shots(adapshot_ctx* ctx, const float* entropy, const int32_t* shot_counts,
+                                    int32_t n_candidates, float tau, int32_t* picked);
+
 /* Measurement aid (not a step of the method).  While enabled, every kernel the context
  * launches is bracketed by two HIP events on the launch stream.  adapshot_profile_read
  * waits for the recorded launches of one kernel kind, returns their summed duration in

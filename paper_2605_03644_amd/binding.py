@@ -27,7 +27,9 @@ KEYS_UNROTATED, KEYS_ROTATED_LOCAL = 0, 1
 EXPORTS = ["adapshot_create", "adapshot_destroy", "adapshot_last_error", "adapshot_version",
            "adapshot_pool_register", "adapshot_assemble", "adapshot_query_attn", "adapshot_probe_entropy",
            "adapshot_profile_enable", "adapshot_profile_read", "adapshot_assemble_batched",
-           "adapshot_query_attn_batched", "adapshot_decode_append"]
+           "adapshot_query_attn_batched", "adapshot_decode_append", "adapshot_probe_entropy_tokens",
+           "adapshot_pick_shots"]
+ENTROPY_FULL_P, ENTROPY_RENORMALISED = 0, 1
 KERNEL_KINDS = ["assemble_reencode", "rope_rows", "query_attn", "attn_combine", "entropy_chunk", "entropy_finish"]
 
 
@@ -84,6 +86,10 @@ def load_library() -> ctypes.CDLL:
     L.adapshot_query_attn.argtypes = [vp, ctypes.POINTER(CacheStruct), i32, i64, vp, vp, vp, i32, i64, vp, vp]
     L.adapshot_probe_entropy.restype = ctypes.c_int
     L.adapshot_probe_entropy.argtypes = [vp, vp, i64, i32, i32, vp, vp]
+    L.adapshot_probe_entropy_tokens.restype = ctypes.c_int
+    L.adapshot_probe_entropy_tokens.argtypes = [vp, vp, i64, i32, i32, vp, i32, i32, vp, vp]
+    L.adapshot_pick_shots.restype = ctypes.c_int
+    L.adapshot_pick_shots.argtypes = [vp, vp, vp, i32, ctypes.c_float, vp]
     L.adapshot_assemble_batched.restype = ctypes.c_int
     L.adapshot_assemble_batched.argtypes = [vp, ctypes.POINTER(CacheStruct), i32, vp, vp, vp, i64, vp]
     L.adapshot_query_attn_batched.restype = ctypes.c_int
@@ -214,6 +220,31 @@ class Context:
         self._check(self.lib.adapshot_probe_entropy(self._h, logits.data_ptr(), logits.stride(0) if rows > 1 else vocab,
                                                     rows, vocab, out.data_ptr(), _stream_ptr(stream)))
         return out
+
+    # -- adapshot_probe_entropy_tokens
+    def probe_entropy_tokens(self, logits: torch.Tensor, token_ids, mode: int = ENTROPY_FULL_P,
+                             out: Optional[torch.Tensor] = None,
+                             stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+        assert logits.dtype == torch.float32 and logits.dim() == 2 and logits.stride(1) == 1
+        rows, vocab = logits.shape
+        ids = np.ascontiguousarray(np.asarray(token_ids, dtype=np.int32))
+        if out is None:
+            out = torch.empty(rows, dtype=torch.float32, device=logits.device)
+        self._check(self.lib.adapshot_probe_entropy_tokens(
+            self._h, logits.data_ptr(), logits.stride(0) if rows > 1 else vocab, rows, vocab,
+            ids.ctypes.data_as(ctypes.c_void_p), int(ids.size), int(mode), out.data_ptr(), _stream_ptr(stream)))
+        return out
+
+    # -- adapshot_pick_shots (host logic)
+    def pick_shots(self, entropy, shot_counts, tau: float) -> int:
+        h = np.ascontiguousarray(np.asarray(entropy, dtype=np.float32))
+        k = np.ascontiguousarray(np.asarray(shot_counts, dtype=np.int32))
+        assert h.shape == k.shape and h.ndim == 1
+        picked = ctypes.c_int32(0)
+        self._check(self.lib.adapshot_pick_shots(self._h, h.ctypes.data_as(ctypes.c_void_p),
+                                                 k.ctypes.data_as(ctypes.c_void_p), int(h.size), float(tau),
+                                                 ctypes.byref(picked)))
+        return int(picked.value)
 
     # -- batched forms: the C structs of several caches are packed into one array for the call and the
     #    advanced lengths are copied back

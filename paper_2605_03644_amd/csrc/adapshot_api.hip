@@ -763,10 +763,10 @@ extern "C" adapshot_status adapshot_query_attn_batched(adapshot_ctx* ctx, const 
     return ADAPSHOT_OK;
 }
 
-extern "C" adapshot_status adapshot_probe_entropy(adapshot_ctx* ctx, const float* logits, int64_t row_stride,
-                                                  int32_t n_rows, int32_t vocab, float* entropy_out,
-                                                  void* hip_stream) {
-    if (!ctx) return ADAPSHOT_EINVAL;
+// Vocabulary-wide pass shared by both entropy entry points; `answer` selects the epilogue.
+static adapshot_status run_probe_entropy(adapshot_ctx* ctx, const float* logits, int64_t row_stride, int32_t n_rows,
+                                         int32_t vocab, const AnswerTokens* answer, float* entropy_out,
+                                         void* hip_stream) {
     if (n_rows < 0 || vocab < 1) return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy: n_rows < 0 or vocab < 1");
     if (n_rows == 0) {
         ctx->last_error.clear();
@@ -795,9 +795,56 @@ extern "C" adapshot_status adapshot_probe_entropy(adapshot_ctx* ctx, const float
     hipStream_t stream = (hipStream_t)hip_stream;
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ENTROPY_CHUNK, stream, [&] { return launch_entropy_chunk(p, stream); });
     if (e == hipSuccess)
-        e = timed_launch(ctx, ADAPSHOT_KERNEL_ENTROPY_FINISH, stream, [&] { return launch_entropy_finish(p, stream); });
+        e = timed_launch(ctx, ADAPSHOT_KERNEL_ENTROPY_FINISH, stream, [&] {
+            return answer ? launch_entropy_finish_tokens(p, *answer, stream) : launch_entropy_finish(p, stream);
+        });
     if (e != hipSuccess) return fail_hip(ctx, "probe_entropy: launch", e);
     ctx->last_error.clear();
+    return ADAPSHOT_OK;
+}
+
+extern "C" adapshot_status adapshot_probe_entropy(adapshot_ctx* ctx, const float* logits, int64_t row_stride,
+                                                  int32_t n_rows, int32_t vocab, float* entropy_out,
+                                                  void* hip_stream) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    return run_probe_entropy(ctx, logits, row_stride, n_rows, vocab, nullptr, entropy_out, hip_stream);
+}
+
+extern "C" adapshot_status adapshot_probe_entropy_tokens(adapshot_ctx* ctx, const float* logits, int64_t row_stride,
+                                                         int32_t n_rows, int32_t vocab, const int32_t* token_ids,
+                                                         int32_t n_tokens, int32_t mode, float* entropy_out,
+                                                         void* hip_stream) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    if (!token_ids || n_tokens < 1 || n_tokens > kMaxAnswerTokens)
+        return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy_tokens: need 1..%d answer tokens", kMaxAnswerTokens);
+    if (mode != ADAPSHOT_ENTROPY_FULL_P && mode != ADAPSHOT_ENTROPY_RENORMALISED)
+        return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy_tokens: unknown mode %d", mode);
+    AnswerTokens c;
+    c.n = n_tokens;
+    c.mode = mode;
+    for (int32_t i = 0; i < kMaxAnswerTokens; ++i) c.id[i] = 0;
+    for (int32_t i = 0; i < n_tokens; ++i) {
+        if (token_ids[i] < 0 || token_ids[i] >= vocab)
+            return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy_tokens: token id %d outside the vocabulary", token_ids[i]);
+        for (int32_t k = 0; k < i; ++k)
+            if (token_ids[k] == token_ids[i])
+                return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy_tokens: token id %d listed twice", token_ids[i]);
+        c.id[i] = token_ids[i];
+    }
+    return run_probe_entropy(ctx, logits, row_stride, n_rows, vocab, &c, entropy_out, hip_stream);
+}
+
+extern "C" adapshot_status adapshot_pick_shots(adapshot_ctx* ctx, const float* entropy, const int32_t* shot_counts,
+                                               int32_t n_candidates, float tau, int32_t* picked) {
+    if (!picked || n_candidates < 0 || (n_candidates > 0 && (!entropy || !shot_counts)))
+        return fail(ctx, ADAPSHOT_EINVAL, "pick_shots: null pointer or negative count");
+    int32_t best = -1;
+    for (int32_t i = 0; i < n_candidates; ++i) {
+        if (shot_counts[i] < 0) return fail(ctx, ADAPSHOT_EINVAL, "pick_shots: negative shot count");
+        if (entropy[i] <= tau && (best < 0 || shot_counts[i] < best)) best = shot_counts[i];
+    }
+    *picked = best;
+    if (ctx) ctx->last_error.clear();
     return ADAPSHOT_OK;
 }
 

@@ -147,6 +147,14 @@ struct EntropyParams {
 };
 hipError_t launch_entropy_chunk(const EntropyParams& p, hipStream_t stream);
 hipError_t launch_entropy_finish(const EntropyParams& p, hipStream_t stream);
+// Eq. (entropy) over a set C of answer tokens, from the same vocabulary-wide partials.
+constexpr int kMaxAnswerTokens = 16;
+struct AnswerTokens {
+    int32_t n;
+    int32_t mode;  // ADAPSHOT_ENTROPY_FULL_P / ADAPSHOT_ENTROPY_RENORMALISED
+    int32_t id[kMaxAnswerTokens];
+};
+hipError_t launch_entropy_finish_tokens(const EntropyParams& p, const AnswerTokens& c, hipStream_t stream);
 
 // ---- host-side helpers -----------------------------------------------------------------
 struct DevBuf {

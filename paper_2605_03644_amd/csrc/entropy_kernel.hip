@@ -153,6 +153,50 @@ __global__ __launch_bounds__(64) void entropy_finish_kernel(EntropyParams p) {
     }
 }
 
+// Eq. (entropy) as printed, summed over the answer tokens C only.  One wavefront per row merges the
+// chunk partials into the vocabulary-wide log-sum-exp; lane c < |C| then holds token c.
+//   full-p reading:      H = -sum_c p_c ln p_c,  ln p_c = z_c - lse
+//   renormalised reading: the same with the log-sum-exp taken over C
+// A term with p_c = 0 contributes 0.
+__global__ __launch_bounds__(64) void entropy_finish_tokens_kernel(EntropyParams p, AnswerTokens c) {
+    const int row = blockIdx.x;
+    const int lane = threadIdx.x;
+    Mst acc = {-INFINITY, 0.f, 0.f};
+    for (int k = lane; k < p.n_chunks; k += 64) {
+        const float* o = p.partials + ((int64_t)row * p.n_chunks + k) * 3;
+        Mst b = {o[0], o[1], o[2]};
+        acc = mst_merge(acc, b);
+    }
+    acc = mst_wave_reduce(acc);
+    const bool row_bad = acc.m == -INFINITY || acc.m == INFINITY || acc.s != acc.s;  // as in the full entropy
+    const float z = lane < c.n ? p.logits[(int64_t)row * p.row_stride + c.id[lane]] : -INFINITY;
+    float lse;
+    if (c.mode == ADAPSHOT_ENTROPY_FULL_P) {
+        lse = acc.m + logf(acc.s);
+    } else {
+        float mc = z;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mc = fmaxf(mc, __shfl_xor(mc, o, 64));
+        float sc = mc == -INFINITY ? 0.f : expf(z - mc);  // lanes past |C| hold -inf: 0
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sc += __shfl_xor(sc, o, 64);
+        lse = mc + logf(sc);  // all of C at -inf: -inf + (-inf) -> handled below
+        if (mc == -INFINITY) lse = NAN;
+    }
+    const float lp = z - lse;
+    const float pc = expf(lp);
+    float h = (lane < c.n && pc > 0.f) ? -pc * lp : 0.f;
+    if (lse != lse) h = NAN;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) h += __shfl_xor(h, o, 64);
+    if (lane == 0) p.out[row] = row_bad ? NAN : h;
+}
+
+hipError_t launch_entropy_finish_tokens(const EntropyParams& p, const AnswerTokens& c, hipStream_t stream) {
+    hipLaunchKernelGGL(entropy_finish_tokens_kernel, dim3((unsigned)p.n_rows), dim3(64), 0, stream, p, c);
+    return hipGetLastError();
+}
+
 hipError_t launch_entropy_chunk(const EntropyParams& p, hipStream_t stream) {
     dim3 grid((unsigned)p.n_chunks, (unsigned)p.n_rows);
     const bool vec = (((uintptr_t)p.logits & 15u) == 0) && (p.row_stride % 4 == 0);

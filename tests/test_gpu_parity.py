@@ -191,6 +191,71 @@ def test_entropy_closed_forms_and_degenerate_rows(ad, oracle_mod):
     ctx.close()
 
 
+@pytest.mark.parametrize("mode", [0, 1])
+def test_entropy_over_answer_tokens(ad, oracle_mod, mode):
+    """Eq. (entropy) over the probe's answer tokens, both readings, at the bench's logit shape and on small,
+    strided and degenerate rows, against the oracle."""
+    ctx = ad.Context(1, 4, 2, 64, 1.0e4, ad.F32)
+    w = wl.WORKLOADS["llama8b_1layer"]
+    z = wl.make_logits(w, "cuda")
+    z[:, 9891] += 9.0   # two likely answer tokens, as a probe prompt would make them
+    z[:, 2822] += 8.5 + torch.linspace(-3, 3, z.shape[0], device="cuda")
+    cases = [(z, [9891, 2822]), (z, [0, w.vocab - 1, 77, 9891]), (z[:5, :1001], [1000]),
+             (z[3:40, 1:4098], list(range(16)))]
+    for zz, ids in cases:
+        got = ctx.probe_entropy_tokens(zz, ids, mode).cpu().numpy().astype(np.float64)
+        want = oracle_mod.entropy_subset(zz.cpu().numpy(), ids, mode)
+        assert np.all(np.isfinite(want)) and float(np.abs(got - want).max()) < 1e-4, (ids, np.abs(got - want).max())
+    h2 = oracle_mod.entropy_subset(z.cpu().numpy(), [9891, 2822], mode)
+    assert h2.max() > 0.3 and h2.min() < h2.max() - 0.05      # the rows do differ: not a constant
+    # degenerate rows
+    d = torch.zeros(6, 4096, device="cuda")
+    d[0, 3] = float("nan"); d[1, 4] = float("inf"); d[2] = -float("inf")
+    d[3, [1, 2]] = -float("inf")
+    d[4, 1] = 50.0                  # all mass on one answer token: H = 0
+    d[5] = -float("inf"); d[5, 1] = 0.3; d[5, 2] = -0.9   # all mass on C: binary entropy in both readings
+    got = ctx.probe_entropy_tokens(d, [1, 2], mode).cpu().numpy().astype(np.float64)
+    want = oracle_mod.entropy_subset(d.cpu().numpy(), [1, 2], mode)
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    assert np.allclose(got[~np.isnan(got)], want[~np.isnan(want)], atol=1e-5)
+    assert np.isnan(got[:3]).all() and got[4] < 1e-6
+    # argument errors are reported before anything is launched
+    out = torch.full((6,), 7.0, device="cuda")
+    for bad in ([1, 1], [4096], [-1], [], list(range(17))):
+        with pytest.raises(ad.AdapshotError):
+            ctx.probe_entropy_tokens(d, bad, mode, out=out)
+    with pytest.raises(ad.AdapshotError):
+        ctx.probe_entropy_tokens(d, [1, 2], 5, out=out)
+    torch.cuda.synchronize()
+    assert float(out.min()) == 7.0
+    ctx.close()
+
+
+def test_adaptive_rounds_end_to_end(ad, oracle_mod):
+    """Two rounds of four parallel probes as in the case study: entropies of each round's logits on the GPU,
+    the stopping rule on the host, against the oracle doing the same."""
+    ctx = ad.Context(1, 4, 2, 64, 1.0e4, ad.F32)
+    g = torch.Generator(device="cuda"); g.manual_seed(77)
+    V, yes, no, tau = 32000, 9454, 2822, 0.65
+    rounds = [[4, 8, 12, 16], [20, 24, 28, 32]]
+    margins = [[0.2, -0.1, 0.05, 0.3], [0.1, 0.25, 1.4, 1.1]]   # confidence grows only late in the second round
+    picked = -1
+    for counts, mg in zip(rounds, margins):
+        z = torch.randn(4, V, device="cuda", generator=g) * 1.4142
+        z[:, yes] = 11.0 + torch.tensor(mg, device="cuda")
+        z[:, no] = 11.0
+        h = ctx.probe_entropy_tokens(z, [yes, no], ad.ENTROPY_FULL_P)
+        h_ref = oracle_mod.entropy_subset(z.cpu().numpy(), [yes, no], oracle_mod.ENTROPY_FULL_P)
+        assert float(np.abs(h.cpu().numpy() - h_ref).max()) < 1e-4
+        assert np.abs(h_ref - tau).min() > 1e-3     # no candidate sits on the threshold
+        picked = ctx.pick_shots(h.cpu().numpy(), counts, tau)
+        assert picked == oracle_mod.pick_shots(h_ref, counts, tau)
+        if picked >= 0:
+            break
+    assert picked == 28
+    ctx.close()
+
+
 # ------------------------------------------------------------------------------ attention
 
 def _attention_case(ad, oracle_mod, w, n_shots_sel, t_q, pos0=0, q_pos0=None, n_ctx=None, max_abs=2e-2,

@@ -50,3 +50,33 @@ def test_create_rejects_bad_descriptions_on_host(lib, field, value):
     assert lib.adapshot_create(ctypes.byref(d), ctypes.byref(h)) == binding.EINVAL
     assert not h.value
     assert lib.adapshot_create(None, ctypes.byref(h)) == binding.EINVAL
+
+
+def test_pick_shots_is_host_logic_and_matches_the_case_study(lib, oracle_mod):
+    """The stopping rule needs no device: called with a null context on the case study's printed entropies
+    (tests/golden/case_study_probe_rounds.txt) and on random candidates against the oracle's rule."""
+    import numpy as np
+    i32, f32 = ctypes.c_int32, ctypes.c_float
+
+    def pick(h, k, tau):
+        h = np.ascontiguousarray(h, np.float32)
+        k = np.ascontiguousarray(k, np.int32)
+        out = i32(7)
+        st = lib.adapshot_pick_shots(None, h.ctypes.data_as(ctypes.c_void_p), k.ctypes.data_as(ctypes.c_void_p),
+                                     i32(h.size), f32(tau), ctypes.byref(out))
+        assert st == 0
+        return out.value
+
+    assert pick([0.6731, 0.7023, 0.7044, 0.6671], [4, 8, 12, 16], 0.65) == -1
+    assert pick([0.6862, 0.6884, 0.6232, 0.6450], [20, 24, 28, 32], 0.65) == 28
+    assert pick([], [], 0.65) == -1
+    assert pick([float("nan"), 0.2], [4, 8], 0.65) == 8
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        n = int(rng.integers(1, 9))
+        h = rng.uniform(0.4, 0.9, n).astype(np.float32)
+        k = rng.permutation(64)[:n].astype(np.int32)
+        tau = float(rng.uniform(0.4, 0.9))
+        assert pick(h, k, tau) == oracle_mod.pick_shots(h.astype(np.float64), k, float(np.float32(tau)))
+    out = i32(0)
+    assert lib.adapshot_pick_shots(None, None, None, i32(3), f32(0.5), ctypes.byref(out)) != 0
