@@ -507,8 +507,8 @@ static adapshot_status run_query_attn(adapshot_ctx* ctx, const adapshot_cache* c
     hipError_t e = ctx->q_rot.reserve((size_t)t_q * d.n_q_heads * d.head_dim * esz);
     if (e == hipSuccess) e = ctx->k_rot.reserve((size_t)t_q * d.n_kv_heads * d.head_dim * esz);
     if (e == hipSuccess)
-        e = ctx->part_o.reserve((size_t)(n_split + 1) * d.n_kv_heads * rows * d.head_dim * sizeof(float));
-    if (e == hipSuccess) e = ctx->part_ml.reserve((size_t)(n_split + 1) * d.n_kv_heads * rows * sizeof(float2));
+        e = ctx->part_o.reserve((size_t)(n_split + 1) * d.n_kv_heads * rows * d.head_dim * (mfma ? 2 : 4));
+    if (e == hipSuccess) e = ctx->part_ml.reserve((size_t)(n_split + 1) * d.n_kv_heads * rows * sizeof(float4));
     if (e != hipSuccess) return fail_hip(ctx, "query_attn: workspace", e);
 
     RopeRowsParams rp;
@@ -535,8 +535,9 @@ static adapshot_status run_query_attn(adapshot_ctx* ctx, const adapshot_cache* c
     ap.q_rot = ctx->q_rot.p;
     ap.k_self_rot = ctx->k_rot.p;
     ap.v_self = v_self;
-    ap.part_o = (float*)ctx->part_o.p;
-    ap.part_ml = (float2*)ctx->part_ml.p;
+    ap.part_o = ctx->part_o.p;
+    ap.part_mlf = (float4*)ctx->part_ml.p;
+    ap.part_half = mfma ? 1 : 0;
     ap.out = out;
     ap.n_ctx = n_ctx;
     ap.keys_per_split = keys_per_split;
@@ -602,11 +603,11 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
         pl.k_off = k_bytes;
         k_bytes += up((size_t)it.t_q * d.n_kv_heads * d.head_dim * esz);
         pl.po_off = po_bytes;
-        po_bytes += up((size_t)(pl.n_split + 1) * d.n_kv_heads * pl.rows * d.head_dim * sizeof(float));
+        po_bytes += up((size_t)(pl.n_split + 1) * d.n_kv_heads * pl.rows * d.head_dim * 2);  // fp16 rows
         pl.pml_off = pml_bytes;
-        pml_bytes += up((size_t)(pl.n_split + 1) * d.n_kv_heads * pl.rows * sizeof(float2));
+        pml_bytes += up((size_t)(pl.n_split + 1) * d.n_kv_heads * pl.rows * sizeof(float4));
         n_attn += d.n_kv_heads * pl.n_row_tiles * (pl.n_split + 1);
-        n_comb += (d.n_kv_heads * pl.rows + 7) / 8;
+        n_comb += (d.n_kv_heads * pl.rows + 15) / 16;
         n_rope += ((int64_t)it.t_q * (d.n_q_heads + d.n_kv_heads) * (d.head_dim / 2) + 255) / 256;
     }
     if (n_attn > INT32_MAX || n_comb > INT32_MAX || n_rope > INT32_MAX)
@@ -665,8 +666,9 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
         b.attn.q_rot = b.rope.q_rot;
         b.attn.k_self_rot = b.rope.k_rot;
         b.attn.v_self = it.v_self;
-        b.attn.part_o = (float*)((char*)ctx->part_o.p + pl.po_off);
-        b.attn.part_ml = (float2*)((char*)ctx->part_ml.p + pl.pml_off);
+        b.attn.part_o = (char*)ctx->part_o.p + pl.po_off;
+        b.attn.part_mlf = (float4*)((char*)ctx->part_ml.p + pl.pml_off);
+        b.attn.part_half = 1;
         b.attn.out = it.out;
         b.attn.n_ctx = it.n_ctx;
         b.attn.keys_per_split = pl.keys_per_split;
@@ -685,7 +687,7 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
                     keys.push_back(Key{tiles, sp == pl.n_split ? -1 : it.cache_index, AttnWork{i, hk, (int32_t)rt, (int32_t)sp}});
         }
         const int64_t pairs = d.n_kv_heads * pl.rows;
-        for (int64_t p0 = 0; p0 < pairs; p0 += 8) hcw[ic++] = CombineWork{i, (int32_t)p0};
+        for (int64_t p0 = 0; p0 < pairs; p0 += 16) hcw[ic++] = CombineWork{i, (int32_t)p0};
         const int64_t rb = ((int64_t)it.t_q * (d.n_q_heads + d.n_kv_heads) * (d.head_dim / 2) + 255) / 256;
         for (int64_t bk = 0; bk < rb; ++bk) hrw[ir++] = RopeWork{i, (int32_t)bk};
     }

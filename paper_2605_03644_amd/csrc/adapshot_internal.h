@@ -100,8 +100,15 @@ struct AttnParams {
     const void* q_rot;
     const void* k_self_rot;
     const void* v_self;
-    float* part_o;   // [n_split+1][h_kv][rows][d]
-    float2* part_ml; // [n_split+1][h_kv][rows]  (running max in log2 units, sum)
+    // Partials, indexed [n_split+1][h_kv][rows]: part_mlf = (reference maximum in log2 units, row sum l,
+    // factor f, unused) and a row O' of d values with  sum_k p_k v_k = f * O'.
+    //   part_half = 0: O' is the unnormalised fp32 accumulator, f = 1 (generic kernel);
+    //   part_half = 1: O' = accumulator / (l * a) in fp16 with a = the largest |accumulator| / l of the row,
+    //                  so |O'| <= 1 whatever the range of V, and f = l * a (MFMA kernel): half the bytes,
+    //                  error per element <= 2^-11 of the row's largest partial output.
+    void* part_o;
+    float4* part_mlf;
+    int32_t part_half;
     void* out;       // [t_q][h_q][d]
     int64_t n_ctx;
     int64_t keys_per_split;
@@ -125,7 +132,7 @@ struct AttnBatchItem {
 struct AttnWork {  // one workgroup of the batched MFMA kernel
     int32_t item, hk, row_tile, split;
 };
-struct CombineWork {  // one workgroup of the batched combine kernel: 8 (kv head, row) pairs from pair0 on
+struct CombineWork {  // one workgroup of the batched combine kernel: 16 (kv head, row) pairs from pair0 on (fp16 partials)
     int32_t item, pair0;
 };
 struct RopeWork {  // one workgroup of the batched rotation kernel: 256 rotation pairs from pair0 on

@@ -6,6 +6,8 @@
 //                    row, head and split) used for fp32 models and for shapes the
 //                    MFMA kernel does not cover;
 //   attn_combine  -- merges the per-split (max, sum, unnormalised output) partials.
+#include <type_traits>
+
 #include "adapshot_internal.h"
 
 namespace adapshot {
@@ -159,11 +161,11 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(AttnParams p) {
         __syncthreads();
     }
     const int64_t pr = ((int64_t)split * p.n_kv_heads + hk) * rows + row;
-    if (lane == 0) p.part_ml[pr] = make_float2(m, l);
+    if (lane == 0) p.part_mlf[pr] = make_float4(m, l, 1.0f, 0.f);
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
         const int e = lane + 64 * c;
-        if (e < d) p.part_o[pr * d + e] = acc[c];
+        if (e < d) ((float*)p.part_o)[pr * d + e] = acc[c];
     }
 }
 
@@ -177,74 +179,103 @@ hipError_t launch_attn_generic(const AttnParams& p, hipStream_t stream) {
 }
 
 // ---- combine --------------------------------------------------------------------------------
-// out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s with M = max_s m_s.  HBM-bound on the partials.
-// A workgroup of 256 lanes handles 8 (kv head, row) pairs: 32 lanes per pair, one float4 of the head
-// dimension per lane; the partial rows of 8 splits are requested together before any is used.  The
-// self split always holds at least one visible key, so the denominator is > 0.
-template <int DTYPE>
+// out = sum_s 2^(m_s - M) f_s O'_s / sum_s 2^(m_s - M) l_s with M = max_s m_s.  HBM-bound on the partials.
+// Lanes per (kv head, row) pair and elements per lane and step: 32 x 4 fp32 or 16 x 8 fp16 (16 bytes per
+// lane either way), so a workgroup of 256 lanes handles 8 or 16 pairs; the partial rows of 8 splits are
+// requested together before any is used.  The self split always holds at least one visible key, so the
+// denominator is > 0.
+template <int DTYPE, bool HALF>
 __device__ __forceinline__ void attn_combine_block(const AttnParams& p, int64_t pair0) {
-    constexpr int SB = 8;  // splits in flight
+    typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+    typedef float f32x8 __attribute__((ext_vector_type(8)));
+    typedef typename std::conditional<HALF, f16x8, f32x4>::type ROW;  // 16 bytes of a partial row
+    constexpr int SB = HALF ? 16 : 8;   // splits in flight
+    constexpr int LP = HALF ? 16 : 32;  // lanes per pair
+    constexpr int EL = HALF ? 8 : 4;    // elements per lane and step
+    constexpr int NV = 2;               // steps: head_dim <= 2 * LP * EL = 256
     const int d = p.head_dim;
     const int g = p.n_q_heads / p.n_kv_heads;
     const int64_t rows = (int64_t)p.t_q * g;
     const int64_t n_pairs = rows * p.n_kv_heads;
-    const int64_t pair = pair0 + (threadIdx.x >> 5);
+    const int64_t pair = pair0 + (threadIdx.x / LP);
     if (pair >= n_pairs) return;
-    const int c = threadIdx.x & 31;
+    const int c = threadIdx.x % LP;
     const int hk = (int)(pair / rows);
     const int64_t row = pair - (int64_t)hk * rows;
     const int j = (int)(row / g);
     const int h = hk * g + (int)(row - (int64_t)j * g);
     const int ns = p.n_split + 1;
     const int64_t split_stride = (int64_t)p.n_kv_heads * rows;  // pairs per split
-    const float2* ml = p.part_ml + pair;
-    const float* po = p.part_o + pair * d;
+    const float4* mlf = p.part_mlf + pair;
+    const char* po = (const char*)p.part_o + pair * d * (HALF ? 2 : 4);
 
-    float M = -INFINITY;
-    for (int s0 = 0; s0 < ns; s0 += SB) {
-        float m[SB];
+    // One round of loads per SB splits: their (m, l, f) and their rows are requested together; the running
+    // maximum M is raised afterwards and what has been accumulated is rescaled (nothing yet: factor 0).
+    float M = -INFINITY, L = 0.f;
+    f32x8 acc[NV];
 #pragma unroll
-        for (int u = 0; u < SB; ++u) m[u] = s0 + u < ns ? ml[(s0 + u) * split_stride].x : -INFINITY;
+    for (int v = 0; v < NV; ++v)
 #pragma unroll
-        for (int u = 0; u < SB; ++u) M = fmaxf(M, m[u]);
-    }
-    float L = 0.f;
-    f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+        for (int i = 0; i < 8; ++i) acc[v][i] = 0.f;
     for (int s0 = 0; s0 < ns; s0 += SB) {
-        float2 mlv[SB];
-        f32x4 o[SB][2];
+        float4 mv[SB];
+        ROW o[SB][NV];
 #pragma unroll
         for (int u = 0; u < SB; ++u) {
             const bool on = s0 + u < ns;
             const int64_t so = (int64_t)(s0 + u) * split_stride;
-            mlv[u] = on ? ml[so] : make_float2(-INFINITY, 0.f);
+            mv[u] = on ? mlf[so] : make_float4(-INFINITY, 0.f, 0.f, 0.f);
 #pragma unroll
-            for (int v = 0; v < 2; ++v) {
-                const int e = 4 * (c + 32 * v);
-                o[u][v] = (on && e < d) ? __builtin_nontemporal_load((const f32x4*)(po + so * d + e))
-                                        : f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int v = 0; v < NV; ++v) {
+                const int e = EL * (c + LP * v);
+#pragma unroll
+                for (int i = 0; i < EL; ++i) o[u][v][i] = 0;
+                if (on && e < d) o[u][v] = __builtin_nontemporal_load((const ROW*)(po + (so * d + e) * (HALF ? 2 : 4)));
             }
         }
+        float cm = mv[0].x;
+#pragma unroll
+        for (int u = 1; u < SB; ++u) cm = fmaxf(cm, mv[u].x);
+        const float M_new = fmaxf(M, cm);
+        const float r = M == -INFINITY ? 0.f : exp2f(M - M_new);
+        M = M_new;
+        L *= r;
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+#pragma unroll
+            for (int i = 0; i < EL; ++i) acc[v][i] *= r;
 #pragma unroll
         for (int u = 0; u < SB; ++u) {
-            const float w = exp2f(mlv[u].x - M);  // empty or absent split: m = -inf -> 0
-            L += w * mlv[u].y;
-            acc[0] += w * o[u][0];
-            acc[1] += w * o[u][1];
+            const float w = mv[u].x == -INFINITY ? 0.f : exp2f(mv[u].x - M);  // empty or absent split: 0
+            L += w * mv[u].y;
+            const float wf = w * mv[u].z;
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+#pragma unroll
+                for (int i = 0; i < EL; ++i) acc[v][i] += wf * (float)o[u][v][i];
         }
     }
     const float inv = 1.0f / L;
 #pragma unroll
-    for (int v = 0; v < 2; ++v) {
-        const int e = 4 * (c + 32 * v);
+    for (int v = 0; v < NV; ++v) {
+        const int e = EL * (c + LP * v);
         if (e < d) {
             const int64_t oo = ((int64_t)j * p.n_q_heads + h) * d + e;
             if (DTYPE == ADAPSHOT_BF16) {
                 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-                const f32x4 r = acc[v] * inv;
-                *(bf16x4*)((unsigned short*)p.out + oo) = __builtin_convertvector(r, bf16x4);
+#pragma unroll
+                for (int q4 = 0; q4 < EL / 4; ++q4) {
+                    const f32x4 r = {acc[v][4 * q4] * inv, acc[v][4 * q4 + 1] * inv, acc[v][4 * q4 + 2] * inv,
+                                     acc[v][4 * q4 + 3] * inv};
+                    *(bf16x4*)((unsigned short*)p.out + oo + 4 * q4) = __builtin_convertvector(r, bf16x4);
+                }
             } else {
-                *(f32x4*)((float*)p.out + oo) = acc[v] * inv;
+#pragma unroll
+                for (int q4 = 0; q4 < EL / 4; ++q4) {
+                    const f32x4 r = {acc[v][4 * q4] * inv, acc[v][4 * q4 + 1] * inv, acc[v][4 * q4 + 2] * inv,
+                                     acc[v][4 * q4 + 3] * inv};
+                    *(f32x4*)((float*)p.out + oo + 4 * q4) = r;
+                }
             }
         }
     }
@@ -252,19 +283,23 @@ __device__ __forceinline__ void attn_combine_block(const AttnParams& p, int64_t 
 
 template <int DTYPE>
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
-    attn_combine_block<DTYPE>(p, (int64_t)blockIdx.x * 8);
+    if (p.part_half) attn_combine_block<DTYPE, true>(p, (int64_t)blockIdx.x * 16);
+    else attn_combine_block<DTYPE, false>(p, (int64_t)blockIdx.x * 8);
 }
 
 template <int DTYPE>
 __global__ __launch_bounds__(256) void attn_combine_batched_kernel(const AttnBatchItem* items, const CombineWork* work) {
     const CombineWork w = work[blockIdx.x];
-    attn_combine_block<DTYPE>(items[w.item].attn, w.pair0);
+    const AttnParams& p = items[w.item].attn;
+    if (p.part_half) attn_combine_block<DTYPE, true>(p, w.pair0);
+    else attn_combine_block<DTYPE, false>(p, w.pair0);
 }
 
 hipError_t launch_attn_combine(const AttnParams& p, hipStream_t stream) {
     const int g = p.n_q_heads / p.n_kv_heads;
     const int64_t n_pairs = (int64_t)p.n_kv_heads * p.t_q * g;
-    dim3 grid((unsigned)((n_pairs + 7) / 8));
+    const int per_wg = p.part_half ? 16 : 8;
+    dim3 grid((unsigned)((n_pairs + per_wg - 1) / per_wg));
     if (p.dtype == ADAPSHOT_BF16)
         hipLaunchKernelGGL(attn_combine_kernel<ADAPSHOT_BF16>, grid, dim3(256), 0, stream, p);
     else

@@ -471,18 +471,29 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     }
     __builtin_amdgcn_s_waitcnt(kWaitVm0);  // the loads of the tiles past the end must land before LDS is released
 
-    // ---- partials: unnormalised O (row-major [row][d]), reference maximum and row sum
+    // ---- partials: the row's reference maximum, sum l and factor f = l * a, and O' = O / (l * a) in fp16, where
+    // a is the largest |O| / l of the row: |O'| <= 1 whatever the range of V (row-major [row][d]).
     const float l_tot = sum_xhalf(l_run);
+    float amax = 0.f;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) amax = fmaxf(amax, fabsf(o[db][r]));
+    amax = max_xhalf(amax);
+    const bool some = amax > 0.f && amax < INFINITY;  // all-zero row (or overflow): plain scale 1
+    const float scale = some ? 1.0f / amax : 1.0f;
     if (row[0] < rows) {
+        typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
         const int64_t pr = ((int64_t)split * p.n_kv_heads + hk) * rows + row[0];
-        if (hh == 0) p.part_ml[pr] = make_float2(m_run, l_tot);
-        float* orow = p.part_o + pr * kD;
+        if (hh == 0) p.part_mlf[pr] = make_float4(m_run, l_tot, some ? amax : 1.0f, 0.f);
+        _Float16* orow = (_Float16*)p.part_o + pr * kD;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
-                f32x4 w = {o[db][4 * rq], o[db][4 * rq + 1], o[db][4 * rq + 2], o[db][4 * rq + 3]};
-                *(f32x4*)(orow + 32 * db + 8 * rq + 4 * hh) = w;
+                const f32x4 w = {o[db][4 * rq] * scale, o[db][4 * rq + 1] * scale, o[db][4 * rq + 2] * scale,
+                                 o[db][4 * rq + 3] * scale};
+                *(f16x4*)(orow + 32 * db + 8 * rq + 4 * hh) = __builtin_convertvector(w, f16x4);
             }
     }
 }
