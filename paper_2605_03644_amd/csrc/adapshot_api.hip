@@ -608,7 +608,7 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
         pml_bytes += up((size_t)(pl.n_split + 1) * d.n_kv_heads * pl.rows * sizeof(float4));
         n_attn += d.n_kv_heads * pl.n_row_tiles * (pl.n_split + 1);
         n_comb += (d.n_kv_heads * pl.rows + 15) / 16;
-        n_rope += ((int64_t)it.t_q * (d.n_q_heads + d.n_kv_heads) * (d.head_dim / 2) + 255) / 256;
+        n_rope += ((int64_t)it.t_q * (d.n_q_heads + d.n_kv_heads) * (d.head_dim / 2 / (16 / (int)esz)) + 255) / 256;
     }
     if (n_attn > INT32_MAX || n_comb > INT32_MAX || n_rope > INT32_MAX)
         return fail(ctx, ADAPSHOT_EINVAL, "query_attn_batched: batch too large for one launch");
@@ -688,7 +688,7 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
         }
         const int64_t pairs = d.n_kv_heads * pl.rows;
         for (int64_t p0 = 0; p0 < pairs; p0 += 16) hcw[ic++] = CombineWork{i, (int32_t)p0};
-        const int64_t rb = ((int64_t)it.t_q * (d.n_q_heads + d.n_kv_heads) * (d.head_dim / 2) + 255) / 256;
+        const int64_t rb = ((int64_t)it.t_q * (d.n_q_heads + d.n_kv_heads) * (d.head_dim / 2 / (16 / (int)esz)) + 255) / 256;
         for (int64_t bk = 0; bk < rb; ++bk) hrw[ir++] = RopeWork{i, (int32_t)bk};
     }
     // Longest workgroups first.  Among equal lengths, the workgroups that read the same slice of the same

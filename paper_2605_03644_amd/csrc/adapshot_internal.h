@@ -135,7 +135,7 @@ struct AttnWork {  // one workgroup of the batched MFMA kernel
 struct CombineWork {  // one workgroup of the batched combine kernel: 16 (kv head, row) pairs from pair0 on (fp16 partials)
     int32_t item, pair0;
 };
-struct RopeWork {  // one workgroup of the batched rotation kernel: 256 rotation pairs from pair0 on
+struct RopeWork {  // one workgroup of the batched rotation kernel: 256 chunk pairs from 256 * block on
     int32_t item, block;
 };
 hipError_t launch_rope_rows_batched(const AttnBatchItem* items, const RopeWork* work, int n_work, int dtype,

@@ -32,31 +32,65 @@ __device__ __forceinline__ void store_elem(void* base, int64_t i, float v) {
 }
 
 // ---- rope_rows ----------------------------------------------------------------------
-// One thread per rotation pair.  Rows 0..t_q*h_q-1 are query rows, the rest self-key rows.
+// One thread per pair of 16-byte chunks holding rotation partners (i, i + d/2), i = NP*ci .. NP*ci + NP - 1.
+// Rows 0..t_q*h_q-1 are query rows, the rest self-key rows.
 template <int DTYPE>
 __device__ __forceinline__ void rope_rows_block(const RopeRowsParams& p, int64_t block) {
+    constexpr int NP = DTYPE == ADAPSHOT_BF16 ? 8 : 4;  // pairs per chunk
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
     const int half = p.head_dim >> 1;
+    const int cpr = half / NP;  // chunk pairs per row
     const int64_t n_q = (int64_t)p.t_q * p.n_q_heads;
     const int64_t n_k = (int64_t)p.t_q * p.n_kv_heads;
     const int64_t idx = block * 256 + threadIdx.x;
-    if (idx >= (n_q + n_k) * half) return;
-    const int64_t row = idx / half;
-    const int i = (int)(idx - row * half);
+    if (idx >= (n_q + n_k) * cpr) return;
+    const int64_t row = idx / cpr;
+    const int ci = (int)(idx - row * cpr);
     const bool is_q = row < n_q;
     const int64_t r = is_q ? row : row - n_q;
     const int j = (int)(r / (is_q ? p.n_q_heads : p.n_kv_heads));
     const int64_t a = p.q_pos0 + j;
-    const float2 h = p.tab_hi[(a >> kRopeLoBits) * half + i];
-    const float2 l = p.tab_lo[(a & (kRopeLo - 1)) * half + i];
-    const float c = h.x * l.x - h.y * l.y;
-    const float s = h.y * l.x + h.x * l.y;
-    const void* src = is_q ? p.q : p.k_self;
-    void* dst = is_q ? p.q_rot : p.k_rot;
-    const int64_t o = r * p.head_dim + i;
-    const float x1 = load_elem<DTYPE>(src, o), x2 = load_elem<DTYPE>(src, o + half);
+    const float2* th = p.tab_hi + (a >> kRopeLoBits) * half + ci * NP;
+    const float2* tl = p.tab_lo + (a & (kRopeLo - 1)) * half + ci * NP;
+    const char* src = (const char*)(is_q ? p.q : p.k_self);
+    char* dst = (char*)(is_q ? p.q_rot : p.k_rot);
+    const int64_t o = (r * p.head_dim + ci * NP) * (DTYPE == ADAPSHOT_BF16 ? 2 : 4);
+    const int64_t ho = (int64_t)half * (DTYPE == ADAPSHOT_BF16 ? 2 : 4);
+    u32x4 x1 = *(const u32x4*)(src + o), x2 = *(const u32x4*)(src + o + ho);
     const float sc = is_q ? p.q_scale : 1.0f;
-    store_elem<DTYPE>(dst, o, (x1 * c - x2 * s) * sc);
-    store_elem<DTYPE>(dst, o + half, (x2 * c + x1 * s) * sc);
+    float y1[NP], y2[NP];
+#pragma unroll
+    for (int w = 0; w < NP; ++w) {
+        const float2 h = th[w], l = tl[w];
+        const float c = h.x * l.x - h.y * l.y;
+        const float s = h.y * l.x + h.x * l.y;
+        float a1, a2;
+        if (DTYPE == ADAPSHOT_BF16) {
+            const unsigned w1 = x1[w >> 1], w2 = x2[w >> 1];
+            a1 = (w & 1) ? __uint_as_float(w1 & 0xffff0000u) : __uint_as_float(w1 << 16);
+            a2 = (w & 1) ? __uint_as_float(w2 & 0xffff0000u) : __uint_as_float(w2 << 16);
+        } else {
+            a1 = __uint_as_float(x1[w]);
+            a2 = __uint_as_float(x2[w]);
+        }
+        y1[w] = (a1 * c - a2 * s) * sc;
+        y2[w] = (a2 * c + a1 * s) * sc;
+    }
+    if (DTYPE == ADAPSHOT_BF16) {
+#pragma unroll
+        for (int w = 0; w < NP; w += 2) {
+            x1[w >> 1] = (unsigned)f32_to_bf16_rne(y1[w]) | ((unsigned)f32_to_bf16_rne(y1[w + 1]) << 16);
+            x2[w >> 1] = (unsigned)f32_to_bf16_rne(y2[w]) | ((unsigned)f32_to_bf16_rne(y2[w + 1]) << 16);
+        }
+    } else {
+#pragma unroll
+        for (int w = 0; w < NP; ++w) {
+            x1[w] = __float_as_uint(y1[w]);
+            x2[w] = __float_as_uint(y2[w]);
+        }
+    }
+    *(u32x4*)(dst + o) = x1;
+    *(u32x4*)(dst + o + ho) = x2;
 }
 
 template <int DTYPE>
@@ -71,7 +105,8 @@ __global__ __launch_bounds__(256) void rope_rows_batched_kernel(const AttnBatchI
 }
 
 hipError_t launch_rope_rows(const RopeRowsParams& p, hipStream_t stream) {
-    const int64_t n = (int64_t)p.t_q * (p.n_q_heads + p.n_kv_heads) * (p.head_dim / 2);
+    const int np = p.dtype == ADAPSHOT_BF16 ? 8 : 4;
+    const int64_t n = (int64_t)p.t_q * (p.n_q_heads + p.n_kv_heads) * (p.head_dim / 2 / np);
     const unsigned blocks = (unsigned)((n + 255) / 256);
     if (p.dtype == ADAPSHOT_BF16)
         hipLaunchKernelGGL(rope_rows_kernel<ADAPSHOT_BF16>, dim3(blocks), dim3(256), 0, stream, p);
@@ -184,15 +219,13 @@ hipError_t launch_attn_generic(const AttnParams& p, hipStream_t stream) {
 // lane either way), so a workgroup of 256 lanes handles 8 or 16 pairs; the partial rows of 8 splits are
 // requested together before any is used.  The self split always holds at least one visible key, so the
 // denominator is > 0.
-template <int DTYPE, bool HALF>
-__device__ __forceinline__ void attn_combine_block(const AttnParams& p, int64_t pair0) {
+template <int DTYPE, bool HALF, int NV, int SB>
+__device__ __forceinline__ void attn_combine_rows(const AttnParams& p, int64_t pair0) {
     typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
     typedef float f32x8 __attribute__((ext_vector_type(8)));
     typedef typename std::conditional<HALF, f16x8, f32x4>::type ROW;  // 16 bytes of a partial row
-    constexpr int SB = HALF ? 16 : 8;   // splits in flight
     constexpr int LP = HALF ? 16 : 32;  // lanes per pair
-    constexpr int EL = HALF ? 8 : 4;    // elements per lane and step
-    constexpr int NV = 2;               // steps: head_dim <= 2 * LP * EL = 256
+    constexpr int EL = HALF ? 8 : 4;    // elements per lane and step; NV steps cover head_dim <= NV * 128
     const int d = p.head_dim;
     const int g = p.n_q_heads / p.n_kv_heads;
     const int64_t rows = (int64_t)p.t_q * g;
@@ -278,6 +311,19 @@ __device__ __forceinline__ void attn_combine_block(const AttnParams& p, int64_t 
                 }
             }
         }
+    }
+}
+
+// SB splits in flight: 8 when the problem has at most 8 partials per row, else 16 (fp16 rows) or 8 (fp32 rows).
+template <int DTYPE, bool HALF>
+__device__ __forceinline__ void attn_combine_block(const AttnParams& p, int64_t pair0) {
+    const bool wide = p.head_dim > 128;
+    if (HALF && p.n_split + 1 > 8) {
+        if (wide) attn_combine_rows<DTYPE, HALF, 2, 16>(p, pair0);
+        else attn_combine_rows<DTYPE, HALF, 1, 16>(p, pair0);
+    } else {
+        if (wide) attn_combine_rows<DTYPE, HALF, 2, 8>(p, pair0);
+        else attn_combine_rows<DTYPE, HALF, 1, 8>(p, pair0);
     }
 }
 
