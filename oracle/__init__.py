@@ -63,6 +63,9 @@ def lib() -> ctypes.CDLL:
         L.adapshot_oracle_entropy.argtypes = [vp, i64, i32, i32, vp]
         L.adapshot_oracle_entropy_subset.restype = None
         L.adapshot_oracle_entropy_subset.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp]
+        L.adapshot_oracle_rank_scores.restype = ctypes.c_int
+        L.adapshot_oracle_rank_scores.argtypes = [vp, ctypes.c_int, vp, i32, vp, i32, i32, i32, i32, f64,
+                                                  ctypes.c_int, i64, vp]
         L.adapshot_oracle_pick_shots.restype = i32
         L.adapshot_oracle_pick_shots.argtypes = [vp, vp, i32, f64]
         _lib = L
@@ -213,3 +216,22 @@ def pick_shots(h, counts, tau: float) -> int:
     if h.shape != counts.shape or h.ndim != 1:
         raise ValueError("h and counts must be 1-D of equal length")
     return int(lib().adapshot_oracle_pick_shots(_p(h), _p(counts), h.size, float(tau)))
+
+
+def rank_scores(k_pool: np.ndarray, dtype: str, shot_offsets, q: np.ndarray, base: float, key_state: int,
+                q_pos0: int = 0) -> np.ndarray:
+    """Relevance s^(i) of every shot (Eq. attention_score, softmax over the whole pool).
+    k_pool: one layer [tokens, H_kv, d]; q [T_q, H_q, d]; returns fp64 [n_shots]."""
+    st = _NP[dtype]
+    k_pool = _chk(k_pool, st); q = _chk(q, st)
+    off = _chk(np.asarray(shot_offsets, dtype=np.int64), np.int64)
+    t_q, h_q, d = q.shape
+    h_kv = k_pool.shape[1]
+    if k_pool.shape[0] < off[-1] or k_pool.shape[2] != d:
+        raise ValueError("pool layer smaller than the shot offsets say")
+    out = np.empty(off.size - 1, np.float64)
+    rc = lib().adapshot_oracle_rank_scores(_p(k_pool), _DT[dtype], _p(off), off.size - 1, _p(q), t_q, h_q, h_kv, d,
+                                           float(base), int(key_state), int(q_pos0), _p(out))
+    if rc != 0:
+        raise ValueError("oracle rank_scores: bad arguments")
+    return out

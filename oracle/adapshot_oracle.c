@@ -30,6 +30,8 @@
  *   rot_rows  -- rot applied row by row with stored input/output (decode-step append).
  *   entropy_subset -- Eq. (entropy) as printed: the sum runs over a set C of answer
  *                tokens only (Yes / No), in two readings of p (see the function).
+ *   rank_scores -- relevance of every pool shot to a query (Eq. attention_score), the
+ *                quantity the examples are sorted by; the reading is stated at the function.
  *   pick_shots -- the stopping rule of the probe iteration: the smallest candidate
  *                shot count whose probe entropy is <= tau (Probe-based Dynamic
  *                Evaluation; parallel multi-probe selects the minimum passing count).
@@ -399,4 +401,96 @@ int32_t adapshot_oracle_pick_shots(const double* h, const int32_t* counts, int32
     for (int32_t i = 0; i < n; ++i)
         if (h[i] <= tau && (best < 0 || counts[i] < best)) best = counts[i];
     return best;
+}
+
+/* ---- relevance of the pool's shots to a query (Eq. attention_score) ----------------- */
+
+/* The query attends to the cached keys of the pool at one representative layer; the
+ * attention a shot receives, averaged over heads, query tokens and the shot's tokens,
+ * is its relevance s^(i).
+ *
+ * Reading.  As printed, the softmax runs over one shot's own T_i keys; each row of that
+ * matrix sums to 1, so its average over all T_q x T_i entries is 1/T_i whatever the
+ * content.  Here the softmax runs over the keys of the WHOLE pool (the shots compete for
+ * the query's attention), and
+ *     s^(i) = 1 / (T_q H_q T_i) * sum_{j, h} sum_{u in shot i} A_h[j, u].
+ * Keys are what the cache holds: the key of token t of a shot encoded at its local
+ * position t (Eq. prefill; for an un-rotated pool it is rotated here and rounded to the
+ * storage type, as a cache would hold it).  The query is encoded on its own: token j at
+ * position q_pos0 + j.  Score = q~ . k~ / sqrt(d), kv head = h / (h_q / h_kv).
+ * k_pool: one layer [tokens][h_kv][d]; scores: [n_shots].  Returns 0, -1 on bad arguments. */
+int adapshot_oracle_rank_scores(const void* k_pool, int dtype, const int64_t* shot_offsets, int32_t n_shots,
+                                const void* q, int32_t t_q, int32_t h_q, int32_t h_kv, int32_t d, double base,
+                                int key_state, int64_t q_pos0, double* scores) {
+    if (h_kv <= 0 || h_q % h_kv != 0 || d <= 0 || d % 2 != 0 || d > 1024 || t_q <= 0 || n_shots <= 0) return -1;
+    const int32_t g = h_q / h_kv;
+    const int64_t n_tok = shot_offsets[n_shots];
+    if (n_tok <= 0) return -1;
+    double* kc = (double*)malloc(sizeof(double) * (size_t)n_tok * h_kv * d);
+    int32_t* shot_of = (int32_t*)malloc(sizeof(int32_t) * (size_t)n_tok);
+    if (!kc || !shot_of) {
+        free(kc);
+        free(shot_of);
+        return -1;
+    }
+    for (int32_t i = 0; i < n_shots; ++i)
+        for (int64_t u = shot_offsets[i]; u < shot_offsets[i + 1]; ++u) {
+            shot_of[u] = i;
+            for (int32_t hk = 0; hk < h_kv; ++hk) {
+                double x[1024], y[1024];
+                const int64_t o = (u * h_kv + hk) * d;
+                for (int32_t e = 0; e < d; ++e) x[e] = load_elem(k_pool, dtype, o + e);
+                if (key_state == ORC_KEYS_UNROTATED) {
+                    adapshot_oracle_rot(x, d, base, (double)(u - shot_offsets[i]), y);
+                    for (int32_t e = 0; e < d; ++e) /* what a cache of this storage type holds */
+                        kc[o + e] = dtype == ORC_BF16 ? bf16_bits_to_double(adapshot_oracle_double_to_bf16(y[e]))
+                                                      : (double)(float)y[e];
+                } else {
+                    for (int32_t e = 0; e < d; ++e) kc[o + e] = x[e];
+                }
+            }
+        }
+    for (int32_t i = 0; i < n_shots; ++i) scores[i] = 0.0;
+    const double inv_sqrt_d = 1.0 / sqrt((double)d);
+    int failed = 0;
+#pragma omp parallel
+    {
+        double* acc = (double*)calloc((size_t)n_shots, sizeof(double));
+        double* sc = (double*)malloc(sizeof(double) * (size_t)n_tok);
+        if (!acc || !sc) {
+#pragma omp atomic write
+            failed = 1;
+        } else {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t r = 0; r < (int64_t)t_q * h_q; ++r) {
+                const int32_t j = (int32_t)(r / h_q), h = (int32_t)(r % h_q), hk = h / g;
+                double x[1024], qr[1024];
+                for (int32_t e = 0; e < d; ++e) x[e] = load_elem(q, dtype, ((int64_t)j * h_q + h) * d + e);
+                adapshot_oracle_rot(x, d, base, (double)(q_pos0 + j), qr);
+                double mx = -INFINITY;
+                for (int64_t u = 0; u < n_tok; ++u) {
+                    const double* k = kc + (u * h_kv + hk) * d;
+                    double dot = 0.0;
+                    for (int32_t e = 0; e < d; ++e) dot += qr[e] * k[e];
+                    sc[u] = dot * inv_sqrt_d;
+                    if (sc[u] > mx) mx = sc[u];
+                }
+                double denom = 0.0;
+                for (int64_t u = 0; u < n_tok; ++u) {
+                    sc[u] = exp(sc[u] - mx);
+                    denom += sc[u];
+                }
+                for (int64_t u = 0; u < n_tok; ++u) acc[shot_of[u]] += sc[u] / denom;
+            }
+#pragma omp critical
+            for (int32_t i = 0; i < n_shots; ++i) scores[i] += acc[i];
+        }
+        free(acc);
+        free(sc);
+    }
+    for (int32_t i = 0; i < n_shots; ++i)
+        scores[i] /= (double)t_q * (double)h_q * (double)(shot_offsets[i + 1] - shot_offsets[i]);
+    free(kc);
+    free(shot_of);
+    return failed ? -1 : 0;
 }

@@ -536,3 +536,107 @@ def test_entropy_subset_degenerate_rows(oracle_mod):
         assert np.isnan(h[0]) and np.isnan(h[1]) and np.isnan(h[2])
     assert oracle_mod.entropy_subset(z, [1, 2], oracle_mod.ENTROPY_FULL_P)[3] == 0.0       # both terms vanish
     assert np.isnan(oracle_mod.entropy_subset(z, [1, 2], oracle_mod.ENTROPY_RENORMALISED)[3])  # nothing to renormalise
+
+
+# ---- Eq. (attention_score): relevance ranking over the pool ---------------------------------------
+
+def _rank_case(seed, n_shots=7, h_q=4, h_kv=2, d=16, t_q=5, lo=3, hi=9):
+    rng = np.random.default_rng(seed)
+    lens = rng.integers(lo, hi, n_shots, endpoint=True)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    k = rng.standard_normal((int(off[-1]), h_kv, d)).astype(np.float32)
+    q = rng.standard_normal((t_q, h_q, d)).astype(np.float32)
+    return off, k, q
+
+
+def _rank_numpy(off, k, q, base, rotate_keys, q_pos0):
+    """Eq. (attention_score) with the softmax over the whole pool, written with numpy and the closed-form
+    rotation matrix, not with the oracle's rot()."""
+    T, h_kv, d = k.shape
+    t_q, h_q, _ = q.shape
+    half = d // 2
+    theta = base ** (-2.0 * np.arange(half) / d)
+
+    def rot(x, a):  # x [..., d]
+        ang = a * theta
+        c, s = np.cos(ang), np.sin(ang)
+        x1, x2 = x[..., :half], x[..., half:]
+        return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], -1)
+
+    kk = k.astype(np.float64)
+    if rotate_keys:
+        kk = kk.copy()
+        for i in range(len(off) - 1):
+            for t in range(off[i + 1] - off[i]):
+                # the cache holds the rotated key in the storage type (fp32 here)
+                kk[off[i] + t] = rot(k[off[i] + t].astype(np.float64), float(t)).astype(np.float32).astype(np.float64)
+    g = h_q // h_kv
+    s = np.zeros(len(off) - 1)
+    for j in range(t_q):
+        for h in range(h_q):
+            qr = rot(q[j, h].astype(np.float64), float(q_pos0 + j))
+            sc = kk[:, h // g, :] @ qr / math.sqrt(d)
+            p = np.exp(sc - sc.max()); p /= p.sum()
+            s += np.add.reduceat(p, off[:-1])
+    return s / (t_q * h_q * np.diff(off))
+
+
+@pytest.mark.parametrize("key_state", [0, 1])
+def test_rank_scores_match_numpy_brute_force(oracle_mod, key_state):
+    off, k, q = _rank_case(21)
+    got = oracle_mod.rank_scores(k, "f32", off, q, 1.0e4, key_state, q_pos0=3)
+    want = _rank_numpy(off, k, q, 1.0e4, rotate_keys=(key_state == 0), q_pos0=3)
+    assert np.allclose(got, want, rtol=1e-10, atol=1e-15)
+    # the un-rotated pool ranked with local positions differs from treating the same numbers as already rotated
+    other = oracle_mod.rank_scores(k, "f32", off, q, 1.0e4, 1 - key_state, q_pos0=3)
+    assert np.abs(other - got).max() > 1e-4 * got.max()
+
+
+def test_rank_scores_invariants(oracle_mod):
+    off, k, q = _rank_case(22, n_shots=9)
+    s = oracle_mod.rank_scores(k, "f32", off, q, 1.0e4, 0)
+    lens = np.diff(off)
+    # all attention mass lands on some shot: sum_i T_i s_i = 1
+    assert abs(float((s * lens).sum()) - 1.0) < 1e-12
+    assert (s > 0).all()
+    # zero queries -> uniform attention -> every shot scores 1 / T_pool whatever its length
+    s0 = oracle_mod.rank_scores(k, "f32", off, np.zeros_like(q), 1.0e4, 0)
+    assert np.allclose(s0, 1.0 / off[-1], rtol=1e-12)
+    # the literal reading (softmax inside one shot) could not rank: it gives 1/T_i for any content
+    # (stated here as the reason for the reading; computed directly)
+    i = 3
+    sc = np.random.default_rng(0).standard_normal((5, lens[i]))
+    p = np.exp(sc) / np.exp(sc).sum(1, keepdims=True)
+    assert abs(p.mean() - 1.0 / lens[i]) < 1e-15
+
+
+def test_rank_scores_find_the_planted_shot(oracle_mod):
+    """A shot whose keys align with the query direction at the matching relative rotation must rank first."""
+    off, k, q = _rank_case(23, n_shots=8, d=16, t_q=4)
+    k = k * 0.1
+    # rotated-local pool: keys are used as stored, so plant the (rotated) query direction itself
+    half = 8
+    theta = 1.0e4 ** (-2.0 * np.arange(half) / 16)
+    def rot(x, a):
+        c, s = np.cos(a * theta), np.sin(a * theta)
+        return np.concatenate([x[:half] * c - x[half:] * s, x[half:] * c + x[:half] * s])
+    target = 5
+    for hk in range(k.shape[1]):
+        qbar = np.mean([rot(q[j, h].astype(np.float64), j) for j in range(q.shape[0]) for h in (2 * hk, 2 * hk + 1)], 0)
+        k[off[target]:off[target + 1], hk, :] = (3.0 * qbar).astype(np.float32)
+    s = oracle_mod.rank_scores(k, "f32", off, q, 1.0e4, 1)
+    assert int(np.argmax(s)) == target and s[target] > 2 * np.delete(s, target).max()
+
+
+def test_rank_scores_bf16_storage_rounds_rotated_keys(oracle_mod):
+    """bf16 pool, un-rotated: the rotated key is rounded to bf16 before the dot product (a cache holds bf16)."""
+    off, k, q = _rank_case(24)
+    kb = (k.view(np.uint32) >> 16).astype(np.uint16)          # truncate to bf16 bit patterns
+    qb = (q.view(np.uint32) >> 16).astype(np.uint16)
+    got = oracle_mod.rank_scores(kb, "bf16", off, qb, 1.0e4, 0)
+    kf = (kb.astype(np.uint32) << 16).view(np.float32)
+    qf = (qb.astype(np.uint32) << 16).view(np.float32)
+    # same computation with exact (unrounded) rotated keys differs slightly, with rounded ones it matches
+    exact = _rank_numpy(off, kf, qf, 1.0e4, rotate_keys=True, q_pos0=0)   # rounds rotated keys to fp32 only
+    assert 0 < np.abs(got - exact).max() < 2e-2 * exact.max()
+    assert abs(float((got * np.diff(off)).sum()) - 1.0) < 1e-12
