@@ -196,6 +196,27 @@ adapshot_status adapshot_probe_entropy_tokens(adapshot_ctx* ctx, const float* lo
                                               int32_t n_tokens, int32_t mode, float* entropy_out,
                                               void* hip_stream);
 
+/* Relevance of every shot of the pool to a query (Attention-based retrieval, Eq. attention_score): the
+ * query attends to the cached keys of ALL pool tokens at one representative layer, and a shot's score is
+ * the attention it receives averaged over heads, query tokens and the shot's tokens,
+ *     s_i = 1 / (t_q * n_q_heads * T_i) * sum_{j, h} sum_{u in shot i} A_h[j, u].
+ * The softmax runs over the whole pool (read inside one shot only, as printed, every row sums to 1 and
+ * the average is 1 / T_i whatever the content).  Keys are taken as a cache holds them: encoded at their
+ * position inside the shot (Eq. prefill); for a pool registered with ADAPSHOT_KEYS_UNROTATED the library
+ * builds that encoding of the layer once and keeps it, together with one more layer-sized buffer, until
+ * another layer is ranked, the pool is registered again or the context is destroyed.  The query is encoded
+ * on its own: token j at position q_pos0 + j.
+ * q: DEVICE [t_q][n_q_heads][head_dim] without rotation; scores_out: DEVICE fp32 [n_shots].
+ * bf16 models with head_dim 128 only (ESTATE otherwise); every shot must hold at least one token. */
+adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer, const void* q, int32_t t_q, int64_t q_pos0,
+                                    float* scores_out, void* hip_stream);
+
+/* The k most relevant shots, best first; equal scores keep the lower shot id first.  scores: HOST
+ * fp32 [n_shots] (a NaN is EINVAL), shot_ids_out: HOST int32 [k].  Host logic, nothing is launched;
+ * ctx may be NULL.  The result is what adapshot_assemble takes as shot_ids (with order = NULL). */
+adapshot_status adapshot_top_k(adapshot_ctx* ctx, const float* scores, int32_t n_shots, int32_t k,
+                               int32_t* shot_ids_out);
+
 /* Stopping rule of the probe iteration (Probe-based Dynamic Evaluation): candidate i activates
  * shot_counts[i] shots and its probe gave entropy[i]; it passes when entropy[i] <= tau.  *picked receives
  * the smallest passing shot count, or -1 when no candidate passes (probe larger counts next).  A NaN

@@ -28,7 +28,7 @@ EXPORTS = ["adapshot_create", "adapshot_destroy", "adapshot_last_error", "adapsh
            "adapshot_pool_register", "adapshot_assemble", "adapshot_query_attn", "adapshot_probe_entropy",
            "adapshot_profile_enable", "adapshot_profile_read", "adapshot_assemble_batched",
            "adapshot_query_attn_batched", "adapshot_decode_append", "adapshot_probe_entropy_tokens",
-           "adapshot_pick_shots"]
+           "adapshot_pick_shots", "adapshot_rank_shots", "adapshot_top_k"]
 ENTROPY_FULL_P, ENTROPY_RENORMALISED = 0, 1
 KERNEL_KINDS = ["assemble_reencode", "rope_rows", "query_attn", "attn_combine", "entropy_chunk", "entropy_finish"]
 
@@ -88,6 +88,10 @@ def load_library() -> ctypes.CDLL:
     L.adapshot_probe_entropy.argtypes = [vp, vp, i64, i32, i32, vp, vp]
     L.adapshot_probe_entropy_tokens.restype = ctypes.c_int
     L.adapshot_probe_entropy_tokens.argtypes = [vp, vp, i64, i32, i32, vp, i32, i32, vp, vp]
+    L.adapshot_rank_shots.restype = ctypes.c_int
+    L.adapshot_rank_shots.argtypes = [vp, i32, vp, i32, i64, vp, vp]
+    L.adapshot_top_k.restype = ctypes.c_int
+    L.adapshot_top_k.argtypes = [vp, vp, i32, i32, vp]
     L.adapshot_pick_shots.restype = ctypes.c_int
     L.adapshot_pick_shots.argtypes = [vp, vp, vp, i32, ctypes.c_float, vp]
     L.adapshot_assemble_batched.restype = ctypes.c_int
@@ -186,6 +190,7 @@ class Context:
         off = np.ascontiguousarray(shot_offsets, dtype=np.int64)
         assert k_pool.is_contiguous() and v_pool.is_contiguous() and k_pool.shape == v_pool.shape
         self._keep = [k_pool, v_pool]
+        self.n_shots = int(off.shape[0] - 1)
         self._check(self.lib.adapshot_pool_register(self._h, k_pool.data_ptr(), v_pool.data_ptr(),
                                                     off.ctypes.data, off.shape[0] - 1, k_pool.shape[1]))
 
@@ -234,6 +239,23 @@ class Context:
             self._h, logits.data_ptr(), logits.stride(0) if rows > 1 else vocab, rows, vocab,
             ids.ctypes.data_as(ctypes.c_void_p), int(ids.size), int(mode), out.data_ptr(), _stream_ptr(stream)))
         return out
+
+    # -- adapshot_rank_shots / adapshot_top_k
+    def rank_shots(self, layer: int, q: torch.Tensor, q_pos0: int = 0, out: Optional[torch.Tensor] = None,
+                   stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+        assert q.is_contiguous() and q.dim() == 3
+        if out is None:
+            out = torch.empty(self.n_shots, dtype=torch.float32, device=q.device)
+        self._check(self.lib.adapshot_rank_shots(self._h, int(layer), q.data_ptr(), int(q.shape[0]), int(q_pos0),
+                                                 out.data_ptr(), _stream_ptr(stream)))
+        return out
+
+    def top_k(self, scores, k: int) -> np.ndarray:
+        sc = np.ascontiguousarray(np.asarray(scores, dtype=np.float32))
+        ids = np.empty(int(k), np.int32)
+        self._check(self.lib.adapshot_top_k(self._h, sc.ctypes.data_as(ctypes.c_void_p), int(sc.size), int(k),
+                                            ids.ctypes.data_as(ctypes.c_void_p)))
+        return ids
 
     # -- adapshot_pick_shots (host logic)
     def pick_shots(self, entropy, shot_counts, tau: float) -> int:

@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libadapshot.so")
-SOURCES = ["adapshot_api.hip", "assemble_kernel.hip", "attn_common.hip", "attn_mfma.hip", "entropy_kernel.hip"]
+SOURCES = ["adapshot_api.hip", "assemble_kernel.hip", "attn_common.hip", "attn_mfma.hip", "entropy_kernel.hip",
+           "rank_kernel.hip"]
 
 
 def hipcc() -> str:

@@ -238,6 +238,13 @@ extern "C" void adapshot_destroy(adapshot_ctx* ctx) {
     ctx->part_ml.release();
     ctx->ent_part.release();
     ctx->batch_tab.release();
+    ctx->rank_k.release();
+    ctx->rank_v.release();
+    ctx->rank_tok.release();
+    ctx->rank_bounds.release();
+    ctx->rank_shot0.release();
+    ctx->rank_inv_len.release();
+    ctx->rank_w.release();
     if (ctx->tab_lo) (void)hipFree(ctx->tab_lo);
     if (ctx->tab_hi) (void)hipFree(ctx->tab_hi);
     delete ctx;
@@ -265,6 +272,7 @@ extern "C" adapshot_status adapshot_pool_register(adapshot_ctx* ctx, const void*
     ctx->shot_offsets.assign(shot_offsets, shot_offsets + n_shots + 1);
     ctx->n_shots = n_shots;
     ctx->pool_layer_stride_tokens = layer_stride_tokens;
+    ctx->rank_layer = -1;  // ranking state belongs to the previous pool
     ctx->last_error.clear();
     return ADAPSHOT_OK;
 }
@@ -538,6 +546,8 @@ static adapshot_status run_query_attn(adapshot_ctx* ctx, const adapshot_cache* c
     ap.part_o = ctx->part_o.p;
     ap.part_mlf = (float4*)ctx->part_ml.p;
     ap.part_half = mfma ? 1 : 0;
+    ap.no_self = 0;
+    ap.split_bounds = nullptr;
     ap.out = out;
     ap.n_ctx = n_ctx;
     ap.keys_per_split = keys_per_split;
@@ -669,6 +679,8 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
         b.attn.part_o = (char*)ctx->part_o.p + pl.po_off;
         b.attn.part_mlf = (float4*)((char*)ctx->part_ml.p + pl.pml_off);
         b.attn.part_half = 1;
+        b.attn.no_self = 0;
+        b.attn.split_bounds = nullptr;
         b.attn.out = it.out;
         b.attn.n_ctx = it.n_ctx;
         b.attn.keys_per_split = pl.keys_per_split;
@@ -834,6 +846,190 @@ extern "C" adapshot_status adapshot_probe_entropy_tokens(adapshot_ctx* ctx, cons
         c.id[i] = token_ids[i];
     }
     return run_probe_entropy(ctx, logits, row_stride, n_rows, vocab, &c, entropy_out, hip_stream);
+}
+
+// Ranking state of one pool layer: windows of consecutive shots (at most head_dim shots and about
+// total / (2 n_cu / n_kv_heads) keys each, so that one query makes a few rounds of workgroups), per-token
+// tables, the locally encoded keys (when the pool stores them un-rotated) and the one-hot rows.
+static adapshot_status rank_prepare(adapshot_ctx* ctx, int32_t layer, hipStream_t stream) {
+    const adapshot_model_desc& d = ctx->desc;
+    const int64_t n_tok = ctx->shot_offsets[(size_t)ctx->n_shots];
+    const int64_t target_windows = std::max<int64_t>(1, 2 * (int64_t)ctx->n_cu / d.n_kv_heads);
+    const int64_t keys_target = std::max<int64_t>(512, ((n_tok + target_windows - 1) / target_windows + 63) / 64 * 64);
+    std::vector<int64_t> bounds;
+    std::vector<int32_t> shot0;
+    std::vector<int32_t> tok((size_t)(2 * n_tok));  // [local index | column]
+    std::vector<float> inv_len((size_t)ctx->n_shots);
+    bounds.push_back(0);
+    shot0.push_back(0);
+    int64_t keys = 0;
+    int32_t first = 0;
+    for (int32_t i = 0; i < ctx->n_shots; ++i) {
+        const int64_t len = ctx->shot_offsets[(size_t)i + 1] - ctx->shot_offsets[(size_t)i];
+        if (i > first && (i - first >= d.head_dim || keys + len > keys_target)) {  // close the window before shot i
+            bounds.push_back(ctx->shot_offsets[(size_t)i]);
+            shot0.push_back(i);
+            first = i;
+            keys = 0;
+        }
+        keys += len;
+        inv_len[(size_t)i] = len > 0 ? 1.0f / (float)len : 0.f;
+        for (int64_t t = 0; t < len; ++t) {
+            tok[(size_t)(ctx->shot_offsets[(size_t)i] + t)] = (int32_t)t;
+            tok[(size_t)(n_tok + ctx->shot_offsets[(size_t)i] + t)] = i - first;
+        }
+    }
+    bounds.push_back(n_tok);
+    shot0.push_back(ctx->n_shots);
+    const int32_t n_split = (int32_t)bounds.size() - 1;
+
+    const size_t layer_bytes = (size_t)n_tok * ctx->row_bytes;
+    const bool rotate = d.key_state == ADAPSHOT_KEYS_UNROTATED;
+    hipError_t e = ctx->rank_v.reserve(layer_bytes);
+    if (e == hipSuccess && rotate) e = ctx->rank_k.reserve(layer_bytes);
+    if (e == hipSuccess) e = ctx->rank_tok.reserve(tok.size() * sizeof(int32_t));
+    if (e == hipSuccess) e = ctx->rank_bounds.reserve(bounds.size() * sizeof(int64_t));
+    if (e == hipSuccess) e = ctx->rank_shot0.reserve(shot0.size() * sizeof(int32_t));
+    if (e == hipSuccess) e = ctx->rank_inv_len.reserve(inv_len.size() * sizeof(float));
+    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: workspace", e);
+    // one-time tables: plain synchronous copies from pageable memory
+    e = hipMemcpy(ctx->rank_tok.p, tok.data(), tok.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(ctx->rank_bounds.p, bounds.data(), bounds.size() * sizeof(int64_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(ctx->rank_shot0.p, shot0.data(), shot0.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(ctx->rank_inv_len.p, inv_len.data(), inv_len.size() * sizeof(float), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: table copy", e);
+
+    RankPrepareParams rp;
+    rp.k_pool = (const char*)ctx->k_pool + (int64_t)layer * ctx->pool_layer_stride_tokens * ctx->row_bytes;
+    rp.k_out = rotate ? (char*)ctx->rank_k.p : nullptr;
+    rp.v_out = (char*)ctx->rank_v.p;
+    rp.tok_local = (const int32_t*)ctx->rank_tok.p;
+    rp.tok_col = (const int32_t*)ctx->rank_tok.p + n_tok;
+    rp.tab_lo = ctx->tab_lo;
+    rp.tab_hi = ctx->tab_hi;
+    rp.n_tok = n_tok;
+    rp.n_kv_heads = d.n_kv_heads;
+    rp.head_dim = d.head_dim;
+    e = launch_rank_prepare(rp, stream);
+    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: prepare launch", e);
+    ctx->rank_layer = layer;
+    ctx->rank_n_split = n_split;
+    return ADAPSHOT_OK;
+}
+
+extern "C" adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer, const void* q, int32_t t_q,
+                                               int64_t q_pos0, float* scores_out, void* hip_stream) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    const adapshot_model_desc& d = ctx->desc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (!ctx->k_pool) return fail(ctx, ADAPSHOT_ESTATE, "rank_shots: no pool registered");
+    if (!attn_mfma_supported(d))
+        return fail(ctx, ADAPSHOT_ESTATE, "rank_shots: needs a bf16 model with head_dim 128 (matrix-core kernel)");
+    if (layer < 0 || layer >= d.n_layers) return fail(ctx, ADAPSHOT_EINVAL, "rank_shots: layer out of range");
+    if (!q || !scores_out) return fail(ctx, ADAPSHOT_EINVAL, "rank_shots: null pointer");
+    if (!aligned16(q) || ((uintptr_t)scores_out & 3u)) return fail(ctx, ADAPSHOT_EINVAL, "rank_shots: q must be 16-byte aligned");
+    if (t_q < 1 || t_q > 65536) return fail(ctx, ADAPSHOT_EINVAL, "rank_shots: t_q must be in [1, 65536]");
+    if (q_pos0 < 0 || q_pos0 + t_q > ctx->max_position)
+        return fail(ctx, ADAPSHOT_ECAPACITY, "rank_shots: query positions exceed max_position");
+    const int64_t n_tok = ctx->shot_offsets[(size_t)ctx->n_shots];
+    if (ctx->n_shots < 1 || n_tok < 1) return fail(ctx, ADAPSHOT_ESTATE, "rank_shots: empty pool");
+    for (int32_t i = 0; i < ctx->n_shots; ++i) {
+        const int64_t len = ctx->shot_offsets[(size_t)i + 1] - ctx->shot_offsets[(size_t)i];
+        if (len < 1) return fail(ctx, ADAPSHOT_ESTATE, "rank_shots: shot %d is empty", i);
+        if (len > ctx->max_position) return fail(ctx, ADAPSHOT_ECAPACITY, "rank_shots: shot %d longer than max_position", i);
+    }
+    if (n_tok * ctx->row_bytes >= ((int64_t)1 << 32))
+        return fail(ctx, ADAPSHOT_ECAPACITY, "rank_shots: a pool layer of 4 GiB or more is not supported");
+    if (ctx->rank_layer != layer) {
+        adapshot_status st = rank_prepare(ctx, layer, stream);
+        if (st != ADAPSHOT_OK) return st;
+    }
+    const int g = d.n_q_heads / d.n_kv_heads;
+    const int64_t rows = (int64_t)t_q * g;
+    const int64_t n_pairs = rows * d.n_kv_heads;
+    const int32_t n_split = ctx->rank_n_split;
+    const size_t esz = (size_t)ctx->elem_bytes;
+    hipError_t e = ctx->q_rot.reserve((size_t)t_q * d.n_q_heads * d.head_dim * esz);
+    if (e == hipSuccess) e = ctx->part_o.reserve((size_t)n_split * n_pairs * d.head_dim * 2);
+    if (e == hipSuccess) e = ctx->part_ml.reserve((size_t)n_split * n_pairs * sizeof(float4));
+    if (e == hipSuccess) e = ctx->rank_w.reserve((size_t)n_split * n_pairs * sizeof(float));
+    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: workspace", e);
+
+    RopeRowsParams rp;
+    rp.q = q;
+    rp.k_self = nullptr;
+    rp.q_rot = ctx->q_rot.p;
+    rp.k_rot = nullptr;
+    rp.tab_lo = ctx->tab_lo;
+    rp.tab_hi = ctx->tab_hi;
+    rp.q_pos0 = q_pos0;
+    rp.t_q = t_q;
+    rp.n_q_heads = d.n_q_heads;
+    rp.n_kv_heads = d.n_kv_heads;
+    rp.head_dim = d.head_dim;
+    rp.dtype = d.dtype;
+    rp.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ROPE_ROWS, stream, [&] { return launch_rope_rows(rp, stream); });
+    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: rope launch", e);
+
+    AttnParams ap;
+    ap.k_cache = d.key_state == ADAPSHOT_KEYS_UNROTATED
+                     ? ctx->rank_k.p
+                     : (const void*)((const char*)ctx->k_pool + (int64_t)layer * ctx->pool_layer_stride_tokens * ctx->row_bytes);
+    ap.v_cache = ctx->rank_v.p;
+    ap.q_rot = ctx->q_rot.p;
+    ap.k_self_rot = nullptr;
+    ap.v_self = nullptr;
+    ap.part_o = ctx->part_o.p;
+    ap.part_mlf = (float4*)ctx->part_ml.p;
+    ap.part_half = 1;
+    ap.no_self = 1;
+    ap.split_bounds = (const int64_t*)ctx->rank_bounds.p;
+    ap.out = nullptr;
+    ap.n_ctx = n_tok;
+    ap.keys_per_split = 64;
+    ap.n_split = n_split;
+    ap.t_q = t_q;
+    ap.n_q_heads = d.n_q_heads;
+    ap.n_kv_heads = d.n_kv_heads;
+    ap.head_dim = d.head_dim;
+    ap.dtype = d.dtype;
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream, [&] { return launch_attn_mfma(ap, stream); });
+    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: attention launch", e);
+
+    RankReduceParams rr;
+    rr.part_o = ctx->part_o.p;
+    rr.part_mlf = (const float4*)ctx->part_ml.p;
+    rr.weights = (float*)ctx->rank_w.p;
+    rr.scores = scores_out;
+    rr.split_shot0 = (const int32_t*)ctx->rank_shot0.p;
+    rr.inv_len = (const float*)ctx->rank_inv_len.p;
+    rr.inv_rows = 1.0f / ((float)t_q * (float)d.n_q_heads);
+    rr.n_split = n_split;
+    rr.n_pairs = (int32_t)n_pairs;
+    rr.head_dim = d.head_dim;
+    rr.n_shots = ctx->n_shots;
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream, [&] { return launch_rank_reduce(rr, stream); });
+    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: reduce launch", e);
+    ctx->last_error.clear();
+    return ADAPSHOT_OK;
+}
+
+// Host logic: the k best shots by score, best first; equal scores keep the lower shot id first.
+extern "C" adapshot_status adapshot_top_k(adapshot_ctx* ctx, const float* scores, int32_t n_shots, int32_t k,
+                                          int32_t* shot_ids_out) {
+    if (n_shots < 0 || k < 0 || k > n_shots || (n_shots > 0 && !scores) || (k > 0 && !shot_ids_out))
+        return fail(ctx, ADAPSHOT_EINVAL, "top_k: bad arguments");
+    for (int32_t i = 0; i < n_shots; ++i)
+        if (scores[i] != scores[i]) return fail(ctx, ADAPSHOT_EINVAL, "top_k: score %d is NaN", i);
+    std::vector<int32_t> idx((size_t)n_shots);
+    for (int32_t i = 0; i < n_shots; ++i) idx[(size_t)i] = i;
+    std::partial_sort(idx.begin(), idx.begin() + k, idx.end(), [&](int32_t a, int32_t b) {
+        return scores[a] > scores[b] || (scores[a] == scores[b] && a < b);
+    });
+    for (int32_t i = 0; i < k; ++i) shot_ids_out[i] = idx[(size_t)i];
+    if (ctx) ctx->last_error.clear();
+    return ADAPSHOT_OK;
 }
 
 extern "C" adapshot_status adapshot_pick_shots(adapshot_ctx* ctx, const float* entropy, const int32_t* shot_counts,

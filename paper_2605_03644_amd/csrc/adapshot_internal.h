@@ -109,6 +109,10 @@ struct AttnParams {
     void* part_o;
     float4* part_mlf;
     int32_t part_half;
+    // Ranking over the pool (MFMA kernel only): context splits with explicit key bounds
+    // [split_bounds[s], split_bounds[s+1]) instead of equal lengths, and no self part.
+    int32_t no_self;
+    const int64_t* split_bounds;
     void* out;       // [t_q][h_q][d]
     int64_t n_ctx;
     int64_t keys_per_split;
@@ -143,6 +147,35 @@ hipError_t launch_rope_rows_batched(const AttnBatchItem* items, const RopeWork* 
 hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, hipStream_t stream);
 hipError_t launch_attn_combine_batched(const AttnBatchItem* items, const CombineWork* work, int n_work, int dtype,
                                        hipStream_t stream);
+
+// ---- relevance ranking over the pool (Eq. attention_score) ----------------------------------
+// The query attends over the locally encoded keys of ALL pool tokens at one layer with a one-hot "value"
+// row per token: column = the token's shot, counted from the first shot of its window of <= head_dim
+// consecutive shots.  A context split is one window, so the MFMA kernel's partial of (split, row) holds
+// the attention mass of every shot of that window; the two kernels below turn the partials into scores.
+struct RankPrepareParams {
+    const char* k_pool;      // one layer [tokens][h_kv][d], un-rotated
+    char* k_out;             // same layout, every key rotated to its position inside its shot; null: not needed
+    char* v_out;             // one-hot rows
+    const int32_t* tok_local;  // [tokens] index of the token inside its shot
+    const int32_t* tok_col;    // [tokens] shot index inside its window
+    const float2* tab_lo;
+    const float2* tab_hi;
+    int64_t n_tok;
+    int32_t n_kv_heads, head_dim;
+};
+hipError_t launch_rank_prepare(const RankPrepareParams& p, hipStream_t stream);
+struct RankReduceParams {
+    const void* part_o;       // [n_split][pairs][d] fp16
+    const float4* part_mlf;   // [n_split][pairs]
+    float* weights;           // [n_split][pairs] scratch
+    float* scores;            // [n_shots]
+    const int32_t* split_shot0;  // [n_split + 1] first shot of every window
+    const float* inv_len;     // [n_shots] 1 / T_i
+    float inv_rows;           // 1 / (t_q * n_q_heads)
+    int32_t n_split, n_pairs, head_dim, n_shots;
+};
+hipError_t launch_rank_reduce(const RankReduceParams& p, hipStream_t stream);
 
 // ---- entropy ------------------------------------------------------------------------
 struct EntropyParams {
@@ -218,6 +251,10 @@ struct adapshot_ctx {
     // scratch
     adapshot::PinnedRing tile_ring;
     adapshot::DevBuf q_rot, k_rot, part_o, part_ml, ent_part, batch_tab;
+    // ranking state of one pool layer, built on first use
+    int32_t rank_layer = -1;
+    int32_t rank_n_split = 0;
+    adapshot::DevBuf rank_k, rank_v, rank_tok, rank_bounds, rank_shot0, rank_inv_len, rank_w;
     adapshot::Profiler prof;
     int n_cu = 256;
     std::string last_error;

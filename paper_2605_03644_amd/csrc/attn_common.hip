@@ -41,7 +41,7 @@ __device__ __forceinline__ void rope_rows_block(const RopeRowsParams& p, int64_t
     const int half = p.head_dim >> 1;
     const int cpr = half / NP;  // chunk pairs per row
     const int64_t n_q = (int64_t)p.t_q * p.n_q_heads;
-    const int64_t n_k = (int64_t)p.t_q * p.n_kv_heads;
+    const int64_t n_k = p.k_self ? (int64_t)p.t_q * p.n_kv_heads : 0;  // ranking rotates the query only
     const int64_t idx = block * 256 + threadIdx.x;
     if (idx >= (n_q + n_k) * cpr) return;
     const int64_t row = idx / cpr;
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(256) void rope_rows_batched_kernel(const AttnBatchI
 
 hipError_t launch_rope_rows(const RopeRowsParams& p, hipStream_t stream) {
     const int np = p.dtype == ADAPSHOT_BF16 ? 8 : 4;
-    const int64_t n = (int64_t)p.t_q * (p.n_q_heads + p.n_kv_heads) * (p.head_dim / 2 / np);
+    const int64_t n = (int64_t)p.t_q * (p.n_q_heads + (p.k_self ? p.n_kv_heads : 0)) * (p.head_dim / 2 / np);
     const unsigned blocks = (unsigned)((n + 255) / 256);
     if (p.dtype == ADAPSHOT_BF16)
         hipLaunchKernelGGL(rope_rows_kernel<ADAPSHOT_BF16>, dim3(blocks), dim3(256), 0, stream, p);

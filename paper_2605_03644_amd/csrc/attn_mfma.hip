@@ -166,7 +166,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
         row_tile = rest % n_row_tiles_arg;
         split = rest / n_row_tiles_arg;
     }
-    const bool self = split == p.n_split;
+    const bool self = !p.no_self && split == p.n_split;
 
     const int g = p.n_q_heads / p.n_kv_heads;
     const int rows = p.t_q * g;
@@ -181,8 +181,18 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     const char* kbase = (const char*)(self ? p.k_self_rot : p.k_cache) + hk * kRowBytes;
     const char* vbase = (const char*)(self ? p.v_self : p.v_cache) + hk * kRowBytes;
     const int64_t kv_stride = (int64_t)p.n_kv_heads * kRowBytes;
-    const int64_t k0 = self ? 0 : (int64_t)split * p.keys_per_split;
-    const int64_t k1 = self ? (int64_t)p.t_q : (k0 + p.keys_per_split < p.n_ctx ? k0 + p.keys_per_split : p.n_ctx);
+    int64_t k0, k1;
+    if (self) {
+        k0 = 0;
+        k1 = p.t_q;
+    } else if (p.split_bounds) {  // explicit bounds (ranking: one window of shots per split)
+        const unsigned* b = (const unsigned*)(p.split_bounds + split);
+        k0 = (int64_t)(((uint64_t)__builtin_amdgcn_readfirstlane(b[1]) << 32) | __builtin_amdgcn_readfirstlane(b[0]));
+        k1 = (int64_t)(((uint64_t)__builtin_amdgcn_readfirstlane(b[3]) << 32) | __builtin_amdgcn_readfirstlane(b[2]));
+    } else {
+        k0 = (int64_t)split * p.keys_per_split;
+        k1 = k0 + p.keys_per_split < p.n_ctx ? k0 + p.keys_per_split : p.n_ctx;
+    }
     const int n_tiles = (int)((k1 - k0 + kTileKeys - 1) / kTileKeys);  // >= 1
 
     // ---- tile loads: wavefront w moves the 1 KB blocks (4 rows) w, w+WAVES, ...; lane = (row in block, chunk).
@@ -502,7 +512,8 @@ hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream) {
     const int g = p.n_q_heads / p.n_kv_heads;
     const int rows = p.t_q * g;
     const int n_row_tiles = (rows + kAttnRowTile - 1) / kAttnRowTile;
-    const unsigned blocks = (unsigned)(p.n_kv_heads * n_row_tiles * (p.n_split + 1));
+    const unsigned blocks = (unsigned)(p.n_kv_heads * n_row_tiles * (p.n_split + (p.no_self ? 0 : 1)));
+    if (blocks == 0) return hipSuccess;
     hipLaunchKernelGGL((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false>), dim3(blocks),
                        dim3(kAttnWaves * 64), 0, stream, p, n_row_tiles, (const AttnBatchItem*)nullptr,
                        (const AttnWork*)nullptr);

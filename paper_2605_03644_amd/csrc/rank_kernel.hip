@@ -1,0 +1,149 @@
+// Relevance ranking of the pool's shots for a query (Eq. attention_score, Attention-based retrieval).
+//
+// The attention itself runs in the MFMA kernel: keys = the locally encoded keys of every pool token at
+// the representative layer, "values" = one-hot rows that mark each token's shot inside its window of at
+// most head_dim consecutive shots, one context split per window, softmax normalised over the whole pool
+// when the splits are merged.  This file holds what surrounds it:
+//   rank_prepare   once per pool layer: rotate every key to its position inside its shot (a pool that
+//                  stores un-rotated keys; Eq. prefill caches them encoded) and write the one-hot rows;
+//   rank_weights   per (kv head, row): merge the splits' (m, l) into the row's global normaliser and
+//                  leave  w[s][row] = f_s 2^(m_s - M) / L  for every split;
+//   rank_reduce    per (window, shot slot): sum w[s][row] * O'[s][row][slot] over all rows and heads,
+//                  scale by 1 / (T_q H_q T_i) and add into the shot's score.
+#include "adapshot_internal.h"
+
+namespace adapshot {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// One thread per (token, kv head, chunk pair): bf16, 8 pairs per 16-byte chunk.
+__global__ __launch_bounds__(256) void rank_prepare_kernel(RankPrepareParams p) {
+    const int half = p.head_dim >> 1;
+    const int cpr = half / 8;  // chunk pairs per head
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t n = p.n_tok * p.n_kv_heads * cpr;
+    if (idx >= n) return;
+    const int ci = (int)(idx % cpr);
+    const int64_t th = idx / cpr;
+    const int hk = (int)(th % p.n_kv_heads);
+    const int64_t u = th / p.n_kv_heads;
+    const int64_t o = ((u * p.n_kv_heads + hk) * p.head_dim + ci * 8) * 2;
+    const int64_t ho = (int64_t)half * 2;
+    if (p.k_out) {
+        const int a = p.tok_local[u];
+        const float2* thi = p.tab_hi + (int64_t)(a >> kRopeLoBits) * half + ci * 8;
+        const float2* tlo = p.tab_lo + (a & (kRopeLo - 1)) * half + ci * 8;
+        u32x4 x1 = *(const u32x4*)(p.k_pool + o), x2 = *(const u32x4*)(p.k_pool + o + ho);
+        float y1[8], y2[8];
+#pragma unroll
+        for (int w = 0; w < 8; ++w) {
+            const float2 h = thi[w], l = tlo[w];
+            const float c = h.x * l.x - h.y * l.y;
+            const float s = h.y * l.x + h.x * l.y;
+            const unsigned w1 = x1[w >> 1], w2 = x2[w >> 1];
+            const float a1 = (w & 1) ? __uint_as_float(w1 & 0xffff0000u) : __uint_as_float(w1 << 16);
+            const float a2 = (w & 1) ? __uint_as_float(w2 & 0xffff0000u) : __uint_as_float(w2 << 16);
+            y1[w] = a1 * c - a2 * s;
+            y2[w] = a2 * c + a1 * s;
+        }
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int w = 0; w < 8; w += 2) {
+            const f32x2 f1 = {y1[w], y1[w + 1]}, f2 = {y2[w], y2[w + 1]};
+            x1[w >> 1] = __builtin_bit_cast(unsigned, __builtin_convertvector(f1, bf16x2));  // round to nearest even
+            x2[w >> 1] = __builtin_bit_cast(unsigned, __builtin_convertvector(f2, bf16x2));
+        }
+        *(u32x4*)(p.k_out + o) = x1;
+        *(u32x4*)(p.k_out + o + ho) = x2;
+    }
+    // one-hot row of this token (the same for every head): bf16 1.0 at column tok_col[u]
+    const int col = p.tok_col[u];
+    u32x4 z1 = {0u, 0u, 0u, 0u}, z2 = {0u, 0u, 0u, 0u};
+    const int e1 = col - ci * 8, e2 = col - half - ci * 8;
+    if (e1 >= 0 && e1 < 8) z1[e1 >> 1] = (e1 & 1) ? 0x3f800000u : 0x00003f80u;
+    if (e2 >= 0 && e2 < 8) z2[e2 >> 1] = (e2 & 1) ? 0x3f800000u : 0x00003f80u;
+    *(u32x4*)(p.v_out + o) = z1;
+    *(u32x4*)(p.v_out + o + ho) = z2;
+}
+
+hipError_t launch_rank_prepare(const RankPrepareParams& p, hipStream_t stream) {
+    const int64_t n = p.n_tok * p.n_kv_heads * (p.head_dim / 16);
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(rank_prepare_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+// 16 lanes per (kv head, row) pair, lane sl taking splits sl, sl + 16, ...; also clears the scores.
+__global__ __launch_bounds__(256) void rank_weights_kernel(RankReduceParams p) {
+    const int64_t gtid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    for (int64_t i = gtid; i < p.n_shots; i += (int64_t)gridDim.x * 256) p.scores[i] = 0.f;
+    const int sl = threadIdx.x & 15;
+    const int64_t pair = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const bool on = pair < p.n_pairs;  // whole 16-lane groups are on or off together
+    float M = -INFINITY;
+    if (on)
+        for (int s = sl; s < p.n_split; s += 16) M = fmaxf(M, p.part_mlf[(int64_t)s * p.n_pairs + pair].x);
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o, 64));
+    float L = 0.f;
+    if (on)
+        for (int s = sl; s < p.n_split; s += 16) {
+            const float4 v = p.part_mlf[(int64_t)s * p.n_pairs + pair];
+            L += v.x == -INFINITY ? 0.f : exp2f(v.x - M) * v.y;
+        }
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) L += __shfl_xor(L, o, 64);
+    const float inv = L > 0.f ? 1.0f / L : 0.f;
+    if (on)
+        for (int s = sl; s < p.n_split; s += 16) {
+            const float4 v = p.part_mlf[(int64_t)s * p.n_pairs + pair];
+            p.weights[(int64_t)s * p.n_pairs + pair] = v.x == -INFINITY ? 0.f : exp2f(v.x - M) * v.z * inv;
+        }
+}
+
+// grid = (n_split, ceil(n_pairs / 256)); 256 threads = 16 row groups x 16 lanes, a lane owning 8 shot slots
+// (16 bytes of a partial row; head_dim 128).  Row group rg takes rows pair0 + rg, + 16, ...; the 16 partial
+// sums of a slot meet in LDS, and one add per (window, slot, block) goes to the score.
+__global__ __launch_bounds__(256) void rank_reduce_kernel(RankReduceParams p) {
+    typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+    __shared__ float red[16][129];
+    const int s = blockIdx.x;
+    const int lane16 = threadIdx.x & 15, rg = threadIdx.x >> 4;
+    const int shot0 = p.split_shot0[s];
+    const int n_here = p.split_shot0[s + 1] - shot0;
+    const int64_t pair0 = (int64_t)blockIdx.y * 256;
+    const int64_t pair1 = pair0 + 256 < p.n_pairs ? pair0 + 256 : p.n_pairs;
+    const _Float16* o = (const _Float16*)p.part_o + ((int64_t)s * p.n_pairs) * 128 + lane16 * 8;
+    const float* w = p.weights + (int64_t)s * p.n_pairs;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int64_t r = pair0 + rg; r < pair1; r += 16) {
+        const f16x8 v = __builtin_nontemporal_load((const f16x8*)(o + r * 128));
+        const float wr = w[r];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] += wr * (float)v[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) red[rg][lane16 * 8 + i] = acc[i];
+    __syncthreads();
+    const int c = threadIdx.x;
+    if (c < 128 && c < n_here) {
+        float t = 0.f;
+#pragma unroll
+        for (int g = 0; g < 16; ++g) t += red[g][c];
+        atomicAdd(p.scores + shot0 + c, t * p.inv_rows * p.inv_len[shot0 + c]);
+    }
+}
+
+hipError_t launch_rank_reduce(const RankReduceParams& p, hipStream_t stream) {
+    if (p.n_split <= 0 || p.n_pairs <= 0) return hipSuccess;
+    hipLaunchKernelGGL(rank_weights_kernel, dim3((unsigned)((p.n_pairs + 15) / 16)), dim3(256), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (p.head_dim != 128) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(rank_reduce_kernel, dim3((unsigned)p.n_split, (unsigned)((p.n_pairs + 255) / 256)), dim3(256), 0,
+                       stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace adapshot
