@@ -80,3 +80,36 @@ def test_pick_shots_is_host_logic_and_matches_the_case_study(lib, oracle_mod):
         assert pick(h, k, tau) == oracle_mod.pick_shots(h.astype(np.float64), k, float(np.float32(tau)))
     out = i32(0)
     assert lib.adapshot_pick_shots(None, None, None, i32(3), f32(0.5), ctypes.byref(out)) != 0
+
+
+def test_top_k_is_host_logic(lib):
+    """Best first, lower shot id first among equal scores, errors for NaN scores and k out of range."""
+    import numpy as np
+    i32 = ctypes.c_int32
+
+    def top_k(scores, k):
+        sc = np.ascontiguousarray(scores, np.float32)
+        out = np.full(max(k, 1), -7, np.int32)
+        st = lib.adapshot_top_k(None, sc.ctypes.data_as(ctypes.c_void_p), i32(sc.size), i32(k),
+                                out.ctypes.data_as(ctypes.c_void_p))
+        return st, out[:k]
+
+    st, ids = top_k([0.1, 0.5, 0.3, 0.5, 0.2], 3)
+    assert st == 0 and ids.tolist() == [1, 3, 2]
+    st, ids = top_k([0.25] * 6, 4)
+    assert st == 0 and ids.tolist() == [0, 1, 2, 3]
+    st, ids = top_k([0.3, 0.1], 0)
+    assert st == 0 and ids.size == 0
+    rng = np.random.default_rng(5)
+    for _ in range(20):
+        n = int(rng.integers(1, 200))
+        sc = rng.integers(0, 50, n).astype(np.float32) / 50.0       # many ties
+        k = int(rng.integers(0, n + 1))
+        st, ids = top_k(sc, k)
+        want = sorted(range(n), key=lambda i: (-sc[i], i))[:k]
+        assert st == 0 and ids.tolist() == want
+    assert top_k([0.1, float("nan")], 1)[0] != 0
+    assert top_k([0.1, 0.2], 3)[0] != 0
+    assert lib.adapshot_top_k(None, None, i32(2), i32(1), None) != 0
+    # the device entry point refuses a null context before touching anything
+    assert lib.adapshot_rank_shots(None, i32(0), None, i32(1), ctypes.c_int64(0), None, None) != 0
