@@ -66,12 +66,96 @@ def cpu_baseline(w, k_pool, v_pool, off, ids, order, q, ks, vs, logits):
                 seconds=dict(assemble=t1 - t0, query_attn=t2 - t1, probe_entropy=t3 - t2)), o, h
 
 
+def extras(ad, dev) -> dict:
+    """Secondary measurements at the other workloads' shapes (one layer each, synthetic, wall-clock over
+    back-to-back calls): relevance ranking over the whole pool, the probe sweep over nested prefixes and one
+    decode step, all through the batched entry points.  Reported beside the headline, not part of it."""
+    out = {}
+
+    def wall(f, n):
+        for _ in range(10):  # more than the library's ring of pinned table buffers, which are allocated on first use
+            f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            f()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    # ranking: config 2's pool and query
+    w = wl.WORKLOADS["llama8b_1layer"]
+    k_pool, v_pool, off = wl.make_pool(w, dev)
+    ctx = ad.Context.for_workload(w)
+    ctx.pool_register(k_pool, v_pool, off)
+    q, _, _ = wl.make_query(w, dev)
+    sc = torch.empty(w.n_shots, dtype=torch.float32, device=dev)
+    dt = wall(lambda: ctx.rank_shots(0, q, out=sc), 10)
+    n_tok = int(off[-1])
+    out["rank_shots"] = {"workload": f"{w.n_shots} shots, {n_tok} pool tokens, {w.t_q} query tokens",
+                         "us_per_query": dt * 1e6, "pool_tokens_per_s": n_tok / dt,
+                         "mfma_tflops_both_products": 4.0 * w.n_q_heads * w.head_dim * w.t_q * n_tok / dt * 1e-12}
+    ctx.close()
+    del k_pool, v_pool
+
+    # probe sweep: 8 queries x prefixes {16..512} of their own 512-shot ordering, 64 probe tokens each
+    w = wl.WORKLOADS["llama8b_sweep"]
+    k_pool, v_pool, off = wl.make_pool(w, dev, n_layers=1)
+    ctx = ad.Context.for_workload(w, n_layers=1)
+    ctx.pool_register(k_pool, v_pool, off)
+    sels = [wl.selection(w, query=qi) for qi in range(8)]
+    totals = [int(sum(off[i + 1] - off[i] for i in ids)) for ids, _ in sels]
+    caches = [ad.Cache(ctx, t, with_index=False) for t in totals]
+    ctx.assemble_batched(caches, [s[0] for s in sels], [s[1] for s in sels])
+    items, flops = [], 0.0
+    for qi in range(8):
+        ids, order = sels[qi]
+        seq = [int(ids[o]) for o in order]
+        qq, ks, vs = wl.make_query(w, dev, query=qi, layer=0)
+        for k in (16, 32, 64, 128, 256, 512):
+            n_ctx = int(sum(off[s + 1] - off[s] for s in seq[:k]))
+            items.append((qi, n_ctx, qq, ks, vs, n_ctx, torch.empty_like(qq)))
+            flops += attn_flops(w, n_ctx, w.t_q)
+    packed = ctx.pack_attn_items(items)
+    dt = wall(lambda: ctx.query_attn_batched(caches, 0, packed), 5)
+    out["probe_sweep_attention"] = {"workload": "48 probes (8 queries x 6 nested prefixes up to 512 shots), 64 tokens each, 1 layer",
+                                    "us_per_call": dt * 1e6, "tflops": flops / dt * 1e-12}
+    ctx.close()
+    del k_pool, v_pool, caches, items
+
+    # decode step: 32 queries x ~16k context, one new token each
+    w = wl.WORKLOADS["qwen7b_decode"]
+    k_pool, v_pool, off = wl.make_pool(w, dev, n_layers=1)
+    ctx = ad.Context.for_workload(w, n_layers=1)
+    ctx.pool_register(k_pool, v_pool, off)
+    nq = w.n_queries
+    sels = [wl.selection(w, query=qi) for qi in range(nq)]
+    totals = [int(sum(off[i + 1] - off[i] for i in ids)) for ids, _ in sels]
+    caches = [ad.Cache(ctx, t + 8, with_index=False) for t in totals]
+    ctx.assemble_batched(caches, [s[0] for s in sels], [s[1] for s in sels])
+    g = torch.Generator(device=dev)
+    g.manual_seed(wl.SEED_BASE + 5)
+    qd = torch.randn(nq, 1, w.n_q_heads, w.head_dim, device=dev, generator=g).bfloat16()
+    kd = torch.randn(nq, 1, w.n_kv_heads, w.head_dim, device=dev, generator=g).bfloat16()
+    vd = torch.randn(nq, 1, w.n_kv_heads, w.head_dim, device=dev, generator=g).bfloat16()
+    od = [torch.empty_like(qd[i]) for i in range(nq)]
+    items = [(i, caches[i].len, qd[i], kd[i], vd[i], caches[i].len, od[i]) for i in range(nq)]
+    packed = ctx.pack_attn_items(items)
+    dt = wall(lambda: ctx.query_attn_batched(caches, 0, packed), 10)
+    kv_bytes = sum(totals) * w.n_kv_heads * w.head_dim * 2 * 2
+    out["decode_step_attention"] = {"workload": f"{nq} queries, ~{int(np.mean(totals))} context tokens each, 1 layer",
+                                    "us_per_step": dt * 1e6, "kv_gbps": kv_bytes / dt * 1e-9,
+                                    "frac_of_hbm_peak": kv_bytes / dt * 1e-9 / HBM_PEAK_GBPS}
+    ctx.close()
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--no-extras", action="store_true", help="skip the secondary measurements (ranking, sweep, decode)")
     ap.add_argument("--workload", default="llama8b_1layer")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy 4 times (reference kernel of known traffic for "
@@ -185,6 +269,13 @@ def main() -> int:
         result["check"] = dict(attn_max_abs=float(np.abs(o - o_ref).max()), entropy_max_abs=float(np.abs(h - h_ref).max()))
     else:
         result["cpu_baseline"] = None
+    if not args.no_extras and not args.copy_calibration:
+        ctx.close()
+        del k_pool, v_pool, caches, logits
+        torch.cuda.empty_cache()
+        result["extras"] = extras(ad, dev)
+        print(json.dumps(result))
+        return 0
     if args.copy_calibration:
         src = torch.empty(128 << 20, dtype=torch.bfloat16, device=dev).normal_()
         dst = torch.empty_like(src)

@@ -299,13 +299,21 @@ class Context:
         self._check(st)
 
     # -- adapshot_query_attn_batched: items = [(cache_index, n_ctx, q, k_self, v_self, q_pos0, out)]
-    def query_attn_batched(self, caches, layer: int, items, stream: Optional[torch.cuda.Stream] = None) -> None:
-        arr = self._pack_caches(caches)
+    @staticmethod
+    def pack_attn_items(items):
+        """The C array of a list of (cache_index, n_ctx, q, k_self, v_self, q_pos0, out); reusable across calls
+        as long as the tensors stay alive and the lengths do not change."""
         its = (AttnItem * len(items))()
         for i, (ci, n_ctx, q, ks, vs, q_pos0, out) in enumerate(items):
             assert q.is_contiguous() and ks.is_contiguous() and vs.is_contiguous() and out.is_contiguous()
             its[i] = AttnItem(q.data_ptr(), ks.data_ptr(), vs.data_ptr(), out.data_ptr(), n_ctx, q_pos0, q.shape[0], ci)
-        self._check(self.lib.adapshot_query_attn_batched(self._h, arr, len(caches), layer, its, len(items),
+        return its
+
+    def query_attn_batched(self, caches, layer: int, items, stream: Optional[torch.cuda.Stream] = None) -> None:
+        """items: a list of (cache_index, n_ctx, q, k_self, v_self, q_pos0, out), or what pack_attn_items made of one."""
+        arr = self._pack_caches(caches)
+        its = items if isinstance(items, ctypes.Array) else self.pack_attn_items(items)
+        self._check(self.lib.adapshot_query_attn_batched(self._h, arr, len(caches), layer, its, len(its),
                                                          _stream_ptr(stream)))
 
     # -- adapshot_decode_append: k_new, v_new [L, n_caches, H_kv, d]

@@ -632,7 +632,7 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
     const size_t attn_off = (items_bytes + 255) & ~(size_t)255;
     const size_t comb_off = (attn_off + (size_t)n_attn * sizeof(AttnWork) + 255) & ~(size_t)255;
     const size_t rope_off = (comb_off + (size_t)n_comb * sizeof(CombineWork) + 255) & ~(size_t)255;
-    const size_t tab_bytes = rope_off + (size_t)n_rope * sizeof(RopeWork);
+    const size_t tab_bytes = (rope_off + (size_t)n_rope * sizeof(RopeWork) + 15) & ~(size_t)15;
     if (e == hipSuccess) e = ctx->batch_tab.reserve(tab_bytes);
     if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: workspace", e);
     int slot = -1;
@@ -715,7 +715,7 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
     });
     for (size_t k = 0; k < keys.size(); ++k) haw[k] = keys[k].w;
 
-    e = hipMemcpyAsync(ctx->batch_tab.p, host, tab_bytes, hipMemcpyHostToDevice, stream);
+    e = launch_copy_table(ctx->batch_tab.p, host, tab_bytes, stream);
     if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: table copy", e);
     e = ctx->tile_ring.mark_in_use(slot, stream);
     if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: event record", e);

@@ -142,6 +142,9 @@ struct CombineWork {  // one workgroup of the batched combine kernel: 16 (kv hea
 struct RopeWork {  // one workgroup of the batched rotation kernel: 256 chunk pairs from 256 * block on
     int32_t item, block;
 };
+// Tables written by the host into pinned memory are brought to device memory by a kernel (a DMA copy
+// between two kernels of a stream costs more than the copy itself).  bytes is a multiple of 16.
+hipError_t launch_copy_table(void* dst, const void* src_pinned, size_t bytes, hipStream_t stream);
 hipError_t launch_rope_rows_batched(const AttnBatchItem* items, const RopeWork* work, int n_work, int dtype,
                                     hipStream_t stream);
 hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, hipStream_t stream);

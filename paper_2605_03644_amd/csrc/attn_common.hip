@@ -6,11 +6,14 @@
 //                    row, head and split) used for fp32 models and for shapes the
 //                    MFMA kernel does not cover;
 //   attn_combine  -- merges the per-split (max, sum, unnormalised output) partials.
+#include <algorithm>
 #include <type_traits>
 
 #include "adapshot_internal.h"
 
 namespace adapshot {
+
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -112,6 +115,18 @@ hipError_t launch_rope_rows(const RopeRowsParams& p, hipStream_t stream) {
         hipLaunchKernelGGL(rope_rows_kernel<ADAPSHOT_BF16>, dim3(blocks), dim3(256), 0, stream, p);
     else
         hipLaunchKernelGGL(rope_rows_kernel<ADAPSHOT_F32>, dim3(blocks), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void copy_table_kernel(u32x4_t* dst, const u32x4_t* src, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+hipError_t launch_copy_table(void* dst, const void* src_pinned, size_t bytes, hipStream_t stream) {
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 512);
+    hipLaunchKernelGGL(copy_table_kernel, dim3(blocks), dim3(256), 0, stream, (u32x4_t*)dst, (const u32x4_t*)src_pinned, n16);
     return hipGetLastError();
 }
 
