@@ -176,3 +176,49 @@ def test_qwen_decode_loop(ad, oracle_mod):
         ctx.decode_append(caches, k_new, v_new)
     assert e.value.status == ad.ECAPACITY and [c.len for c in caches] == lens
     ctx.close()
+
+
+def test_batched_attention_edge_items_match_single_calls(ad, oracle_mod):
+    """One batch mixing an empty context, a one-token query, a ragged query length and a long context, over two
+    caches: every item equals its single-call result (same kernels, different split plan) within the bf16
+    output rounding, and the empty-context item is checked against the oracle."""
+    w = wl.WORKLOADS["llama8b_sweep"]
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=1)
+    ctx = ad.Context.for_workload(w, n_layers=1)
+    ctx.pool_register(k_pool, v_pool, off)
+    sels = []
+    for qi in range(2):
+        ids, order = wl.selection(w, query=qi)
+        ids, order = ids[:40], np.argsort(np.argsort(order[:40])).astype(np.int32)
+        sels.append((ids, order))
+    totals = [int(sum(off[i + 1] - off[i] for i in ids)) for ids, _ in sels]
+    caches = [ad.Cache(ctx, t) for t in totals]
+    ctx.assemble_batched(caches, [s[0] for s in sels], [s[1] for s in sels])
+    g = torch.Generator(device="cuda"); g.manual_seed(4242)
+
+    def qkv(t_q):
+        q = torch.randn(t_q, w.n_q_heads, w.head_dim, device="cuda", generator=g).bfloat16()
+        ks = torch.randn(t_q, w.n_kv_heads, w.head_dim, device="cuda", generator=g).bfloat16()
+        vs = torch.randn(t_q, w.n_kv_heads, w.head_dim, device="cuda", generator=g).bfloat16()
+        return q, ks, vs
+
+    specs = [(0, 0, 5), (1, totals[1], 1), (0, totals[0], 37), (1, 777, 64), (0, 63, 3), (1, 65, 130)]
+    items, singles = [], []
+    for ci, n_ctx, t_q in specs:
+        q, ks, vs = qkv(t_q)
+        items.append((ci, n_ctx, q, ks, vs, n_ctx, torch.empty_like(q)))
+        singles.append(ctx.query_attn(caches[ci], 0, n_ctx, q, ks, vs, n_ctx).float().cpu().numpy())
+    ctx.query_attn_batched(caches, 0, items)
+    ctx.query_attn_batched(caches, 0, [])          # an empty batch is a no-op
+    torch.cuda.synchronize()
+    for (ci, n_ctx, t_q), it, one in zip(specs, items, singles):
+        got = it[6].float().cpu().numpy()
+        assert np.isfinite(got).all()
+        assert float(np.abs(got - one).max()) <= 2.0 ** -7 * max(1.0, float(np.abs(one).max())), (ci, n_ctx, t_q)
+    # the empty-context item attends to its own tokens only
+    ci, n_ctx, t_q = specs[0]
+    q, ks, vs = items[0][2], items[0][3], items[0][4]
+    ref = oracle_mod.query_attn(H.to_storage(caches[0].k[0]), H.to_storage(caches[0].v[0]), w.dtype, 0, H.to_storage(q),
+                                H.to_storage(ks), H.to_storage(vs), w.rope_theta, 0)
+    H.check_attention(items[0][6].float().cpu().numpy(), ref)
+    ctx.close()
