@@ -22,7 +22,9 @@
 // The two wavefronts of a SIMD run the same three phases per 64-key tile -- S^T (matrix core),
 // softmax (VALU), O^T accumulation (matrix core) -- but rotated against each other: wavefronts 0-3 go
 // S(t), softmax(t), PV(t); wavefronts 4-7 go PV(t-1), S(t), softmax(t).  While one of them runs
-// its exponentials the other one feeds the matrix core, with one workgroup barrier per tile.
+// its exponentials the other one feeds the matrix core, with one workgroup barrier per tile.  A wave
+// raises its issue priority for its matrix-core phases (s_setprio): when both waves of a SIMD have an
+// instruction ready, the MFMA goes first and the other wave's vector work fills the gaps (-6 % time).
 //
 // The S^T accumulators start from -m (m = the row's reference maximum, in registers) instead of zero,
 // so the scores leave the matrix core already shifted and the exponentials need no subtraction; the
@@ -326,6 +328,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
 
     // S^T(t) - m = K(t) . Q^T - m from K buffer `buf`: 16 MFMAs, fragments read kPD steps ahead
     auto s_phase = [&](int buf) __attribute__((always_inline)) {
+        __builtin_amdgcn_s_setprio(1);  // matrix-core phases win the issue arbitration over the other wave's softmax
         bf16x8 fr[kPD];
 #pragma unroll
         for (int i = 0; i < kPD; ++i) fr[i] = k_frag(buf, i & 1, i >> 1);
@@ -345,6 +348,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     };
     // O^T += V^T . P^T from V buffer `buf`: 16 MFMAs, 2 transposing reads per fragment
     auto pv_phase = [&](int buf) __attribute__((always_inline)) {
+        __builtin_amdgcn_s_setprio(1);
         bf16x8 fr[kPD];
 #pragma unroll
         for (int i = 0; i < kPD; ++i) fr[i] = v_frag(buf, i >> 2, i & 3);
@@ -367,6 +371,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     const int n_keys = (int)(k1 - k0);
     const int lim = (self ? (jrow[0] < n_keys ? jrow[0] + 1 : n_keys) : n_keys) - 4 * hh;
     auto softmax_phase = [&](int t) __attribute__((always_inline)) {
+        __builtin_amdgcn_s_setprio(0);
         if (self || (t + 1) * kTileKeys > n_keys) {
             const int lim_t = lim - t * kTileKeys;
 #pragma unroll
