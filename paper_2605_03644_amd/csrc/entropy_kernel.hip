@@ -46,23 +46,38 @@ __device__ __forceinline__ Mst mst_wave_reduce(Mst v) {
     return v;
 }
 
-// Fold a batch of N values into the running (m, s, t).  NaN logits poison s through exp(NaN).
+// a * b with 0 * anything = 0 (v_mul_legacy_f32)
+__device__ __forceinline__ float mul_legacy(float a, float b) {
+    float r;
+    asm("v_mul_legacy_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// Fold a batch of N values into the running (m, s, t).  A NaN logit poisons s through exp(NaN); a -inf
+// logit gives e = 0 and must contribute 0 to t although dz = -inf: the legacy multiply returns 0 for
+// 0 * anything, which is exactly the limit p ln p -> 0.
 template <int N>
 __device__ __forceinline__ void mst_add_batch(Mst& acc, const float (&z)[N]) {
     float bm = z[0];
 #pragma unroll
     for (int i = 1; i < N; ++i) bm = fmaxf(bm, z[i]);
-    bool nan = false;
-#pragma unroll
-    for (int i = 0; i < N; ++i) nan |= (z[i] != z[i]);
     const float M = fmaxf(acc.m, bm);
-    if (nan || M == INFINITY) {  // NaN or +inf logit: the row has no distribution
+    if (M == INFINITY) {  // +inf logit: the row has no distribution
         acc.m = M;
         acc.s = NAN;
         acc.t = NAN;
         return;
     }
-    if (M == -INFINITY) return;  // nothing but -inf so far
+    if (M == -INFINITY) {  // nothing but -inf so far, unless a NaN hides behind the maximum (fmaxf skips NaN)
+        bool nan = false;
+#pragma unroll
+        for (int i = 0; i < N; ++i) nan |= (z[i] != z[i]);
+        if (nan) {
+            acc.s = NAN;
+            acc.t = NAN;
+        }
+        return;
+    }
     if (M > acc.m) {
         const float dm = acc.m - M;
         const float w = __expf(dm);  // acc.m = -inf -> 0
@@ -76,7 +91,7 @@ __device__ __forceinline__ void mst_add_batch(Mst& acc, const float (&z)[N]) {
         const float dz = z[i] - M;
         const float e = __expf(dz);
         s += e;
-        t += e > 0.f ? dz * e : 0.f;
+        t += mul_legacy(e, dz);
     }
     acc.s += s;
     acc.t += t;
@@ -92,8 +107,33 @@ __global__ __launch_bounds__(256) void entropy_chunk_kernel(EntropyParams p) {
     const int c1 = min(c0 + p.chunk, p.vocab);
     Mst acc = {-INFINITY, 0.f, 0.f};
     if (VEC) {
-        // 4 float4 per thread per step, each load instruction covering 4 KB contiguous per workgroup
-        for (int base = c0; base < c1; base += 4096) {
+        // 4 float4 per thread per step, each load instruction covering 4 KB contiguous per workgroup.  Full
+        // steps (the common case) take a branch-free path and the next step's loads are issued before this
+        // step's values are used; the ragged last step of a row checks every element.
+        auto load_full = [&](int base, float (&v)[16]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const f32x4 x = __builtin_nontemporal_load((const f32x4*)(z + base + u * 1024 + tid * 4));
+#pragma unroll
+                for (int k = 0; k < 4; ++k) v[4 * u + k] = x[k];
+            }
+        };
+        int base = c0;
+        if (base + 4096 <= c1) {
+            float cur[16];
+            load_full(base, cur);
+            base += 4096;
+            while (base + 4096 <= c1) {
+                float nxt[16];
+                load_full(base, nxt);
+                base += 4096;
+                mst_add_batch<16>(acc, cur);
+#pragma unroll
+                for (int k = 0; k < 16; ++k) cur[k] = nxt[k];
+            }
+            mst_add_batch<16>(acc, cur);
+        }
+        for (; base < c1; base += 4096) {
             float v[16];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
