@@ -364,3 +364,42 @@ def test_attention_llama8b_bf16_full(ad, oracle_mod):
     w = wl.WORKLOADS["llama8b_1layer"]
     (mx, fro), got, ref = _attention_case(ad, oracle_mod, w, w.m_select, w.t_q)
     assert np.linalg.norm(ref) > 0
+
+
+def test_attention_bf16_context_length_sweep(ad, oracle_mod):
+    """Context lengths around every boundary of the key loop (64-key tiles, the four-tile unroll, split edges)
+    and query lengths around the 32-row and 256-row edges, sampled outputs against the oracle; one cache,
+    single calls and one batched call over the same cases."""
+    w = wl.WORKLOADS["llama8b_1layer"]
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=1)
+    ids, order = wl.selection(w)
+    ids, order = ids[:48], np.argsort(np.argsort(order[:48])).astype(np.int32)
+    ctx = ad.Context.for_workload(w, n_layers=1)
+    ctx.pool_register(k_pool, v_pool, off)
+    total = int(sum(off[i + 1] - off[i] for i in ids))
+    cache = ad.Cache(ctx, total, with_index=False)
+    ctx.assemble(cache, ids, order)
+    kc, vc = H.to_storage(cache.k[0]), H.to_storage(cache.v[0])
+    g = torch.Generator(device="cuda"); g.manual_seed(31337)
+    cases = [(1, 1), (63, 7), (64, 8), (65, 9), (127, 33), (129, 64), (255, 65), (257, 1), (320, 2), (511, 5),
+             (1000, 3), (1025, 70), (2048, 4), (4097, 1), (total, 6)]
+    rng = np.random.default_rng(8)
+    items, refs = [], []
+    for n_ctx, t_q in cases:
+        q = torch.randn(t_q, w.n_q_heads, w.head_dim, device="cuda", generator=g).bfloat16()
+        ks = torch.randn(t_q, w.n_kv_heads, w.head_dim, device="cuda", generator=g).bfloat16()
+        vs = torch.randn(t_q, w.n_kv_heads, w.head_dim, device="cuda", generator=g).bfloat16()
+        pairs = np.stack([rng.integers(0, t_q, 4), rng.integers(0, w.n_q_heads, 4)], 1).astype(np.int32)
+        pairs[0] = (t_q - 1, w.n_q_heads - 1)
+        ref = oracle_mod.query_attn(kc, vc, w.dtype, n_ctx, H.to_storage(q), H.to_storage(ks), H.to_storage(vs),
+                                    w.rope_theta, n_ctx, pairs=pairs)
+        out = ctx.query_attn(cache, 0, n_ctx, q, ks, vs, n_ctx).float().cpu().numpy()
+        H.check_attention(np.stack([out[j, h] for j, h in pairs]), ref)
+        items.append((0, n_ctx, q, ks, vs, n_ctx, torch.empty_like(q)))
+        refs.append((pairs, ref))
+    ctx.query_attn_batched([cache], 0, items)
+    torch.cuda.synchronize()
+    for it, (pairs, ref) in zip(items, refs):
+        out = it[6].float().cpu().numpy()
+        H.check_attention(np.stack([out[j, h] for j, h in pairs]), ref)
+    ctx.close()
