@@ -21,7 +21,7 @@ def hipcc() -> str:
 
 
 def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
-    """Compile every HIP source into one shared library.  Always recompiles."""
+    """Compile every HIP source into one shared library and return its path.  Always recompiles."""
     cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
@@ -33,12 +33,12 @@ def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in r.stdout.splitlines()
+    log = "\n".join(l for l in r.stdout.splitlines()
                     if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
     if r.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out, flush=True)
+        raise RuntimeError("hipcc failed:\n" + log)
+    if verbose and log.strip():
+        print(log, flush=True)
     return out
 
 

@@ -34,6 +34,35 @@ def test_header_symbols_are_exported(lib):
     assert sorted(binding.EXPORTS) == names
 
 
+def test_build_returns_the_library_path(monkeypatch, tmp_path):
+    """build() hands back the path it wrote (the driver's build step checks that the file exists) and
+    raises with the compiler's output when hipcc fails; hipcc itself is stubbed out here."""
+    import subprocess
+    from paper_2605_03644_amd import build
+    seen = {}
+
+    class Done:
+        def __init__(self, rc):
+            self.returncode, self.stdout = rc, "warning: something\nerror: boom\n"
+
+    def fake_run(cmd, **kw):
+        seen["cmd"] = cmd
+        return Done(seen["rc"])
+
+    monkeypatch.setattr(subprocess, "run", fake_run)
+    seen["rc"] = 0
+    target = str(tmp_path / "lib.so")
+    assert build.build(out=target) == target
+    assert seen["cmd"][-2:] == ["-o", target] and "--offload-arch=gfx950" in seen["cmd"]
+    assert all(any(c.endswith(s) for c in seen["cmd"]) for s in build.SOURCES)
+    i = seen["cmd"].index("-packed-fp32-ops")
+    assert seen["cmd"][i - 3:i] == ["-Xclang", "-target-feature", "-Xclang"]
+    assert build.build() == build.LIB
+    seen["rc"] = 1
+    with pytest.raises(RuntimeError, match="boom"):
+        build.build(out=target)
+
+
 def test_version_and_null_context(lib):
     assert b"adapshot" in lib.adapshot_version()
     assert lib.adapshot_last_error(None) == b"null context"
