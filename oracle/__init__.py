@@ -18,8 +18,10 @@ from typing import Optional, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "adapshot_oracle.c")
-_LIB = os.path.join(_HERE, "libadapshot_oracle.so")
+# ADAPSHOT_ORACLE_SRC points the loader at another copy of the C file (the mutation check of the pins
+# compiles deliberately broken copies in a scratch directory); the library is built next to it.
+_SRC = os.environ.get("ADAPSHOT_ORACLE_SRC", os.path.join(_HERE, "adapshot_oracle.c"))
+_LIB = os.path.join(os.path.dirname(os.path.abspath(_SRC)), "libadapshot_oracle.so")
 
 F32, BF16 = 0, 1
 KEYS_UNROTATED, KEYS_ROTATED_LOCAL = 0, 1

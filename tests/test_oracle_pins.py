@@ -29,6 +29,7 @@ def test_bf16_rounding_matches_library_on_fp32_inputs(oracle_mod):
     x = np.concatenate([rng.standard_normal(4000).astype(np.float32),
                         (rng.standard_normal(500) * 1e-30).astype(np.float32),
                         (rng.standard_normal(500) * 1e30).astype(np.float32),
+                        (rng.standard_normal(500) * 3e-39).astype(np.float32),   # bf16 subnormals
                         np.array([0.0, -0.0, 1.0, -1.0, 3.3895314e38, 1e-40, -1e-40, 9.2e-41], np.float32)])
     want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     got = np.array([oracle_mod.double_to_bf16(float(v)) for v in x], np.uint16)
@@ -45,6 +46,10 @@ def test_bf16_rounding_ties_and_single_step(oracle_mod):
     assert f(float("inf")) == 0x7F80 and f(float("-inf")) == 0xFF80
     assert f(3.4e38) == 0x7F80                    # above the largest bf16 (3.3895e38) + half spacing
     assert f(2.0 ** -133) == 0x0001 and f(2.0 ** -135) == 0x0000
+    # subnormal range: the spacing stays 2^-133, ties go to the even code
+    assert f(0.75 * 2.0 ** -133) == 0x0001 and f(1.75 * 2.0 ** -133) == 0x0002
+    assert f(1.5 * 2.0 ** -133) == 0x0002 and f(2.5 * 2.0 ** -133) == 0x0002 and f(-3.5 * 2.0 ** -133) == 0x8004
+    assert f(127.5 * 2.0 ** -133) == 0x0080      # rounds up into the smallest normal number
     assert oracle_mod.bf16_bits_to_f64(np.array([0x3F81], np.uint16))[0] == 1.0078125
 
 
@@ -549,9 +554,12 @@ def _rank_case(seed, n_shots=7, h_q=4, h_kv=2, d=16, t_q=5, lo=3, hi=9):
     return off, k, q
 
 
-def _rank_numpy(off, k, q, base, rotate_keys, q_pos0):
+def _rank_numpy(off, k, q, base, rotate_keys, q_pos0, store=None):
     """Eq. (attention_score) with the softmax over the whole pool, written with numpy and the closed-form
-    rotation matrix, not with the oracle's rot()."""
+    rotation matrix, not with the oracle's rot().  `store` rounds a rotated key to the cache's storage type
+    (default: fp32)."""
+    if store is None:
+        store = lambda y: y.astype(np.float32).astype(np.float64)
     T, h_kv, d = k.shape
     t_q, h_q, _ = q.shape
     half = d // 2
@@ -569,7 +577,7 @@ def _rank_numpy(off, k, q, base, rotate_keys, q_pos0):
         for i in range(len(off) - 1):
             for t in range(off[i + 1] - off[i]):
                 # the cache holds the rotated key in the storage type (fp32 here)
-                kk[off[i] + t] = rot(k[off[i] + t].astype(np.float64), float(t)).astype(np.float32).astype(np.float64)
+                kk[off[i] + t] = store(rot(k[off[i] + t].astype(np.float64), float(t)))
     g = h_q // h_kv
     s = np.zeros(len(off) - 1)
     for j in range(t_q):
@@ -636,7 +644,11 @@ def test_rank_scores_bf16_storage_rounds_rotated_keys(oracle_mod):
     got = oracle_mod.rank_scores(kb, "bf16", off, qb, 1.0e4, 0)
     kf = (kb.astype(np.uint32) << 16).view(np.float32)
     qf = (qb.astype(np.uint32) << 16).view(np.float32)
-    # same computation with exact (unrounded) rotated keys differs slightly, with rounded ones it matches
+    # with the rotated keys rounded to bf16 by the library's own conversion the scores match; with the
+    # rotated keys kept in fp32 they differ by the size of a bf16 rounding, not by nothing
+    to_bf16 = lambda y: torch.from_numpy(y).to(torch.bfloat16).to(torch.float64).numpy()
+    want = _rank_numpy(off, kf, qf, 1.0e4, rotate_keys=True, q_pos0=0, store=to_bf16)
+    assert np.allclose(got, want, rtol=1e-9, atol=0)
     exact = _rank_numpy(off, kf, qf, 1.0e4, rotate_keys=True, q_pos0=0)   # rounds rotated keys to fp32 only
-    assert 0 < np.abs(got - exact).max() < 2e-2 * exact.max()
+    assert 1e-6 * exact.max() < np.abs(got - exact).max() < 2e-2 * exact.max()
     assert abs(float((got * np.diff(off)).sum()) - 1.0) < 1e-12
