@@ -8,7 +8,7 @@ with every input already resident in HBM.  Selections, caches and logits rotate 
 distinct buffers so that a step does not find its inputs in the 256 MB Infinity Cache.
 
 Prints ONE JSON line: whole-path throughput (`value`, context tokens re-encoded and attended per
-second), per-kernel durations from HIP events on the launch stream, the roofline of the dominant
+second), per-kernel durations from HIP events attached to the dispatches on the launch stream, the roofline of the dominant
 kernel, and the CPU oracle timed on the host cores as a reported baseline.
 """
 from __future__ import annotations
@@ -210,7 +210,7 @@ def main() -> int:
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
 
-    # Same steps again with every kernel bracketed by HIP events on the launch stream.
+    # Same steps again, every kernel's dispatch carrying a pair of HIP events on the launch stream.
     ctx.profile_enable(True)
     for i in range(args.steps):
         step(i)

@@ -227,10 +227,11 @@ adapshot_status adapshot_pick_shots(adapshot_ctx* ctx, const float* entropy, con
                                     int32_t n_candidates, float tau, int32_t* picked);
 
 /* Measurement aid (not a step of the method).  While enabled, every kernel the context
- * launches is bracketed by two HIP events on the launch stream.  adapshot_profile_read
- * waits for the recorded launches of one kernel kind, returns their summed duration in
- * milliseconds and their count, and forgets them.  Event records cost a few microseconds
- * per launch, so whole-path throughput is measured with profiling off. */
+ * launches carries a pair of HIP events attached to its dispatch on the launch stream, whose
+ * difference is the kernel's own execution time (events recorded before and after a launch
+ * would add about 2.5 us of command-processor round trips).  adapshot_profile_read waits for
+ * the recorded launches of one kernel kind, returns their summed duration in milliseconds
+ * and their count, and forgets them.  Whole-path throughput is measured with profiling off. */
 typedef enum {
     ADAPSHOT_KERNEL_ASSEMBLE = 0,       /* fused gather + re-encode */
     ADAPSHOT_KERNEL_ROPE_ROWS = 1,      /* rotation of the query rows and their own keys */

@@ -14,6 +14,8 @@ using namespace adapshot;
 
 namespace adapshot {
 
+thread_local LaunchEvents g_launch_events;
+
 hipError_t DevBuf::reserve(size_t need) {
     if (need <= bytes) return hipSuccess;
     if (p) {
@@ -102,11 +104,19 @@ hipError_t Profiler::begin(int kind, hipStream_t stream) {
         }
     }
     recs.push_back(r);
-    return hipEventRecord(r.start, stream);
+    g_launch_events.start = r.start;  // the next launch_kernel on this thread attaches the pair to its dispatch
+    g_launch_events.stop = r.stop;
+    (void)stream;
+    return hipSuccess;
 }
 
 hipError_t Profiler::end(hipStream_t stream) {
     if (!on || recs.empty()) return hipSuccess;
+    if (!g_launch_events.start) return hipSuccess;  // consumed by the launch
+    // nothing was launched (an empty problem): record the pair around nothing so that it can be read back
+    g_launch_events = LaunchEvents{};
+    hipError_t e = hipEventRecord(recs.back().start, stream);
+    if (e != hipSuccess) return e;
     return hipEventRecord(recs.back().stop, stream);
 }
 
@@ -122,13 +132,16 @@ void Profiler::release() {
 
 }  // namespace adapshot
 
-// Launch one kernel, bracketed by timing events when profiling is on.
+// Launch exactly one kernel; when profiling is on its dispatch carries a pair of timing events.
 template <typename F>
 static hipError_t timed_launch(adapshot_ctx* ctx, int kind, hipStream_t stream, F&& launch) {
     hipError_t e = ctx->prof.begin(kind, stream);
     if (e != hipSuccess) return e;
     e = launch();
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess) {
+        g_launch_events = LaunchEvents{};  // a launch that failed before its dispatch leaves no pair behind
+        return e;
+    }
     return ctx->prof.end(stream);
 }
 
@@ -1009,7 +1022,9 @@ extern "C" adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer,
     rr.n_pairs = (int32_t)n_pairs;
     rr.head_dim = d.head_dim;
     rr.n_shots = ctx->n_shots;
-    e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream, [&] { return launch_rank_reduce(rr, stream); });
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream, [&] { return launch_rank_weights(rr, stream); });
+    if (e == hipSuccess)
+        e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream, [&] { return launch_rank_reduce(rr, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "rank_shots: reduce launch", e);
     ctx->last_error.clear();
     return ADAPSHOT_OK;

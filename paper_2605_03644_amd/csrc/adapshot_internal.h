@@ -1,6 +1,7 @@
 // Internal declarations shared by the host API and the kernel translation units.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include <string>
@@ -178,7 +179,8 @@ struct RankReduceParams {
     float inv_rows;           // 1 / (t_q * n_q_heads)
     int32_t n_split, n_pairs, head_dim, n_shots;
 };
-hipError_t launch_rank_reduce(const RankReduceParams& p, hipStream_t stream);
+hipError_t launch_rank_weights(const RankReduceParams& p, hipStream_t stream);  // merge weights of the windows
+hipError_t launch_rank_reduce(const RankReduceParams& p, hipStream_t stream);   // weighted sum over rows and heads
 
 // ---- entropy ------------------------------------------------------------------------
 struct EntropyParams {
@@ -219,6 +221,27 @@ struct PinnedRing {
     hipError_t mark_in_use(int slot, hipStream_t stream);
     void release();
 };
+
+// Timing events of the launch in progress.  When set, launch_kernel attaches them to the dispatch itself
+// (hipExtLaunchKernelGGL): their difference is then the kernel's own execution time as its completion
+// signal records it, without the two command-processor round trips that events recorded around a launch
+// add (about 2.5 us on this part).  One dispatch consumes the pair.
+struct LaunchEvents {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+extern thread_local LaunchEvents g_launch_events;
+
+template <typename... KArgs, typename... Args>
+inline void launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t stream, Args&&... args) {
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "one argument per kernel parameter");
+    if (g_launch_events.start) {
+        const LaunchEvents ev = g_launch_events;
+        g_launch_events = LaunchEvents{};
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, ev.start, ev.stop, 0, static_cast<KArgs>(args)...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, static_cast<KArgs>(args)...);
+    }
+}
 
 // Optional per-kernel timing with HIP events on the launch stream (measurement aid).
 struct Profiler {

@@ -161,7 +161,7 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
 template <int DTYPE, int CH>
 static hipError_t launch_t(const AssembleParams& p, hipStream_t stream) {
     dim3 grid((unsigned)p.n_tiles, (unsigned)p.layer_groups, 2);
-    hipLaunchKernelGGL((assemble_reencode_kernel<DTYPE, CH>), grid, dim3(256), 0, stream, p);
+    launch_kernel((assemble_reencode_kernel<DTYPE, CH>), grid, dim3(256), stream, p);
     return hipGetLastError();
 }
 
@@ -234,8 +234,7 @@ __global__ __launch_bounds__(128) void decode_append_kernel(DecodeAppendParams p
 
 template <int DTYPE, int CH>
 static hipError_t launch_decode_t(const DecodeAppendParams& p, hipStream_t stream) {
-    hipLaunchKernelGGL((decode_append_kernel<DTYPE, CH>), dim3((unsigned)p.count, (unsigned)p.n_layers), dim3(128), 0,
-                       stream, p);
+    launch_kernel((decode_append_kernel<DTYPE, CH>), dim3((unsigned)p.count, (unsigned)p.n_layers), dim3(128), stream, p);
     return hipGetLastError();
 }
 

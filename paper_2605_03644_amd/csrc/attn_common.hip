@@ -112,9 +112,9 @@ hipError_t launch_rope_rows(const RopeRowsParams& p, hipStream_t stream) {
     const int64_t n = (int64_t)p.t_q * (p.n_q_heads + (p.k_self ? p.n_kv_heads : 0)) * (p.head_dim / 2 / np);
     const unsigned blocks = (unsigned)((n + 255) / 256);
     if (p.dtype == ADAPSHOT_BF16)
-        hipLaunchKernelGGL(rope_rows_kernel<ADAPSHOT_BF16>, dim3(blocks), dim3(256), 0, stream, p);
+        launch_kernel(rope_rows_kernel<ADAPSHOT_BF16>, dim3(blocks), dim3(256), stream, p);
     else
-        hipLaunchKernelGGL(rope_rows_kernel<ADAPSHOT_F32>, dim3(blocks), dim3(256), 0, stream, p);
+        launch_kernel(rope_rows_kernel<ADAPSHOT_F32>, dim3(blocks), dim3(256), stream, p);
     return hipGetLastError();
 }
 
@@ -126,7 +126,7 @@ hipError_t launch_copy_table(void* dst, const void* src_pinned, size_t bytes, hi
     const size_t n16 = bytes / 16;
     if (n16 == 0) return hipSuccess;
     const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 512);
-    hipLaunchKernelGGL(copy_table_kernel, dim3(blocks), dim3(256), 0, stream, (u32x4_t*)dst, (const u32x4_t*)src_pinned, n16);
+    launch_kernel(copy_table_kernel, dim3(blocks), dim3(256), stream, (u32x4_t*)dst, (const u32x4_t*)src_pinned, n16);
     return hipGetLastError();
 }
 
@@ -134,9 +134,9 @@ hipError_t launch_rope_rows_batched(const AttnBatchItem* items, const RopeWork* 
                                     hipStream_t stream) {
     if (n_work <= 0) return hipSuccess;
     if (dtype == ADAPSHOT_BF16)
-        hipLaunchKernelGGL(rope_rows_batched_kernel<ADAPSHOT_BF16>, dim3((unsigned)n_work), dim3(256), 0, stream, items, work);
+        launch_kernel(rope_rows_batched_kernel<ADAPSHOT_BF16>, dim3((unsigned)n_work), dim3(256), stream, items, work);
     else
-        hipLaunchKernelGGL(rope_rows_batched_kernel<ADAPSHOT_F32>, dim3((unsigned)n_work), dim3(256), 0, stream, items, work);
+        launch_kernel(rope_rows_batched_kernel<ADAPSHOT_F32>, dim3((unsigned)n_work), dim3(256), stream, items, work);
     return hipGetLastError();
 }
 
@@ -222,9 +222,9 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(AttnParams p) {
 hipError_t launch_attn_generic(const AttnParams& p, hipStream_t stream) {
     dim3 grid((unsigned)(p.t_q * p.n_q_heads), (unsigned)(p.n_split + 1));
     if (p.dtype == ADAPSHOT_BF16)
-        hipLaunchKernelGGL(attn_generic_kernel<ADAPSHOT_BF16>, grid, dim3(64), 0, stream, p);
+        launch_kernel(attn_generic_kernel<ADAPSHOT_BF16>, grid, dim3(64), stream, p);
     else
-        hipLaunchKernelGGL(attn_generic_kernel<ADAPSHOT_F32>, grid, dim3(64), 0, stream, p);
+        launch_kernel(attn_generic_kernel<ADAPSHOT_F32>, grid, dim3(64), stream, p);
     return hipGetLastError();
 }
 
@@ -362,9 +362,9 @@ hipError_t launch_attn_combine(const AttnParams& p, hipStream_t stream) {
     const int per_wg = p.part_half ? 16 : 8;
     dim3 grid((unsigned)((n_pairs + per_wg - 1) / per_wg));
     if (p.dtype == ADAPSHOT_BF16)
-        hipLaunchKernelGGL(attn_combine_kernel<ADAPSHOT_BF16>, grid, dim3(256), 0, stream, p);
+        launch_kernel(attn_combine_kernel<ADAPSHOT_BF16>, grid, dim3(256), stream, p);
     else
-        hipLaunchKernelGGL(attn_combine_kernel<ADAPSHOT_F32>, grid, dim3(256), 0, stream, p);
+        launch_kernel(attn_combine_kernel<ADAPSHOT_F32>, grid, dim3(256), stream, p);
     return hipGetLastError();
 }
 
@@ -372,9 +372,9 @@ hipError_t launch_attn_combine_batched(const AttnBatchItem* items, const Combine
                                        hipStream_t stream) {
     if (n_work <= 0) return hipSuccess;
     if (dtype == ADAPSHOT_BF16)
-        hipLaunchKernelGGL(attn_combine_batched_kernel<ADAPSHOT_BF16>, dim3((unsigned)n_work), dim3(256), 0, stream, items, work);
+        launch_kernel(attn_combine_batched_kernel<ADAPSHOT_BF16>, dim3((unsigned)n_work), dim3(256), stream, items, work);
     else
-        hipLaunchKernelGGL(attn_combine_batched_kernel<ADAPSHOT_F32>, dim3((unsigned)n_work), dim3(256), 0, stream, items, work);
+        launch_kernel(attn_combine_batched_kernel<ADAPSHOT_F32>, dim3((unsigned)n_work), dim3(256), stream, items, work);
     return hipGetLastError();
 }
 

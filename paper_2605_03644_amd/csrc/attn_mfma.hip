@@ -519,16 +519,16 @@ hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream) {
     const int n_row_tiles = (rows + kAttnRowTile - 1) / kAttnRowTile;
     const unsigned blocks = (unsigned)(p.n_kv_heads * n_row_tiles * (p.n_split + (p.no_self ? 0 : 1)));
     if (blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false>), dim3(blocks),
-                       dim3(kAttnWaves * 64), 0, stream, p, n_row_tiles, (const AttnBatchItem*)nullptr,
+    launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false>), dim3(blocks),
+                       dim3(kAttnWaves * 64), stream, p, n_row_tiles, (const AttnBatchItem*)nullptr,
                        (const AttnWork*)nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, hipStream_t stream) {
     if (n_work <= 0) return hipSuccess;
-    hipLaunchKernelGGL((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), true>), dim3((unsigned)n_work),
-                       dim3(kAttnWaves * 64), 0, stream, AttnParams{}, 0, items, work);
+    launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), true>), dim3((unsigned)n_work),
+                       dim3(kAttnWaves * 64), stream, AttnParams{}, 0, items, work);
     return hipGetLastError();
 }
 

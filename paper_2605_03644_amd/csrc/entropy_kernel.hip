@@ -233,7 +233,7 @@ __global__ __launch_bounds__(64) void entropy_finish_tokens_kernel(EntropyParams
 }
 
 hipError_t launch_entropy_finish_tokens(const EntropyParams& p, const AnswerTokens& c, hipStream_t stream) {
-    hipLaunchKernelGGL(entropy_finish_tokens_kernel, dim3((unsigned)p.n_rows), dim3(64), 0, stream, p, c);
+    launch_kernel(entropy_finish_tokens_kernel, dim3((unsigned)p.n_rows), dim3(64), stream, p, c);
     return hipGetLastError();
 }
 
@@ -241,14 +241,14 @@ hipError_t launch_entropy_chunk(const EntropyParams& p, hipStream_t stream) {
     dim3 grid((unsigned)p.n_chunks, (unsigned)p.n_rows);
     const bool vec = (((uintptr_t)p.logits & 15u) == 0) && (p.row_stride % 4 == 0);
     if (vec)
-        hipLaunchKernelGGL(entropy_chunk_kernel<true>, grid, dim3(256), 0, stream, p);
+        launch_kernel(entropy_chunk_kernel<true>, grid, dim3(256), stream, p);
     else
-        hipLaunchKernelGGL(entropy_chunk_kernel<false>, grid, dim3(256), 0, stream, p);
+        launch_kernel(entropy_chunk_kernel<false>, grid, dim3(256), stream, p);
     return hipGetLastError();
 }
 
 hipError_t launch_entropy_finish(const EntropyParams& p, hipStream_t stream) {
-    hipLaunchKernelGGL(entropy_finish_kernel, dim3((unsigned)p.n_rows), dim3(64), 0, stream, p);
+    launch_kernel(entropy_finish_kernel, dim3((unsigned)p.n_rows), dim3(64), stream, p);
     return hipGetLastError();
 }
 

@@ -70,7 +70,7 @@ __global__ __launch_bounds__(256) void rank_prepare_kernel(RankPrepareParams p) 
 hipError_t launch_rank_prepare(const RankPrepareParams& p, hipStream_t stream) {
     const int64_t n = p.n_tok * p.n_kv_heads * (p.head_dim / 16);
     if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(rank_prepare_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p);
+    launch_kernel(rank_prepare_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), stream, p);
     return hipGetLastError();
 }
 
@@ -135,14 +135,16 @@ __global__ __launch_bounds__(256) void rank_reduce_kernel(RankReduceParams p) {
     }
 }
 
+hipError_t launch_rank_weights(const RankReduceParams& p, hipStream_t stream) {
+    if (p.n_split <= 0 || p.n_pairs <= 0) return hipSuccess;
+    launch_kernel(rank_weights_kernel, dim3((unsigned)((p.n_pairs + 15) / 16)), dim3(256), stream, p);
+    return hipGetLastError();
+}
+
 hipError_t launch_rank_reduce(const RankReduceParams& p, hipStream_t stream) {
     if (p.n_split <= 0 || p.n_pairs <= 0) return hipSuccess;
-    hipLaunchKernelGGL(rank_weights_kernel, dim3((unsigned)((p.n_pairs + 15) / 16)), dim3(256), 0, stream, p);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
     if (p.head_dim != 128) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(rank_reduce_kernel, dim3((unsigned)p.n_split, (unsigned)((p.n_pairs + 255) / 256)), dim3(256), 0,
-                       stream, p);
+    launch_kernel(rank_reduce_kernel, dim3((unsigned)p.n_split, (unsigned)((p.n_pairs + 255) / 256)), dim3(256), stream, p);
     return hipGetLastError();
 }
 
