@@ -222,3 +222,57 @@ def test_batched_attention_edge_items_match_single_calls(ad, oracle_mod):
                                 H.to_storage(ks), H.to_storage(vs), w.rope_theta, 0)
     H.check_attention(items[0][6].float().cpu().numpy(), ref)
     ctx.close()
+
+
+def test_byte_offsets_beyond_4gib_in_pool_and_cache(ad, oracle_mod):
+    """Six layers of the config-4 shape.  The pool holds 1.07 GB per layer and operand and the cache is given
+    a capacity of 520k tokens, so layer 3 starts beyond byte offset 2^31 and layer 5 beyond 2^32 in both.
+    Those two layers are checked: assemble on every selected token, untouched rows around them, attention
+    over the assembled context, and one appended decode token."""
+    w = wl.WORKLOADS["llama70b_128k"]
+    L, m, t_q, cap = 6, 48, 16, 520_000
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=L)
+    row_bytes = w.n_kv_heads * w.head_dim * 2
+    assert 3 * int(off[-1]) * row_bytes > 2 ** 31 and 5 * int(off[-1]) * row_bytes > 2 ** 32
+    assert 3 * cap * row_bytes > 2 ** 31 and 5 * cap * row_bytes > 2 ** 32
+    ids, order = wl.selection(w)
+    ids = ids[:m]
+    order = np.argsort(np.argsort(order[:m])).astype(np.int32)
+    ctx = ad.Context.for_workload(w, n_layers=L)
+    ctx.pool_register(k_pool, v_pool, off)
+    total = int(sum(off[i + 1] - off[i] for i in ids))
+    cache = ad.Cache(ctx, cap)
+    ctx.assemble(cache, ids, order)
+    torch.cuda.synchronize()
+    pl = oracle_mod.plan(off, ids, order)
+    assert np.array_equal(cache.slot_pos[:total].cpu().numpy(), pl["slot_pos"])
+    src = torch.from_numpy(pl["slot_src"]).cuda()
+    small = dict(pl, slot_src=np.arange(total, dtype=np.int64))   # the same plan over the gathered rows only
+    q, ks, vs = wl.make_query(w, "cuda", t_q=t_q)
+    g = torch.Generator(device="cuda"); g.manual_seed(w.seed + 5)
+    k_new = torch.randn(L, 1, w.n_kv_heads, w.head_dim, device="cuda", generator=g).to(torch.bfloat16)
+    v_new = torch.randn(L, 1, w.n_kv_heads, w.head_dim, device="cuda", generator=g).to(torch.bfloat16)
+    for layer in (3, 5):
+        kp, vp = H.to_storage(k_pool[layer:layer + 1, src]), H.to_storage(v_pool[layer:layer + 1, src])
+        ko, vo, kx = oracle_mod.assemble(kp, vp, w.dtype, w.rope_theta, 0, small, 0, total, want_exact=True)
+        kg, vg = H.to_storage(cache.k[layer:layer + 1, :total]), H.to_storage(cache.v[layer:layer + 1, :total])
+        assert np.array_equal(vg, vo)
+        H.check_reencode_bf16(kg, ko, kx, kp)
+        # nothing was written past the assembled rows of this layer or before the first row of the next one
+        assert not cache.k[layer, total:total + 4096].any() and not cache.v[layer, total:total + 4096].any()
+        assert not cache.k[layer, cap - 4096:].any() and not cache.v[layer, cap - 4096:].any()
+        out = ctx.query_attn(cache, layer, total, q, ks, vs, total)
+        ref = oracle_mod.query_attn(kg[0], vg[0], w.dtype, total, H.to_storage(q), H.to_storage(ks), H.to_storage(vs),
+                                    w.rope_theta, total)
+        H.check_attention(out.float().cpu().numpy(), ref)
+    ctx.decode_append([cache], k_new, v_new)
+    torch.cuda.synchronize()
+    assert cache.len == total + 1
+    kn, vn = H.to_storage(k_new), H.to_storage(v_new)
+    for layer in (3, 5):
+        rot = oracle_mod.rot_rows(kn[layer, 0], w.dtype, w.rope_theta, np.full(w.n_kv_heads, float(total)))
+        got = H.to_storage(cache.k[layer, total])
+        assert (got == rot).mean() > 0.99 and np.abs(H.storage_to_f64(got) - H.storage_to_f64(rot)).max() < 0.05
+        assert np.array_equal(H.to_storage(cache.v[layer, total]), vn[layer, 0])
+        assert not cache.k[layer, total + 1:total + 4096].any()
+    ctx.close()
