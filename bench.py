@@ -150,6 +150,112 @@ def extras(ad, dev) -> dict:
     del k_pool, v_pool, caches, items, packed
     torch.cuda.empty_cache()
 
+    def fits(name, need):
+        free, _ = torch.cuda.mem_get_info()
+        if free < need + (8 << 30):
+            out[name] = {"skipped": f"needs {(need + (8 << 30)) / 2**30:.0f} GiB of device memory, {free / 2**30:.0f} GiB free"}
+            return False
+        return True
+
+    # the probe sweep at its full size: 32 layers, 8 queries, one assembly of each query's 512-shot ordering
+    # serves its six nested prefixes; then 48 probes attend, layer by layer, in one batched call per layer
+    w = wl.WORKLOADS["llama8b_sweep"]
+    off = wl.shot_offsets(w)
+    row = w.n_kv_heads * w.head_dim * 2
+    sels = [wl.selection(w, query=qi) for qi in range(w.n_queries)]
+    totals = [int(sum(off[i + 1] - off[i] for i in ids)) for ids, _ in sels]
+    if fits("llama8b_sweep_full_size", 2 * w.n_layers * row * (int(off[-1]) + sum(totals))):
+        k_pool, v_pool, off = wl.make_pool(w, dev)
+        ctx = ad.Context.for_workload(w)
+        ctx.pool_register(k_pool, v_pool, off)
+        caches = [ad.Cache(ctx, t, with_index=False) for t in totals]
+        best = None
+        for _ in range(2):
+            for c in caches:
+                c.reset()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ctx.assemble_batched(caches, [s[0] for s in sels], [s[1] for s in sels])
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+        moved = 4.0 * w.n_layers * row * sum(totals)
+        items, flops = [], 0.0
+        for qi in range(w.n_queries):
+            ids, order = sels[qi]
+            seq = [int(ids[o]) for o in order]
+            qq, ks, vs = wl.make_query(w, dev, query=qi, layer=0)
+            for k in w.prefixes:
+                n_ctx = int(sum(off[s + 1] - off[s] for s in seq[:k]))
+                items.append((qi, n_ctx, qq, ks, vs, n_ctx, torch.empty_like(qq)))
+                flops += attn_flops(w, n_ctx, w.t_q)
+        packed = ctx.pack_attn_items(items)
+        for layer in (0, 1):
+            ctx.query_attn_batched(caches, layer, packed)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for layer in range(w.n_layers):
+            ctx.query_attn_batched(caches, layer, packed)
+        torch.cuda.synchronize()
+        dta = time.perf_counter() - t0
+        out["llama8b_sweep_full_size"] = {
+            "workload": f"{w.n_layers} layers, {w.n_queries} queries x {len(w.prefixes)} nested prefixes up to 512 shots "
+                        f"(~{int(np.mean(totals))} tokens), {w.t_q} probe tokens",
+            "assemble_ms": best * 1e3, "assemble_gbps": moved / best * 1e-9,
+            "assemble_frac_of_hbm_peak": moved / best * 1e-9 / HBM_PEAK_GBPS,
+            "sweep_attention_all_layers_ms": dta * 1e3, "attention_tflops": flops * w.n_layers / dta * 1e-12}
+        ctx.close()
+        del k_pool, v_pool, caches, items, packed
+        torch.cuda.empty_cache()
+
+    # the decode workload at its full size: 28 layers, 32 queries with their own 200-shot contexts, 64 steps;
+    # every step appends one token per query to every layer and attends with it, layer by layer
+    w = wl.WORKLOADS["qwen7b_decode"]
+    off = wl.shot_offsets(w)
+    row = w.n_kv_heads * w.head_dim * 2
+    nq, steps = w.n_queries, w.decode_steps
+    sels = [wl.selection(w, query=qi) for qi in range(nq)]
+    totals = [int(sum(off[i + 1] - off[i] for i in ids)) for ids, _ in sels]
+    if fits("qwen7b_decode_full_size", 2 * w.n_layers * row * (int(off[-1]) + sum(totals) + nq * steps)):
+        k_pool, v_pool, off = wl.make_pool(w, dev)
+        ctx = ad.Context.for_workload(w)
+        ctx.pool_register(k_pool, v_pool, off)
+        caches = [ad.Cache(ctx, t + steps, with_index=False) for t in totals]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ctx.assemble_batched(caches, [s[0] for s in sels], [s[1] for s in sels])
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        moved = 4.0 * w.n_layers * row * sum(totals)
+        g = torch.Generator(device=dev)
+        g.manual_seed(wl.SEED_BASE + 6)
+        kn = torch.randn(w.n_layers, nq, w.n_kv_heads, w.head_dim, device=dev, generator=g).bfloat16()
+        vn = torch.randn(w.n_layers, nq, w.n_kv_heads, w.head_dim, device=dev, generator=g).bfloat16()
+        qd = torch.randn(nq, 1, w.n_q_heads, w.head_dim, device=dev, generator=g).bfloat16()
+        kd = torch.randn(nq, 1, w.n_kv_heads, w.head_dim, device=dev, generator=g).bfloat16()
+        vd = torch.randn(nq, 1, w.n_kv_heads, w.head_dim, device=dev, generator=g).bfloat16()
+        od = [torch.empty_like(qd[i]) for i in range(nq)]
+        kv_bytes = 0.0
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            ctx.decode_append(caches, kn, vn)
+            packed = ctx.pack_attn_items([(i, caches[i].len, qd[i], kd[i], vd[i], caches[i].len, od[i]) for i in range(nq)])
+            for layer in range(w.n_layers):
+                ctx.query_attn_batched(caches, layer, packed)
+            kv_bytes += 2.0 * w.n_layers * row * sum(c.len for c in caches)
+        torch.cuda.synchronize()
+        dtd = time.perf_counter() - t0
+        out["qwen7b_decode_full_size"] = {
+            "workload": f"{w.n_layers} layers, {nq} queries x ~{int(np.mean(totals))} context tokens, {steps} decode steps "
+                        "(append + attention in every layer)",
+            "assemble_ms": dt * 1e3, "assemble_gbps": moved / dt * 1e-9,
+            "decode_ms_per_step": dtd / steps * 1e3, "decode_tokens_per_s": nq * steps / dtd,
+            "kv_gbps": kv_bytes / dtd * 1e-9, "frac_of_hbm_peak": kv_bytes / dtd * 1e-9 / HBM_PEAK_GBPS}
+        ctx.close()
+        del k_pool, v_pool, caches, packed
+        torch.cuda.empty_cache()
+
     # the 70B-shaped workload at its full size: all 80 layers of the 4000-shot pool resident (~167 GB),
     # 1000 shots (~127k tokens, ~42 GB) assembled in one call, then the query attending layer by layer
     w = wl.WORKLOADS["llama70b_128k"]
@@ -157,10 +263,7 @@ def extras(ad, dev) -> dict:
     ids, order = wl.selection(w)
     total = int(sum(off[i + 1] - off[i] for i in ids))
     row = w.n_kv_heads * w.head_dim * 2
-    need = 2 * w.n_layers * row * (int(off[-1]) + total) + (8 << 30)
-    free, _ = torch.cuda.mem_get_info()
-    if free < need:
-        out["llama70b_128k_full_size"] = {"skipped": f"needs {need / 2**30:.0f} GiB of device memory, {free / 2**30:.0f} GiB free"}
+    if not fits("llama70b_128k_full_size", 2 * w.n_layers * row * (int(off[-1]) + total)):
         return out
     k_pool, v_pool, off = wl.make_pool(w, dev)
     ctx = ad.Context.for_workload(w)
