@@ -560,6 +560,7 @@ static adapshot_status run_query_attn(adapshot_ctx* ctx, const adapshot_cache* c
     ap.part_mlf = (float4*)ctx->part_ml.p;
     ap.part_half = mfma ? 1 : 0;
     ap.no_self = 0;
+    ap.v_blocks = 4;
     ap.split_bounds = nullptr;
     ap.out = out;
     ap.n_ctx = n_ctx;
@@ -693,6 +694,7 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
         b.attn.part_mlf = (float4*)((char*)ctx->part_ml.p + pl.pml_off);
         b.attn.part_half = 1;
         b.attn.no_self = 0;
+        b.attn.v_blocks = 4;
         b.attn.split_bounds = nullptr;
         b.attn.out = it.out;
         b.attn.n_ctx = it.n_ctx;
@@ -861,9 +863,14 @@ extern "C" adapshot_status adapshot_probe_entropy_tokens(adapshot_ctx* ctx, cons
     return run_probe_entropy(ctx, logits, row_stride, n_rows, vocab, &c, entropy_out, hip_stream);
 }
 
-// Ranking state of one pool layer: windows of consecutive shots (at most head_dim shots and about
+// Shots per window: their one-hot columns fill one 32-column block of a V row, so the second product of
+// the attention kernel needs a quarter of its matrix instructions.
+constexpr int kRankWindowShots = 32;
+
+// Ranking state of one pool layer: windows of consecutive shots (at most kRankWindowShots shots and about
 // total / (2 n_cu / n_kv_heads) keys each, so that one query makes a few rounds of workgroups), per-token
 // tables, the locally encoded keys (when the pool stores them un-rotated) and the one-hot rows.
+
 static adapshot_status rank_prepare(adapshot_ctx* ctx, int32_t layer, hipStream_t stream) {
     const adapshot_model_desc& d = ctx->desc;
     const int64_t n_tok = ctx->shot_offsets[(size_t)ctx->n_shots];
@@ -879,7 +886,7 @@ static adapshot_status rank_prepare(adapshot_ctx* ctx, int32_t layer, hipStream_
     int32_t first = 0;
     for (int32_t i = 0; i < ctx->n_shots; ++i) {
         const int64_t len = ctx->shot_offsets[(size_t)i + 1] - ctx->shot_offsets[(size_t)i];
-        if (i > first && (i - first >= d.head_dim || keys + len > keys_target)) {  // close the window before shot i
+        if (i > first && (i - first >= kRankWindowShots || keys + len > keys_target)) {  // close the window before shot i
             bounds.push_back(ctx->shot_offsets[(size_t)i]);
             shot0.push_back(i);
             first = i;
@@ -997,6 +1004,7 @@ extern "C" adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer,
     ap.part_mlf = (float4*)ctx->part_ml.p;
     ap.part_half = 1;
     ap.no_self = 1;
+    ap.v_blocks = 1;  // rank_prepare closes a window after kRankWindowShots = 32 shots: one block of columns
     ap.split_bounds = (const int64_t*)ctx->rank_bounds.p;
     ap.out = nullptr;
     ap.n_ctx = n_tok;

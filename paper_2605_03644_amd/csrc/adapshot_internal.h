@@ -113,6 +113,7 @@ struct AttnParams {
     // Ranking over the pool (MFMA kernel only): context splits with explicit key bounds
     // [split_bounds[s], split_bounds[s+1]) instead of equal lengths, and no self part.
     int32_t no_self;
+    int32_t v_blocks;  // 32-column blocks of a V row that carry data: 4, or 1 when every window holds <= 32 shots
     const int64_t* split_bounds;
     void* out;       // [t_q][h_q][d]
     int64_t n_ctx;

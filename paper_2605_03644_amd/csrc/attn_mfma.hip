@@ -136,7 +136,8 @@ __device__ __forceinline__ T load_uniform(const T* ptr) {
 
 // WAVES wavefronts, each owning NR blocks of 32 rows for the whole key loop.  BATCHED: the workgroup takes
 // its problem and its (kv head, row tile, split) from the work list instead of the launch arguments.
-template <int WAVES, int NR, bool BATCHED>
+// PVB: 32-column blocks of V that carry data (4 = the whole head; ranking's one-hot rows use 1).
+template <int WAVES, int NR, bool BATCHED, int PVB>
 __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg, int n_row_tiles_arg,
                                                                const AttnBatchItem* items, const AttnWork* work) {
     constexpr int PASSES = (kTileKeys * 16) / (WAVES * 64);  // 1 KB blocks of a tile per wavefront
@@ -346,23 +347,25 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
             if (i + kPD < 16) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
     };
-    // O^T += V^T . P^T from V buffer `buf`: 16 MFMAs, 2 transposing reads per fragment
+    // O^T += V^T . P^T from V buffer `buf`: 4 * PVB MFMAs, 2 transposing reads per fragment
     auto pv_phase = [&](int buf) __attribute__((always_inline)) {
+        constexpr int NPV = 4 * PVB;
+        constexpr int PD = kPD < NPV ? kPD : NPV;
         __builtin_amdgcn_s_setprio(1);
-        bf16x8 fr[kPD];
+        bf16x8 fr[PD];
 #pragma unroll
-        for (int i = 0; i < kPD; ++i) fr[i] = v_frag(buf, i >> 2, i & 3);
+        for (int i = 0; i < PD; ++i) fr[i] = v_frag(buf, i / PVB, i % PVB);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {  // ks = i/4, db = i%4
-            const bf16x8 a = fr[i % kPD];
-            if (i + kPD < 16) fr[i % kPD] = v_frag(buf, (i + kPD) >> 2, (i + kPD) & 3);
-            o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, pb[i >> 2]), o[i & 3], 0, 0, 0);
+        for (int i = 0; i < NPV; ++i) {  // ks = i / PVB, db = i % PVB
+            const bf16x8 a = fr[i % PD];
+            if (i + PD < NPV) fr[i % PD] = v_frag(buf, (i + PD) / PVB, (i + PD) % PVB);
+            o[i % PVB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, pb[i / PVB]), o[i % PVB], 0, 0, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x100, 2 * kPD, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * PD, 0);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < NPV; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (i + kPD < 16) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            if (i + PD < NPV) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
     };
     // masks + online softmax of tile t with a lazily updated reference maximum; leaves P^T(t) in pb
@@ -519,15 +522,20 @@ hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream) {
     const int n_row_tiles = (rows + kAttnRowTile - 1) / kAttnRowTile;
     const unsigned blocks = (unsigned)(p.n_kv_heads * n_row_tiles * (p.n_split + (p.no_self ? 0 : 1)));
     if (blocks == 0) return hipSuccess;
-    launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false>), dim3(blocks),
-                       dim3(kAttnWaves * 64), stream, p, n_row_tiles, (const AttnBatchItem*)nullptr,
-                       (const AttnWork*)nullptr);
+    if (p.v_blocks == 1)
+        launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 1>), dim3(blocks),
+                      dim3(kAttnWaves * 64), stream, p, n_row_tiles, (const AttnBatchItem*)nullptr,
+                      (const AttnWork*)nullptr);
+    else
+        launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 4>), dim3(blocks),
+                      dim3(kAttnWaves * 64), stream, p, n_row_tiles, (const AttnBatchItem*)nullptr,
+                      (const AttnWork*)nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, hipStream_t stream) {
     if (n_work <= 0) return hipSuccess;
-    launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), true>), dim3((unsigned)n_work),
+    launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), true, 4>), dim3((unsigned)n_work),
                        dim3(kAttnWaves * 64), stream, AttnParams{}, 0, items, work);
     return hipGetLastError();
 }
