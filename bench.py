@@ -157,6 +157,22 @@ def extras(ad, dev) -> dict:
             return False
         return True
 
+    # probe entropy at other batch sizes: one row is latency-bound, thousands of rows stream
+    w = wl.WORKLOADS["llama8b_1layer"]
+    ctx = ad.Context.for_workload(w)
+    big = wl.make_logits(w, dev, n_rows=4096)
+    ent = {}
+    for rows in (1, 48, 128, 4096):
+        views = [big[(i * rows) % (4096 - rows + 1):][:rows] for i in range(8)]  # different rows of the 2.1 GB buffer each call
+        ho = torch.empty(rows, dtype=torch.float32, device=dev)
+        it = iter(range(10 ** 9))
+        dt = wall(lambda: ctx.probe_entropy(views[next(it) % 8], out=ho), 20)
+        ent[str(rows)] = {"us": dt * 1e6, "gbps": rows * w.vocab * 4 / dt * 1e-9}
+    out["probe_entropy_by_rows"] = {"workload": f"{w.vocab}-way fp32 logits, wall clock per call (two kernels)", **ent}
+    ctx.close()
+    del big, views
+    torch.cuda.empty_cache()
+
     # the probe sweep at its full size: 32 layers, 8 queries, one assembly of each query's 512-shot ordering
     # serves its six nested prefixes; then 48 probes attend, layer by layer, in one batched call per layer
     w = wl.WORKLOADS["llama8b_sweep"]
@@ -204,8 +220,34 @@ def extras(ad, dev) -> dict:
             "assemble_ms": best * 1e3, "assemble_gbps": moved / best * 1e-9,
             "assemble_frac_of_hbm_peak": moved / best * 1e-9 / HBM_PEAK_GBPS,
             "sweep_attention_all_layers_ms": dta * 1e3, "attention_tflops": flops * w.n_layers / dta * 1e-12}
+        # the same sweep with every (query, prefix) assembled from scratch into a cache of its own, as the
+        # workload is worded: 1008 shots per query instead of 512
+        del caches, items, packed
+        torch.cuda.empty_cache()
+        pre = [(qi, k) for qi in range(w.n_queries) for k in w.prefixes]
+        ptot = []
+        for qi, k in pre:
+            ids, order = sels[qi]
+            ptot.append(int(sum(off[ids[o] + 1] - off[ids[o]] for o in order[:k])))
+        if fits("llama8b_sweep_full_size_from_scratch", 2 * w.n_layers * row * sum(ptot)):
+            pc = [ad.Cache(ctx, t, with_index=False) for t in ptot]
+            pid, pord = [], []
+            for qi, k in pre:
+                ids, order = sels[qi]
+                pid.append(np.asarray([ids[o] for o in order[:k]], dtype=np.int32))
+                pord.append(None)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ctx.assemble_batched(pc, pid, pord)
+            torch.cuda.synchronize()
+            dts = time.perf_counter() - t0
+            moved_s = 4.0 * w.n_layers * row * sum(ptot)
+            out["llama8b_sweep_full_size"]["from_scratch_assemble_ms"] = dts * 1e3
+            out["llama8b_sweep_full_size"]["from_scratch_assemble_gbps"] = moved_s / dts * 1e-9
+            out["llama8b_sweep_full_size"]["from_scratch_gb_moved"] = moved_s * 1e-9
+            del pc
         ctx.close()
-        del k_pool, v_pool, caches, items, packed
+        del k_pool, v_pool
         torch.cuda.empty_cache()
 
     # the decode workload at its full size: 28 layers, 32 queries with their own 200-shot contexts, 64 steps;

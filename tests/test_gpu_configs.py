@@ -81,8 +81,8 @@ def test_probe_sweep_nested_prefixes_batched(ad, oracle_mod):
 
 def test_llama70b_128k_context_sampled(ad, oracle_mod):
     """Config 4 at full context size on one layer: 1000 of 4000 shots (~128k tokens), 256 query tokens,
-    64 q heads / 8 kv heads.  Assemble is checked in full for V and on sampled tokens for K; attention
-    on sampled (row, head) outputs."""
+    64 q heads / 8 kv heads.  Assemble is checked in full; attention on 1000 sampled (row, head) outputs
+    (each one a 127k-key softmax for the oracle)."""
     w = wl.WORKLOADS["llama70b_128k"]
     k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=1)
     ids, order = wl.selection(w)
@@ -104,7 +104,8 @@ def test_llama70b_128k_context_sampled(ad, oracle_mod):
     assert np.array_equal(vg, vo)
     H.check_reencode_bf16(kg, ko, kx, kp[:, pl["slot_src"]])
     rng = np.random.default_rng(4)
-    pairs = np.stack([rng.integers(0, w.t_q, 48), rng.integers(0, w.n_q_heads, 48)], axis=1).astype(np.int32)
+    n_s = 1000
+    pairs = np.stack([rng.integers(0, w.t_q, n_s), rng.integers(0, w.n_q_heads, n_s)], axis=1).astype(np.int32)
     pairs[0] = (0, 0); pairs[1] = (w.t_q - 1, w.n_q_heads - 1)
     ref = oracle_mod.query_attn(kg[0], vg[0], w.dtype, total, H.to_storage(q), H.to_storage(ks), H.to_storage(vs),
                                 w.rope_theta, total, pairs=pairs)
