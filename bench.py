@@ -66,6 +66,41 @@ def cpu_baseline(w, k_pool, v_pool, off, ids, order, q, ks, vs, logits):
                 seconds=dict(assemble=t1 - t0, query_attn=t2 - t1, probe_entropy=t3 - t2)), o, h
 
 
+def measured_ceilings(dev) -> dict:
+    """What library routines reach on this very GPU, measured now: a device-to-device copy and a reduction
+    over 512 MB (HBM), and a square bf16 GEMM (matrix cores).  Context for the fractions of the published peaks."""
+    def per_call(f, n):
+        for _ in range(3):
+            f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / n
+
+    src = torch.empty(256 << 20, dtype=torch.bfloat16, device=dev).normal_()
+    dst = torch.empty_like(src)
+    nbytes = src.numel() * 2
+    t_copy = per_call(lambda: dst.copy_(src), 20)
+    f32 = src.view(torch.float32)
+    t_read = per_call(lambda: torch.sum(f32), 20)
+    del dst
+    gemm = {}
+    for m, n, k in ((8192, 8192, 8192), (16384, 8192, 8192), (16384, 16384, 4096), (4096, 4096, 32768)):
+        a = torch.randn(m, k, device=dev, dtype=torch.bfloat16)
+        b = torch.randn(k, n, device=dev, dtype=torch.bfloat16)
+        c = torch.empty(m, n, device=dev, dtype=torch.bfloat16)
+        t = per_call(lambda: torch.matmul(a, b, out=c), 10)
+        gemm[f"{m}x{n}x{k}"] = 2.0 * m * n * k / t * 1e-12
+        del a, b, c
+    return {"copy_gbps": 2.0 * nbytes / t_copy * 1e-9, "torch_sum_gbps": nbytes / t_read * 1e-9,
+            "gemm_bf16_tflops": max(gemm.values()), "gemm_bf16_tflops_by_shape": gemm,
+            "how": "torch copy_ and sum over 512 MB, torch.matmul in bf16 (best of the shapes listed), timed now on this GPU"}
+
+
 def extras(ad, dev) -> dict:
     """Secondary measurements at the other workloads' shapes (one layer each, synthetic, wall-clock over
     back-to-back calls): relevance ranking over the whole pool, the probe sweep over nested prefixes and one
@@ -467,6 +502,14 @@ def main() -> int:
         ctx.close()
         del k_pool, v_pool, caches, logits
         torch.cuda.empty_cache()
+        try:
+            ceil = measured_ceilings(dev)
+            result["measured_ceilings"] = ceil
+            rl["assemble_reencode"]["frac_of_measured_copy"] = rl["assemble_reencode"]["achieved"] / ceil["copy_gbps"]
+            rl["entropy_chunk"]["frac_of_torch_sum"] = rl["entropy_chunk"]["achieved"] / ceil["torch_sum_gbps"]
+            rl["query_attn"]["frac_of_measured_gemm"] = rl["query_attn"]["achieved"] / ceil["gemm_bf16_tflops"]
+        except Exception as e:
+            result["measured_ceilings"] = {"error": f"{type(e).__name__}: {e}"}
         try:
             result["extras"] = extras(ad, dev)
         except Exception as e:  # the headline above stands on its own; say what happened to the rest
