@@ -128,7 +128,10 @@ adapshot_status adapshot_assemble(adapshot_ctx* ctx, adapshot_cache* cache, cons
  * [t_q][n_q_heads][head_dim] in desc.dtype.  Scores and the online softmax are kept
  * in fp32; bf16 models use bf16 MFMA for q k^T and p v with fp32 accumulation, and the
  * partial outputs of the context splits are exchanged as fp16 rows scaled by their
- * largest element (error <= 2^-11 of that element, below the bf16 rounding of out). */
+ * largest element (error <= 2^-11 of that element, below the bf16 rounding of out).
+ * Errors, all found before anything is launched (out is then untouched): EINVAL (null or
+ * misaligned pointer, t_q < 1, layer out of range, n_ctx < 0, q_pos0 < 0), ESTATE (n_ctx beyond
+ * cache->len), ECAPACITY (q_pos0 + t_q beyond max_position). */
 adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot_cache* cache, int32_t layer,
                                     int64_t n_ctx, const void* q, const void* k_self,
                                     const void* v_self, int32_t t_q, int64_t q_pos0, void* out,

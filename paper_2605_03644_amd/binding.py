@@ -155,6 +155,7 @@ class Context:
         self.desc = ModelDesc(n_layers, n_q_heads, n_kv_heads, head_dim, float(rope_theta), dtype, key_state,
                               max_position)
         self._h = ctypes.c_void_p()
+        self.n_shots = 0  # set by pool_register
         st = self.lib.adapshot_create(ctypes.byref(self.desc), ctypes.byref(self._h))
         if st != OK:
             raise AdapshotError(st, "adapshot_create failed (bad model description or no usable HIP device)")

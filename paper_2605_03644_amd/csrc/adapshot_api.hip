@@ -489,7 +489,8 @@ static adapshot_status check_query_attn(adapshot_ctx* ctx, const adapshot_cache*
         return fail(ctx, ADAPSHOT_ESTATE, "query_attn: n_ctx %lld beyond assembled length %lld", (long long)n_ctx,
                     (long long)cache->len);
     if (n_ctx > 0 && (!cache->k || !cache->v)) return fail(ctx, ADAPSHOT_EINVAL, "query_attn: null cache buffers");
-    if (q_pos0 < 0 || q_pos0 + t_q > ctx->max_position)
+    if (q_pos0 < 0) return fail(ctx, ADAPSHOT_EINVAL, "query_attn: q_pos0 < 0");
+    if (q_pos0 + t_q > ctx->max_position)
         return fail(ctx, ADAPSHOT_ECAPACITY, "query_attn: query positions exceed max_position");
     if (!aligned16(q) || !aligned16(k_self) || !aligned16(v_self) || !aligned16(out) || !aligned16(cache->k) ||
         !aligned16(cache->v))
@@ -775,7 +776,10 @@ extern "C" adapshot_status adapshot_query_attn_batched(adapshot_ctx* ctx, const 
             return fail(ctx, ADAPSHOT_EINVAL, "query_attn_batched: item %d: cache_index out of range", i);
         adapshot_status st = check_query_attn(ctx, &caches[it.cache_index], layer, it.n_ctx, it.q, it.k_self, it.v_self,
                                               it.t_q, it.q_pos0, it.out);
-        if (st != ADAPSHOT_OK) return st;
+        if (st != ADAPSHOT_OK) {  // say which item it was
+            ctx->last_error = "query_attn_batched: item " + std::to_string(i) + ": " + ctx->last_error;
+            return st;
+        }
     }
     if (n_items > 0 && attn_mfma_supported(ctx->desc)) {
         adapshot_status st = run_query_attn_batch(ctx, caches, layer, items, n_items, (hipStream_t)hip_stream);
@@ -949,7 +953,8 @@ extern "C" adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer,
     if (!q || !scores_out) return fail(ctx, ADAPSHOT_EINVAL, "rank_shots: null pointer");
     if (!aligned16(q) || ((uintptr_t)scores_out & 3u)) return fail(ctx, ADAPSHOT_EINVAL, "rank_shots: q must be 16-byte aligned");
     if (t_q < 1 || t_q > 65536) return fail(ctx, ADAPSHOT_EINVAL, "rank_shots: t_q must be in [1, 65536]");
-    if (q_pos0 < 0 || q_pos0 + t_q > ctx->max_position)
+    if (q_pos0 < 0) return fail(ctx, ADAPSHOT_EINVAL, "rank_shots: q_pos0 < 0");
+    if (q_pos0 + t_q > ctx->max_position)
         return fail(ctx, ADAPSHOT_ECAPACITY, "rank_shots: query positions exceed max_position");
     const int64_t n_tok = ctx->shot_offsets[(size_t)ctx->n_shots];
     if (ctx->n_shots < 1 || n_tok < 1) return fail(ctx, ADAPSHOT_ESTATE, "rank_shots: empty pool");

@@ -403,3 +403,67 @@ def test_attention_bf16_context_length_sweep(ad, oracle_mod):
         out = it[6].float().cpu().numpy()
         H.check_attention(np.stack([out[j, h] for j, h in pairs]), ref)
     ctx.close()
+
+
+def test_attention_entropy_and_ranking_errors_launch_nothing(ad):
+    """Every bad argument is reported with its status before anything is launched: the output buffers keep
+    their sentinel, also when only one item of a batch is bad."""
+    w = wl.WORKLOADS["llama8b_1layer"]
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=1)
+    ctx = ad.Context.for_workload(w, n_layers=1, max_position=4096)
+    q, ks, vs = wl.make_query(w, "cuda", t_q=8)
+    with pytest.raises(ad.AdapshotError) as e:   # no pool yet
+        ctx.rank_shots(0, q)
+    assert e.value.status == ad.ESTATE
+    ctx.pool_register(k_pool, v_pool, off)
+    cache = ad.Cache(ctx, 512)
+    ctx.assemble(cache, [3, 5])
+    n = cache.len
+    out = torch.full_like(q, 7.0)
+
+    def bad(status, **kw):
+        a = dict(layer=0, n_ctx=n, q_pos0=n)
+        a.update(kw)
+        with pytest.raises(ad.AdapshotError) as e:
+            ctx.query_attn(cache, a["layer"], a["n_ctx"], a.get("q", q), ks, vs, a["q_pos0"], out=out)
+        assert e.value.status == status, (kw, e.value)
+        assert ctx.last_error()
+
+    bad(ad.ESTATE, n_ctx=n + 1)              # beyond the assembled length
+    bad(ad.EINVAL, n_ctx=-1)
+    bad(ad.EINVAL, layer=1)
+    bad(ad.EINVAL, layer=-1)
+    bad(ad.ECAPACITY, q_pos0=4096 - 4)       # the query's positions run past max_position
+    bad(ad.EINVAL, q_pos0=-1)
+    bad(ad.EINVAL, q=q.view(-1)[1:1 + 7 * q.shape[1] * q.shape[2]].view(7, q.shape[1], q.shape[2]))  # not 16-byte aligned
+    # a batch with one bad item among good ones launches nothing at all
+    outs = [torch.full_like(q, 7.0) for _ in range(3)]
+    items = [(0, n, q, ks, vs, n, outs[0]), (0, n + 1, q, ks, vs, n, outs[1]), (0, n // 2, q, ks, vs, n // 2, outs[2])]
+    with pytest.raises(ad.AdapshotError) as e:
+        ctx.query_attn_batched([cache], 0, items)
+    assert e.value.status == ad.ESTATE and "item 1" in e.value.message
+    with pytest.raises(ad.AdapshotError) as e:
+        ctx.query_attn_batched([cache], 0, [(1, n, q, ks, vs, n, outs[0])])   # cache index out of range
+    assert e.value.status == ad.EINVAL
+    # entropy
+    z = wl.make_logits(w, "cuda", n_rows=4)
+    h = torch.full((4,), 7.0, device="cuda")
+    for ids, mode in (([w.vocab], 0), ([-1], 0), ([5, 5], 0), ([], 0), (list(range(17)), 0), ([1, 2], 2)):
+        with pytest.raises(ad.AdapshotError) as e:
+            ctx.probe_entropy_tokens(z, ids, mode, out=h)
+        assert e.value.status == ad.EINVAL, (ids, mode)
+    with pytest.raises(ad.AdapshotError) as e:   # rows overlap: row stride shorter than the vocabulary
+        ctx._check(ctx.lib.adapshot_probe_entropy(ctx._h, z.data_ptr(), w.vocab - 1, 4, w.vocab, h.data_ptr(), None))
+    assert e.value.status == ad.EINVAL
+    # ranking
+    sc = torch.full((w.n_shots,), 7.0, device="cuda")
+    for layer, pos in ((1, 0), (0, 4096 - 4), (0, -1)):
+        with pytest.raises(ad.AdapshotError):
+            ctx.rank_shots(layer, q, q_pos0=pos, out=sc)
+    torch.cuda.synchronize()
+    assert (out == 7.0).all() and all((o == 7.0).all() for o in outs) and (h == 7.0).all() and (sc == 7.0).all()
+    # and the same context still works afterwards
+    ok = ctx.query_attn(cache, 0, n, q, ks, vs, n, out=out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(ok.float()).all() and not (ok == 7.0).all() and ctx.last_error() == ""
+    ctx.close()
