@@ -190,10 +190,10 @@ class Context:
     def pool_register(self, k_pool: torch.Tensor, v_pool: torch.Tensor, shot_offsets: np.ndarray) -> None:
         off = np.ascontiguousarray(shot_offsets, dtype=np.int64)
         assert k_pool.is_contiguous() and v_pool.is_contiguous() and k_pool.shape == v_pool.shape
-        self._keep = [k_pool, v_pool]
-        self.n_shots = int(off.shape[0] - 1)
         self._check(self.lib.adapshot_pool_register(self._h, k_pool.data_ptr(), v_pool.data_ptr(),
                                                     off.ctypes.data, off.shape[0] - 1, k_pool.shape[1]))
+        self._keep = [k_pool, v_pool]  # the library borrows the pool: keep it alive, and only once it is accepted
+        self.n_shots = int(off.shape[0] - 1)
 
     # -- adapshot_assemble
     def assemble(self, cache: Cache, shot_ids: Sequence[int], order: Optional[Sequence[int]] = None,

@@ -467,3 +467,42 @@ def test_attention_entropy_and_ranking_errors_launch_nothing(ad):
     torch.cuda.synchronize()
     assert torch.isfinite(ok.float()).all() and not (ok == 7.0).all() and ctx.last_error() == ""
     ctx.close()
+
+
+def test_pool_and_batched_assemble_errors_change_nothing(ad, oracle_mod):
+    """A rejected pool leaves the registered one in place; a batch of assemblies with one bad member writes to
+    no cache and moves no length."""
+    w = wl.WORKLOADS["tiny_fp32"]
+    k_pool, v_pool, off = wl.make_pool(w, "cuda")
+    ctx = ad.Context.for_workload(w, max_position=4096)
+    ctx.pool_register(k_pool, v_pool, off)
+    bad_off = off.copy()
+    bad_off[3] = bad_off[2] - 1                                  # decreasing
+    for o, kp in ((bad_off, k_pool), (off, k_pool[:, : int(off[-1]) - 1].contiguous())):   # second: pool shorter than the offsets say
+        with pytest.raises(ad.AdapshotError) as e:
+            ctx.pool_register(kp, kp.clone(), o)
+        assert e.value.status == ad.EINVAL
+    assert ctx.n_shots == w.n_shots
+    c0, c1 = ad.Cache(ctx, 200), ad.Cache(ctx, 200)
+    for ids, orders, status in (([[0, 1], [2, 99]], None, ad.ESHOT),
+                                ([[0, 1], [2, 3]], [None, [0, 5]], ad.ESHOT),
+                                ([[0, 1], list(range(12))], None, ad.ECAPACITY)):
+        with pytest.raises(ad.AdapshotError) as e:
+            ctx.assemble_batched([c0, c1], ids, orders)
+        assert e.value.status == status, (ids, e.value)
+    with pytest.raises(ad.AdapshotError) as e:                    # the same cache twice in one batch
+        ctx.assemble_batched([c0, c0], [[0], [1]])
+    assert e.value.status == ad.EINVAL
+    torch.cuda.synchronize()
+    for c in (c0, c1):
+        assert c.len == 0 and not c.k.any() and not c.v.any() and (c.slot_shot == -1).all()
+    # the pool registered first is still the one in use
+    ctx.assemble_batched([c0, c1], [[0, 1], [2, 3]])
+    torch.cuda.synchronize()
+    kp, vp = H.to_storage(k_pool), H.to_storage(v_pool)
+    for c, ids in ((c0, [0, 1]), (c1, [2, 3])):
+        pl = oracle_mod.plan(off, ids, None)
+        ko, vo, _ = oracle_mod.assemble(kp, vp, w.dtype, w.rope_theta, 0, pl, 0, 200)
+        assert c.len == pl["n"] and np.array_equal(H.to_storage(c.v), vo)
+        assert np.abs(H.to_storage(c.k).astype(np.float64) - ko).max() < 1e-4
+    ctx.close()
