@@ -506,3 +506,41 @@ def test_pool_and_batched_assemble_errors_change_nothing(ad, oracle_mod):
         assert c.len == pl["n"] and np.array_equal(H.to_storage(c.v), vo)
         assert np.abs(H.to_storage(c.k).astype(np.float64) - ko).max() < 1e-4
     ctx.close()
+
+
+def test_calls_are_ordered_on_the_callers_stream(ad, oracle_mod):
+    """The inputs are produced on a side stream behind several milliseconds of other work, and the library is called
+    with that stream right away: it sees the right inputs only if its kernels are ordered on that stream too.
+    The results are read back after synchronising that stream alone."""
+    w = wl.WORKLOADS["llama8b_1layer"]
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=1)
+    ctx = ad.Context.for_workload(w, n_layers=1)
+    ctx.pool_register(k_pool, v_pool, off)
+    ids, order = wl.selection(w)
+    ids, order = ids[:6], np.argsort(np.argsort(order[:6])).astype(np.int32)
+    z_src = wl.make_logits(w, "cuda", n_rows=8)
+    q_src, ks, vs = wl.make_query(w, "cuda", t_q=16)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    cache = ad.Cache(ctx, 1024)
+    z = torch.zeros_like(z_src)
+    q = torch.zeros_like(q_src)
+    with torch.cuda.stream(s):
+        a = torch.randn(4096, 4096, device="cuda")
+        for _ in range(40):                      # a few milliseconds of work ahead of the inputs
+            a = torch.tanh(a @ a * 1e-3)
+        z.copy_(z_src)
+        q.copy_(q_src)
+        ctx.assemble(cache, ids, order, stream=s)
+        n = cache.len
+        out = ctx.query_attn(cache, 0, n, q, ks, vs, n, stream=s)
+        h = ctx.probe_entropy(z, stream=s)
+        h2 = ctx.probe_entropy_tokens(z, [11, 22], ad.ENTROPY_FULL_P, stream=s)
+    s.synchronize()
+    want_h = oracle_mod.entropy(z_src.cpu().numpy())
+    assert np.abs(h.cpu().numpy() - want_h).max() < 1e-4
+    assert np.abs(h2.cpu().numpy() - oracle_mod.entropy_subset(z_src.cpu().numpy(), [11, 22], 0)).max() < 1e-4
+    ref = oracle_mod.query_attn(H.to_storage(cache.k[0]), H.to_storage(cache.v[0]), w.dtype, n, H.to_storage(q_src),
+                                H.to_storage(ks), H.to_storage(vs), w.rope_theta, n)
+    H.check_attention(out.float().cpu().numpy(), ref)
+    ctx.close()
