@@ -544,3 +544,43 @@ def test_calls_are_ordered_on_the_callers_stream(ad, oracle_mod):
                                 H.to_storage(ks), H.to_storage(vs), w.rope_theta, n)
     H.check_attention(out.float().cpu().numpy(), ref)
     ctx.close()
+
+
+def test_two_contexts_on_two_streams(ad, oracle_mod):
+    """One context per concurrent stream: two contexts over the same borrowed pool, each with its own cache and
+    query, are driven from two streams at once, several rounds, and both match the oracle."""
+    w = wl.WORKLOADS["llama8b_1layer"]
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=1)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    ctxs, caches, sels, qs, outs = [], [], [], [], []
+    for i in range(2):
+        c = ad.Context.for_workload(w, n_layers=1)
+        c.pool_register(k_pool, v_pool, off)
+        ids, order = wl.selection(w, query=i)
+        m = 5 + 3 * i
+        sels.append((ids[:m], np.argsort(np.argsort(order[:m])).astype(np.int32)))
+        ctxs.append(c)
+        caches.append(ad.Cache(c, 2048))
+        qs.append(wl.make_query(w, "cuda", query=i, t_q=24 + 8 * i))
+        outs.append(torch.empty_like(qs[i][0]))
+    torch.cuda.synchronize()
+    for rnd in range(4):
+        for i in range(2):
+            caches[i].reset()
+            ctxs[i].assemble(caches[i], sels[i][0], sels[i][1], stream=streams[i])
+            n = caches[i].len
+            ctxs[i].query_attn(caches[i], 0, n, *qs[i], n, out=outs[i], stream=streams[i])
+    for s in streams:
+        s.synchronize()
+    kp, vp = H.to_storage(k_pool), H.to_storage(v_pool)
+    for i in range(2):
+        pl = oracle_mod.plan(off, sels[i][0], sels[i][1])
+        n = pl["n"]
+        ko, vo, _ = oracle_mod.assemble(kp, vp, w.dtype, w.rope_theta, 0, pl, 0, n)
+        assert caches[i].len == n and np.array_equal(H.to_storage(caches[i].v[:, :n]), vo)
+        q, ks, vs = qs[i]
+        ref = oracle_mod.query_attn(H.to_storage(caches[i].k[0]), H.to_storage(caches[i].v[0]), w.dtype, n,
+                                    H.to_storage(q), H.to_storage(ks), H.to_storage(vs), w.rope_theta, n)
+        H.check_attention(outs[i].float().cpu().numpy(), ref)
+        ctxs[i].close()
