@@ -584,3 +584,23 @@ def test_two_contexts_on_two_streams(ad, oracle_mod):
                                     H.to_storage(q), H.to_storage(ks), H.to_storage(vs), w.rope_theta, n)
         H.check_attention(outs[i].float().cpu().numpy(), ref)
         ctxs[i].close()
+
+
+@pytest.mark.parametrize("dtype,d,hq,hkv", [("f32", 8, 2, 1), ("f32", 32, 4, 4), ("f32", 128, 6, 2),
+                                            ("bf16", 16, 2, 2), ("bf16", 64, 8, 2), ("bf16", 256, 4, 1)])
+def test_other_head_shapes(ad, oracle_mod, dtype, d, hq, hkv):
+    """Every head_dim the library accepts besides the workloads' own (fp32: 8..128, bf16: 16..256 in powers of
+    two), with grouped, ungrouped and single kv heads: assemble in both key states, then attention over the
+    result (the one-wavefront kernel serves every shape the matrix-core kernel does not)."""
+    import dataclasses
+    w = dataclasses.replace(wl.WORKLOADS["tiny_fp32"], name=f"shape_{dtype}_{d}", n_q_heads=hq, n_kv_heads=hkv,
+                            head_dim=d, dtype=dtype, rope_theta=5.0e5)
+    for key_state in (0, 1):
+        res = _run_assemble_case(ad, oracle_mod, w, key_state, 17, [0.5])
+        assert res["total"] > 0
+    if dtype == "f32":
+        _attention_case(ad, oracle_mod, w, 8, 16, max_abs=1e-4, rel_fro=1e-5)
+        _attention_case(ad, oracle_mod, w, 3, 1, pos0=1000, max_abs=1e-4, rel_fro=1e-5)
+    else:
+        _attention_case(ad, oracle_mod, w, 8, 16)
+        _attention_case(ad, oracle_mod, w, 3, 1, pos0=1000)
