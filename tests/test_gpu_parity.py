@@ -604,3 +604,13 @@ def test_other_head_shapes(ad, oracle_mod, dtype, d, hq, hkv):
     else:
         _attention_case(ad, oracle_mod, w, 8, 16)
         _attention_case(ad, oracle_mod, w, 3, 1, pos0=1000)
+
+
+@pytest.mark.parametrize("hq,hkv,t_q", [(4, 4, 300), (3, 3, 40), (32, 2, 20), (5, 1, 60), (48, 6, 33), (16, 16, 1)])
+def test_matrix_core_kernel_other_groupings(ad, oracle_mod, hq, hkv, t_q):
+    """bf16, head_dim 128 with group sizes 1, 5, 8 and 16 and kv head counts that are not multiples of the XCD count;
+    row counts t_q * g that end inside a wavefront's 32 rows, inside a 256-row tile, and in a second tile."""
+    import dataclasses
+    w = dataclasses.replace(wl.WORKLOADS["llama8b_1layer"], name=f"grouping_{hq}_{hkv}", n_q_heads=hq, n_kv_heads=hkv)
+    _attention_case(ad, oracle_mod, w, 7, t_q)
+    _attention_case(ad, oracle_mod, w, 2, t_q, n_ctx=65, pos0=3)
