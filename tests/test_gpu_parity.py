@@ -614,3 +614,29 @@ def test_matrix_core_kernel_other_groupings(ad, oracle_mod, hq, hkv, t_q):
     w = dataclasses.replace(wl.WORKLOADS["llama8b_1layer"], name=f"grouping_{hq}_{hkv}", n_q_heads=hq, n_kv_heads=hkv)
     _attention_case(ad, oracle_mod, w, 7, t_q)
     _attention_case(ad, oracle_mod, w, 2, t_q, n_ctx=65, pos0=3)
+
+
+@pytest.mark.parametrize("direction", ["rising", "falling", "spikes"])
+def test_attention_bf16_wide_score_range(ad, oracle_mod, direction):
+    """Keys scaled by a factor that changes along the context (0.05 .. 3): the row maxima keep rising from tile to
+    tile (the reference maximum is moved and everything accumulated rescaled again and again), or fall so that
+    late tiles underflow to nothing, or jump at isolated keys.  The scores now span some twenty powers of two,
+    and the bf16 rounding of the rotated query, which every bf16 attention carries into its scores, grows with
+    them (about 2^-9 of a score): the bars are 1.5 times the ones for N(0,1) keys."""
+    w = wl.WORKLOADS["llama8b_1layer"]
+
+    def mutate(cache, q, ks, vs, q_pos0):
+        n = cache.len
+        u = torch.arange(n, device="cuda", dtype=torch.float32) / max(n - 1, 1)
+        if direction == "rising":
+            f = 0.05 + 2.95 * u
+        elif direction == "falling":
+            f = 3.0 - 2.95 * u
+        else:
+            f = torch.full_like(u, 0.3)
+            f[::97] = 3.0
+        cache.k[0, :n] = (cache.k[0, :n].float() * f[:, None, None]).to(cache.k.dtype)
+
+    (worst, fro), got, ref = _attention_case(ad, oracle_mod, w, 9, 40, mutate=mutate, max_abs=3e-2, rel_fro=1.5e-2)
+    print(f"{direction}: max-abs {worst:.3e}, rel-Frobenius {fro:.3e}")
+    assert np.isfinite(got).all() and np.abs(ref).max() > 0.5
