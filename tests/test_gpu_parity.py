@@ -78,7 +78,7 @@ def _run_assemble_case(ad, oracle_mod, w, key_state, pos0, splits, n_layers=None
 
 
 @pytest.mark.parametrize("key_state", [0, 1])
-@pytest.mark.parametrize("pos0,splits", [(0, []), (11, [0.4]), (100000, [0.25, 0.5])])
+@pytest.mark.parametrize("pos0,splits", [(0, []), (11, [0.4]), (100000, [0.25, 0.5]), (1048576 - 300, [])])
 def test_assemble_tiny_fp32(ad, oracle_mod, key_state, pos0, splits):
     w = wl.WORKLOADS["tiny_fp32"]
     _run_assemble_case(ad, oracle_mod, w, key_state, pos0, splits)
