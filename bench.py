@@ -366,7 +366,21 @@ def extras(ad, dev) -> dict:
         ctx.query_attn(cache, layer, total, q, ks, vs, total, out=o)
     torch.cuda.synchronize()
     dta = time.perf_counter() - t0
+    # consistency at full size: the last layer (byte offsets far beyond 2^32) against a one-layer context over
+    # the same slice of the pool, whose path the parity tests check against the oracle
+    last = w.n_layers - 1
+    ctx.query_attn(cache, last, total, q, ks, vs, total, out=o)
+    ctx1 = ad.Context.for_workload(w, n_layers=1)
+    ctx1.pool_register(k_pool[last:last + 1], v_pool[last:last + 1], off)
+    c1 = ad.Cache(ctx1, total, with_index=False)
+    ctx1.assemble(c1, ids, order)
+    o1 = ctx1.query_attn(c1, 0, total, q, ks, vs, total)
+    torch.cuda.synchronize()
+    same = bool(torch.equal(c1.k[0], cache.k[last]) and torch.equal(c1.v[0], cache.v[last]) and torch.equal(o1, o))
+    ctx1.close()
+    del c1
     out["llama70b_128k_full_size"] = {
+        "last_layer_equals_one_layer_path": same,
         "workload": f"{w.n_layers} layers, pool {2 * w.n_layers * row * int(off[-1]) / 1e9:.0f} GB resident, "
                     f"{len(ids)} shots = {total} tokens assembled per call, {w.t_q} query tokens",
         "assemble_ms": best * 1e3, "assemble_gbps": moved / best * 1e-9,
