@@ -12,7 +12,8 @@
 // ONCE into LDS -- one fp32 angle addition of two fp64-built table entries,
 // a = 64*hi + lo -- and then stream all heads and layers through it: a lane owns the
 // two 16-byte chunks that hold the pair partners (i, i + d/2), rotates them in fp32 and
-// stores both.  V workgroups are a plain 128-bit copy.
+// stores both.  V workgroups are a plain 128-bit copy.  Both streams keep their loads one step ahead of
+// their stores (the first K step is requested before the angle table is built): -8 % on a 27k-token launch.
 #include "adapshot_internal.h"
 
 namespace adapshot {
@@ -78,23 +79,39 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
     const int64_t dst_off = (int64_t)td.dst_slot * row_bytes;
 
     if (blockIdx.z == 1) {
-        // ---- V: dense copy of n_tok rows per layer ----
+        // ---- V: dense copy of n_tok rows per layer, one step (4 x 16 bytes per lane) ahead ----
         const int n16 = (int)((n_tok * row_bytes) >> 4);
-        for (int l = blockIdx.y; l < p.n_layers; l += p.layer_groups) {
+        auto vload = [&](int l, int i0, u32x4(&r)[4]) __attribute__((always_inline)) {
             const char* src = p.v_pool + (int64_t)l * p.pool_layer_stride_bytes + src_off;
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (i0 + 256 * u < n16) r[u] = ld16(src + ((int64_t)(i0 + 256 * u) << 4));
+        };
+        auto vstore = [&](int l, int i0, u32x4(&r)[4]) __attribute__((always_inline)) {
             char* dst = p.v_out + (int64_t)l * p.cache_layer_stride_bytes + dst_off;
-            int i = tid;
-            for (; i + 768 < n16; i += 1024) {
-                u32x4 r0 = ld16(src + ((int64_t)i << 4));
-                u32x4 r1 = ld16(src + ((int64_t)(i + 256) << 4));
-                u32x4 r2 = ld16(src + ((int64_t)(i + 512) << 4));
-                u32x4 r3 = ld16(src + ((int64_t)(i + 768) << 4));
-                st16(dst + ((int64_t)i << 4), r0);
-                st16(dst + ((int64_t)(i + 256) << 4), r1);
-                st16(dst + ((int64_t)(i + 512) << 4), r2);
-                st16(dst + ((int64_t)(i + 768) << 4), r3);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (i0 + 256 * u < n16) st16(dst + ((int64_t)(i0 + 256 * u) << 4), r[u]);
+        };
+        int l = blockIdx.y, i0 = tid;
+        bool have = l < p.n_layers;
+        u32x4 cur[4];
+        if (have) vload(l, i0, cur);
+        while (have) {
+            int ln = l, in = i0 + 1024;
+            if (in - tid >= n16) {  // this layer's rows are done (workgroup-uniform test)
+                in = tid;
+                ln += p.layer_groups;
             }
-            for (; i < n16; i += 256) st16(dst + ((int64_t)i << 4), ld16(src + ((int64_t)i << 4)));
+            const bool more = ln < p.n_layers;
+            u32x4 nxt[4];
+            if (more) vload(ln, in, nxt);
+            vstore(l, i0, cur);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
+            l = ln;
+            i0 = in;
+            have = more;
         }
         return;
     }
@@ -105,6 +122,47 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
         if (p.slot_tok) p.slot_tok[td.dst_slot + tid] = td.tok0 + tid;
         if (p.slot_pos) p.slot_pos[td.dst_slot + tid] = (int64_t)td.pos_first + tid;
     }
+
+    const int rpt = p.n_kv_heads * CH;  // lane items per token: (head, chunk)
+    const int n_items = n_tok * rpt;
+    // One step of the K stream: up to 4 (head, chunk) items per lane, both pair partners of each.
+    struct Step {
+        u32x4 a[4], b[4];
+        int64_t off[4];
+        int csi[4];
+    };
+    auto load_step = [&](const char* src, int base, Step& st) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int f = base + u * 256 + tid;
+            if (f < n_items) {
+                const int tau = f / rpt;
+                const int r = f - tau * rpt;
+                const int h = r / CH;
+                const int c = r - h * CH;
+                st.off[u] = (int64_t)tau * row_bytes + h * HEAD_BYTES + c * 16;
+                st.csi[u] = tau * HALF + c * NP;
+                st.a[u] = ld16(src + st.off[u]);
+                st.b[u] = ld16(src + st.off[u] + CH * 16);
+            }
+        }
+    };
+    auto store_step = [&](char* dst, int base, Step& st) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int f = base + u * 256 + tid;
+            if (f < n_items) {
+                rotate_chunks<DTYPE>(st.a[u], st.b[u], cs + st.csi[u]);
+                st16(dst + st.off[u], st.a[u]);
+                st16(dst + st.off[u] + CH * 16, st.b[u]);
+            }
+        }
+    };
+    // The first keys are requested before the angle table is built, so that the table's own loads and
+    // arithmetic run under their latency.
+    const int l0 = blockIdx.y;
+    Step first;
+    if (l0 < p.n_layers) load_step(p.k_pool + (int64_t)l0 * p.pool_layer_stride_bytes + src_off, 0, first);
 
     // cos/sin of every (token, frequency) of the tile, two frequencies per step.
     for (int it = tid; it < n_tok * (HALF / 2); it += 256) {
@@ -122,39 +180,25 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
     }
     __syncthreads();
 
-    const int rpt = p.n_kv_heads * CH;  // lane items per token: (head, chunk)
-    const int n_items = n_tok * rpt;
-    for (int l = blockIdx.y; l < p.n_layers; l += p.layer_groups) {
-        const char* src = p.k_pool + (int64_t)l * p.pool_layer_stride_bytes + src_off;
-        char* dst = p.k_out + (int64_t)l * p.cache_layer_stride_bytes + dst_off;
-        for (int base = 0; base < n_items; base += 1024) {
-            u32x4 a[4], b[4];
-            int64_t off[4];
-            int csi[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int f = base + u * 256 + tid;
-                if (f < n_items) {
-                    const int tau = f / rpt;
-                    const int r = f - tau * rpt;
-                    const int h = r / CH;
-                    const int c = r - h * CH;
-                    off[u] = (int64_t)tau * row_bytes + h * HEAD_BYTES + c * 16;
-                    csi[u] = tau * HALF + c * NP;
-                    a[u] = ld16(src + off[u]);
-                    b[u] = ld16(src + off[u] + CH * 16);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int f = base + u * 256 + tid;
-                if (f < n_items) {
-                    rotate_chunks<DTYPE>(a[u], b[u], cs + csi[u]);
-                    st16(dst + off[u], a[u]);
-                    st16(dst + off[u] + CH * 16, b[u]);
-                }
-            }
+    // The stream runs one step ahead: the loads of the next step (the next 1024 items of this layer, or the
+    // first of the next layer) are in flight while the current one is rotated and stored.
+    int l = l0, base = 0;
+    bool have = l0 < p.n_layers;
+    Step cur = first;
+    while (have) {
+        int ln = l, bn = base + 1024;
+        if (bn >= n_items) {
+            bn = 0;
+            ln += p.layer_groups;
         }
+        const bool more = ln < p.n_layers;
+        Step nxt;
+        if (more) load_step(p.k_pool + (int64_t)ln * p.pool_layer_stride_bytes + src_off, bn, nxt);
+        store_step(p.k_out + (int64_t)l * p.cache_layer_stride_bytes + dst_off, base, cur);
+        cur = nxt;
+        l = ln;
+        base = bn;
+        have = more;
     }
 }
 
