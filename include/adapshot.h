@@ -23,6 +23,15 @@
  *     the GPU.  A context owns device scratch (RoPE tables, tile descriptors,
  *     split partials), so calls on ONE context must be issued in stream order on
  *     one stream at a time; use one context per concurrent stream.
+ *   - Allocation and waiting.  adapshot_create allocates the RoPE tables (hipMalloc and two
+ *     blocking copies).  adapshot_query_attn, adapshot_query_attn_batched, adapshot_probe_entropy,
+ *     adapshot_probe_entropy_tokens and adapshot_rank_shots keep grow-only workspaces: a call that
+ *     needs more than any earlier call on the context calls hipMalloc (an outgrown buffer is kept
+ *     until adapshot_destroy, never freed in a call, so no call waits for the device); a call that
+ *     fits the existing workspaces allocates nothing.  adapshot_assemble, the batched calls and
+ *     adapshot_rank_shots write small tables into a ring of 8 pinned host buffers (hipHostMalloc
+ *     when one must grow); the ninth such call in flight waits for the first one's kernels.  No
+ *     call synchronises the device or the stream otherwise.
  *   - Every function validates its arguments on the host BEFORE launching
  *     anything: a call that returns an error has written nothing to device
  *     memory.  The reason is kept per context (adapshot_last_error).
@@ -129,6 +138,11 @@ adapshot_status adapshot_assemble(adapshot_ctx* ctx, adapshot_cache* cache, cons
  * in fp32; bf16 models use bf16 MFMA for q k^T and p v with fp32 accumulation, and the
  * partial outputs of the context splits are exchanged as fp16 rows scaled by their
  * largest element (error <= 2^-11 of that element, below the bf16 rounding of out).
+ * Accuracy of the bf16 path depends on the data: the rotated, pre-scaled query and the keys are bf16
+ * matrix operands, so a score carries about 2^-9 of its own magnitude as error and the output error
+ * grows with the spread of the scores.  With N(0,1) queries, keys and values the outputs stay within
+ * 2e-2 (max-abs) of the exact result; keys three times as large were measured at 1.9e-2, eight times
+ * as large at 6e-2.  Accumulation, maxima and sums are fp32 throughout.
  * Errors, all found before anything is launched (out is then untouched): EINVAL (null or
  * misaligned pointer, t_q < 1, layer out of range, n_ctx < 0, q_pos0 < 0), ESTATE (n_ctx beyond
  * cache->len), ECAPACITY (q_pos0 + t_q beyond max_position). */
@@ -209,8 +223,10 @@ adapshot_status adapshot_probe_entropy_tokens(adapshot_ctx* ctx, const float* lo
  * the average is 1 / T_i whatever the content).  Keys are taken as a cache holds them: encoded at their
  * position inside the shot (Eq. prefill); for a pool registered with ADAPSHOT_KEYS_UNROTATED the library
  * builds that encoding of the layer once and keeps it, together with one more layer-sized buffer, until
- * another layer is ranked, the pool is registered again or the context is destroyed.  The query is encoded
- * on its own: token j at position q_pos0 + j.
+ * another layer is ranked, the pool is registered again or the context is destroyed.  The kept state is
+ * tied to the registration, not to the bytes: after rewriting pool contents in place, call
+ * adapshot_pool_register again before ranking.  The query is encoded on its own: token j at position
+ * q_pos0 + j.  The reduction order is fixed: the same inputs give bit-identical scores.
  * q: DEVICE [t_q][n_q_heads][head_dim] without rotation; scores_out: DEVICE fp32 [n_shots].
  * bf16 models with head_dim 128 only (ESTATE otherwise); every shot must hold at least one token. */
 adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer, const void* q, int32_t t_q, int64_t q_pos0,
@@ -228,6 +244,13 @@ adapshot_status adapshot_top_k(adapshot_ctx* ctx, const float* scores, int32_t n
  * entropy never passes.  Host arrays, host logic: nothing is launched.  ctx may be NULL. */
 adapshot_status adapshot_pick_shots(adapshot_ctx* ctx, const float* entropy, const int32_t* shot_counts,
                                     int32_t n_candidates, float tau, int32_t* picked);
+
+/* Test and tuning aid (not a step of the method): fixes the number of context splits the attention
+ * planner cuts a context into (1..64; 0 gives the choice back to the planner, which sizes the splits to
+ * the compute units).  A batched call gives the longest item that many splits and every other item the
+ * same split length.  The result of the attention does not depend on the split count beyond the
+ * summation order of the partials. */
+adapshot_status adapshot_set_attn_splits(adapshot_ctx* ctx, int32_t n_split);
 
 /* Measurement aid (not a step of the method).  While enabled, every kernel the context
  * launches carries a pair of HIP events attached to its dispatch on the launch stream, whose

@@ -28,7 +28,7 @@ EXPORTS = ["adapshot_create", "adapshot_destroy", "adapshot_last_error", "adapsh
            "adapshot_pool_register", "adapshot_assemble", "adapshot_query_attn", "adapshot_probe_entropy",
            "adapshot_profile_enable", "adapshot_profile_read", "adapshot_assemble_batched",
            "adapshot_query_attn_batched", "adapshot_decode_append", "adapshot_probe_entropy_tokens",
-           "adapshot_pick_shots", "adapshot_rank_shots", "adapshot_top_k"]
+           "adapshot_pick_shots", "adapshot_rank_shots", "adapshot_top_k", "adapshot_set_attn_splits"]
 ENTROPY_FULL_P, ENTROPY_RENORMALISED = 0, 1
 KERNEL_KINDS = ["assemble_reencode", "rope_rows", "query_attn", "attn_combine", "entropy_chunk", "entropy_finish"]
 
@@ -100,6 +100,8 @@ def load_library() -> ctypes.CDLL:
     L.adapshot_query_attn_batched.argtypes = [vp, ctypes.POINTER(CacheStruct), i32, i32, ctypes.POINTER(AttnItem), i32, vp]
     L.adapshot_decode_append.restype = ctypes.c_int
     L.adapshot_decode_append.argtypes = [vp, ctypes.POINTER(CacheStruct), i32, vp, vp, i64, vp]
+    L.adapshot_set_attn_splits.restype = ctypes.c_int
+    L.adapshot_set_attn_splits.argtypes = [vp, i32]
     L.adapshot_profile_enable.restype = ctypes.c_int
     L.adapshot_profile_enable.argtypes = [vp, i32]
     L.adapshot_profile_read.restype = ctypes.c_int
@@ -327,6 +329,10 @@ class Context:
                                              _stream_ptr(stream))
         self._unpack_lens(caches, arr)
         self._check(st)
+
+    # -- adapshot_set_attn_splits
+    def set_attn_splits(self, n_split: int) -> None:
+        self._check(self.lib.adapshot_set_attn_splits(self._h, int(n_split)))
 
     # -- adapshot_profile_enable / adapshot_profile_read
     def profile_enable(self, on: bool) -> None:

@@ -16,22 +16,20 @@ namespace adapshot {
 
 thread_local LaunchEvents g_launch_events;
 
-hipError_t DevBuf::reserve(size_t need) {
+// Grow-only.  A buffer that is too small is not freed here: kernels already enqueued (on any stream) may
+// still use it, and hipFree would stall the whole device.  It is parked in `retired` until the context is
+// destroyed; the new one is at least half as large again as the old, so the parked memory stays below
+// twice the final size.  Contents are not carried over: every workspace is rewritten by the call that
+// reserves it.
+hipError_t DevBuf::reserve(size_t need, std::vector<void*>& retired) {
     if (need <= bytes) return hipSuccess;
-    if (p) {
-        // Earlier kernels may still read the old buffer: drain before freeing it.
-        hipError_t e = hipDeviceSynchronize();
-        if (e != hipSuccess) return e;
-        (void)hipFree(p);
-        p = nullptr;
-        bytes = 0;
-    }
-    size_t want = std::max(need, (size_t)1 << 16);
-    hipError_t e = hipMalloc(&p, want);
-    if (e != hipSuccess) {
-        p = nullptr;
-        return e;
-    }
+    size_t want = std::max(std::max(need, bytes + bytes / 2), (size_t)1 << 16);
+    want = (want + 255) & ~(size_t)255;
+    void* fresh = nullptr;
+    hipError_t e = hipMalloc(&fresh, want);
+    if (e != hipSuccess) return e;
+    if (p) retired.push_back(p);
+    p = fresh;
     bytes = want;
     return hipSuccess;
 }
@@ -253,11 +251,11 @@ extern "C" void adapshot_destroy(adapshot_ctx* ctx) {
     ctx->batch_tab.release();
     ctx->rank_k.release();
     ctx->rank_v.release();
-    ctx->rank_tok.release();
-    ctx->rank_bounds.release();
-    ctx->rank_shot0.release();
-    ctx->rank_inv_len.release();
     ctx->rank_w.release();
+    ctx->rank_part.release();
+    ctx->rank_tab.release();
+    for (void* q : ctx->retired) (void)hipFree(q);
+    ctx->retired.clear();
     if (ctx->tab_lo) (void)hipFree(ctx->tab_lo);
     if (ctx->tab_hi) (void)hipFree(ctx->tab_hi);
     delete ctx;
@@ -521,16 +519,17 @@ static adapshot_status run_query_attn(adapshot_ctx* ctx, const adapshot_cache* c
         const int64_t want = mfma ? std::max<int64_t>(units, (int64_t)ctx->n_cu - units) : (int64_t)ctx->n_cu * 8;
         const int64_t target = std::max<int64_t>(1, want / units);
         n_split = std::min<int64_t>(std::min<int64_t>(target, key_tiles), 64);
+        if (ctx->force_splits > 0) n_split = std::min<int64_t>(ctx->force_splits, key_tiles);
         keys_per_split = ((key_tiles + n_split - 1) / n_split) * 64;
         n_split = (n_ctx + keys_per_split - 1) / keys_per_split;
     }
 
     const size_t esz = (size_t)ctx->elem_bytes;
-    hipError_t e = ctx->q_rot.reserve((size_t)t_q * d.n_q_heads * d.head_dim * esz);
-    if (e == hipSuccess) e = ctx->k_rot.reserve((size_t)t_q * d.n_kv_heads * d.head_dim * esz);
+    hipError_t e = ctx->q_rot.reserve((size_t)t_q * d.n_q_heads * d.head_dim * esz, ctx->retired);
+    if (e == hipSuccess) e = ctx->k_rot.reserve((size_t)t_q * d.n_kv_heads * d.head_dim * esz, ctx->retired);
     if (e == hipSuccess)
-        e = ctx->part_o.reserve((size_t)(n_split + 1) * d.n_kv_heads * rows * d.head_dim * (mfma ? 2 : 4));
-    if (e == hipSuccess) e = ctx->part_ml.reserve((size_t)(n_split + 1) * d.n_kv_heads * rows * sizeof(float4));
+        e = ctx->part_o.reserve((size_t)(n_split + 1) * d.n_kv_heads * rows * d.head_dim * (mfma ? 2 : 4), ctx->retired);
+    if (e == hipSuccess) e = ctx->part_ml.reserve((size_t)(n_split + 1) * d.n_kv_heads * rows * sizeof(float4), ctx->retired);
     if (e != hipSuccess) return fail_hip(ctx, "query_attn: workspace", e);
 
     RopeRowsParams rp;
@@ -599,7 +598,12 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
         tile_units += units * ((items[i].n_ctx + 63) / 64);
     }
     const int64_t target_wgs = (int64_t)ctx->n_cu * 2;
-    const int64_t split_tiles_common = std::max<int64_t>(8, (tile_units + target_wgs - 1) / target_wgs);
+    int64_t split_tiles_common = std::max<int64_t>(8, (tile_units + target_wgs - 1) / target_wgs);
+    if (ctx->force_splits > 0) {  // the longest item gets the forced split count, the others the same split length
+        int64_t longest = 1;
+        for (int32_t i = 0; i < n_items; ++i) longest = std::max<int64_t>(longest, (items[i].n_ctx + 63) / 64);
+        split_tiles_common = (longest + ctx->force_splits - 1) / ctx->force_splits;
+    }
 
     struct Plan {
         int64_t rows, n_row_tiles, n_split, keys_per_split;
@@ -639,16 +643,16 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
         return fail(ctx, ADAPSHOT_EINVAL, "query_attn_batched: batch too large for one launch");
 
     // ---- workspace and tables
-    hipError_t e = ctx->q_rot.reserve(q_bytes);
-    if (e == hipSuccess) e = ctx->k_rot.reserve(k_bytes);
-    if (e == hipSuccess) e = ctx->part_o.reserve(po_bytes);
-    if (e == hipSuccess) e = ctx->part_ml.reserve(pml_bytes);
+    hipError_t e = ctx->q_rot.reserve(q_bytes, ctx->retired);
+    if (e == hipSuccess) e = ctx->k_rot.reserve(k_bytes, ctx->retired);
+    if (e == hipSuccess) e = ctx->part_o.reserve(po_bytes, ctx->retired);
+    if (e == hipSuccess) e = ctx->part_ml.reserve(pml_bytes, ctx->retired);
     const size_t items_bytes = (size_t)n_items * sizeof(AttnBatchItem);
     const size_t attn_off = (items_bytes + 255) & ~(size_t)255;
     const size_t comb_off = (attn_off + (size_t)n_attn * sizeof(AttnWork) + 255) & ~(size_t)255;
     const size_t rope_off = (comb_off + (size_t)n_comb * sizeof(CombineWork) + 255) & ~(size_t)255;
     const size_t tab_bytes = (rope_off + (size_t)n_rope * sizeof(RopeWork) + 15) & ~(size_t)15;
-    if (e == hipSuccess) e = ctx->batch_tab.reserve(tab_bytes);
+    if (e == hipSuccess) e = ctx->batch_tab.reserve(tab_bytes, ctx->retired);
     if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: workspace", e);
     int slot = -1;
     void* host = nullptr;
@@ -801,6 +805,7 @@ static adapshot_status run_probe_entropy(adapshot_ctx* ctx, const float* logits,
                                          int32_t vocab, const AnswerTokens* answer, float* entropy_out,
                                          void* hip_stream) {
     if (n_rows < 0 || vocab < 1) return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy: n_rows < 0 or vocab < 1");
+    if (vocab > (1 << 30)) return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy: vocab beyond 2^30");
     if (n_rows == 0) {
         ctx->last_error.clear();
         return ADAPSHOT_OK;
@@ -822,7 +827,9 @@ static adapshot_status run_probe_entropy(adapshot_ctx* ctx, const float* logits,
     while (chunk > 1024 && (int64_t)n_rows * ((vocab + chunk - 1) / chunk) < (int64_t)ctx->n_cu * 4) chunk /= 2;
     p.chunk = (int32_t)chunk;
     p.n_chunks = (int32_t)((vocab + chunk - 1) / chunk);
-    hipError_t e = ctx->ent_part.reserve((size_t)n_rows * p.n_chunks * 3 * sizeof(float));
+    if ((int64_t)n_rows * p.n_chunks > INT32_MAX)
+        return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy: n_rows x vocab chunks beyond 2^31 - 1 workgroups");
+    hipError_t e = ctx->ent_part.reserve((size_t)n_rows * p.n_chunks * 3 * sizeof(float), ctx->retired);
     if (e != hipSuccess) return fail_hip(ctx, "probe_entropy: workspace", e);
     p.partials = (float*)ctx->ent_part.p;
     hipStream_t stream = (hipStream_t)hip_stream;
@@ -882,53 +889,80 @@ static adapshot_status rank_prepare(adapshot_ctx* ctx, int32_t layer, hipStream_
     const int64_t keys_target = std::max<int64_t>(512, ((n_tok + target_windows - 1) / target_windows + 63) / 64 * 64);
     std::vector<int64_t> bounds;
     std::vector<int32_t> shot0;
-    std::vector<int32_t> tok((size_t)(2 * n_tok));  // [local index | column]
-    std::vector<float> inv_len((size_t)ctx->n_shots);
+    std::vector<int32_t> shot_split((size_t)ctx->n_shots);
     bounds.push_back(0);
     shot0.push_back(0);
-    int64_t keys = 0;
-    int32_t first = 0;
-    for (int32_t i = 0; i < ctx->n_shots; ++i) {
-        const int64_t len = ctx->shot_offsets[(size_t)i + 1] - ctx->shot_offsets[(size_t)i];
-        if (i > first && (i - first >= kRankWindowShots || keys + len > keys_target)) {  // close the window before shot i
-            bounds.push_back(ctx->shot_offsets[(size_t)i]);
-            shot0.push_back(i);
-            first = i;
-            keys = 0;
-        }
-        keys += len;
-        inv_len[(size_t)i] = len > 0 ? 1.0f / (float)len : 0.f;
-        for (int64_t t = 0; t < len; ++t) {
-            tok[(size_t)(ctx->shot_offsets[(size_t)i] + t)] = (int32_t)t;
-            tok[(size_t)(n_tok + ctx->shot_offsets[(size_t)i] + t)] = i - first;
+    {
+        int64_t keys = 0;
+        int32_t first = 0;
+        for (int32_t i = 0; i < ctx->n_shots; ++i) {
+            const int64_t len = ctx->shot_offsets[(size_t)i + 1] - ctx->shot_offsets[(size_t)i];
+            if (i > first && (i - first >= kRankWindowShots || keys + len > keys_target)) {  // close the window before shot i
+                bounds.push_back(ctx->shot_offsets[(size_t)i]);
+                shot0.push_back(i);
+                first = i;
+                keys = 0;
+            }
+            keys += len;
+            shot_split[(size_t)i] = (int32_t)shot0.size() - 1;
         }
     }
     bounds.push_back(n_tok);
     shot0.push_back(ctx->n_shots);
     const int32_t n_split = (int32_t)bounds.size() - 1;
 
+    // One table blob, written into a pinned buffer and brought over by a kernel on the caller's stream:
+    // [bounds int64 | local index of every token | window column of every token | first shot of every
+    //  window | window of every shot | 1 / T_i], every part 16-byte aligned.
+    auto up16 = [](size_t v) { return (v + 15) & ~(size_t)15; };
+    const size_t off_bounds = 0;
+    const size_t off_tok = up16(off_bounds + bounds.size() * sizeof(int64_t));
+    const size_t off_shot0 = up16(off_tok + (size_t)(2 * n_tok) * sizeof(int32_t));
+    const size_t off_split = up16(off_shot0 + shot0.size() * sizeof(int32_t));
+    const size_t off_inv = up16(off_split + shot_split.size() * sizeof(int32_t));
+    const size_t tab_bytes = up16(off_inv + (size_t)ctx->n_shots * sizeof(float));
+
     const size_t layer_bytes = (size_t)n_tok * ctx->row_bytes;
     const bool rotate = d.key_state == ADAPSHOT_KEYS_UNROTATED;
-    hipError_t e = ctx->rank_v.reserve(layer_bytes);
-    if (e == hipSuccess && rotate) e = ctx->rank_k.reserve(layer_bytes);
-    if (e == hipSuccess) e = ctx->rank_tok.reserve(tok.size() * sizeof(int32_t));
-    if (e == hipSuccess) e = ctx->rank_bounds.reserve(bounds.size() * sizeof(int64_t));
-    if (e == hipSuccess) e = ctx->rank_shot0.reserve(shot0.size() * sizeof(int32_t));
-    if (e == hipSuccess) e = ctx->rank_inv_len.reserve(inv_len.size() * sizeof(float));
+    hipError_t e = ctx->rank_v.reserve(layer_bytes, ctx->retired);
+    if (e == hipSuccess && rotate) e = ctx->rank_k.reserve(layer_bytes, ctx->retired);
+    if (e == hipSuccess) e = ctx->rank_tab.reserve(tab_bytes, ctx->retired);
     if (e != hipSuccess) return fail_hip(ctx, "rank_shots: workspace", e);
-    // one-time tables: plain synchronous copies from pageable memory
-    e = hipMemcpy(ctx->rank_tok.p, tok.data(), tok.size() * sizeof(int32_t), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(ctx->rank_bounds.p, bounds.data(), bounds.size() * sizeof(int64_t), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(ctx->rank_shot0.p, shot0.data(), shot0.size() * sizeof(int32_t), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(ctx->rank_inv_len.p, inv_len.data(), inv_len.size() * sizeof(float), hipMemcpyHostToDevice);
+    int slot = -1;
+    void* host = nullptr;
+    e = ctx->tile_ring.acquire(tab_bytes, &slot, &host);
+    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: pinned tables", e);
+    memcpy((char*)host + off_bounds, bounds.data(), bounds.size() * sizeof(int64_t));
+    int32_t* tok = (int32_t*)((char*)host + off_tok);
+    float* inv_len = (float*)((char*)host + off_inv);
+    for (int32_t i = 0; i < ctx->n_shots; ++i) {
+        const int64_t t0 = ctx->shot_offsets[(size_t)i], len = ctx->shot_offsets[(size_t)i + 1] - t0;
+        const int32_t col = i - shot0[(size_t)shot_split[(size_t)i]];
+        inv_len[i] = len > 0 ? 1.0f / (float)len : 0.f;
+        for (int64_t t = 0; t < len; ++t) {
+            tok[t0 + t] = (int32_t)t;
+            tok[n_tok + t0 + t] = col;
+        }
+    }
+    memcpy((char*)host + off_shot0, shot0.data(), shot0.size() * sizeof(int32_t));
+    memcpy((char*)host + off_split, shot_split.data(), shot_split.size() * sizeof(int32_t));
+    e = launch_copy_table(ctx->rank_tab.p, host, tab_bytes, stream);
     if (e != hipSuccess) return fail_hip(ctx, "rank_shots: table copy", e);
+    e = ctx->tile_ring.mark_in_use(slot, stream);
+    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: event record", e);
+    const char* tab = (const char*)ctx->rank_tab.p;
+    ctx->rank_bounds = (const int64_t*)(tab + off_bounds);
+    ctx->rank_tok = (const int32_t*)(tab + off_tok);
+    ctx->rank_shot0 = (const int32_t*)(tab + off_shot0);
+    ctx->rank_shot_split = (const int32_t*)(tab + off_split);
+    ctx->rank_inv_len = (const float*)(tab + off_inv);
 
     RankPrepareParams rp;
     rp.k_pool = (const char*)ctx->k_pool + (int64_t)layer * ctx->pool_layer_stride_tokens * ctx->row_bytes;
     rp.k_out = rotate ? (char*)ctx->rank_k.p : nullptr;
     rp.v_out = (char*)ctx->rank_v.p;
-    rp.tok_local = (const int32_t*)ctx->rank_tok.p;
-    rp.tok_col = (const int32_t*)ctx->rank_tok.p + n_tok;
+    rp.tok_local = ctx->rank_tok;
+    rp.tok_col = ctx->rank_tok + n_tok;
     rp.tab_lo = ctx->tab_lo;
     rp.tab_hi = ctx->tab_hi;
     rp.n_tok = n_tok;
@@ -974,10 +1008,12 @@ extern "C" adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer,
     const int64_t n_pairs = rows * d.n_kv_heads;
     const int32_t n_split = ctx->rank_n_split;
     const size_t esz = (size_t)ctx->elem_bytes;
-    hipError_t e = ctx->q_rot.reserve((size_t)t_q * d.n_q_heads * d.head_dim * esz);
-    if (e == hipSuccess) e = ctx->part_o.reserve((size_t)n_split * n_pairs * d.head_dim * 2);
-    if (e == hipSuccess) e = ctx->part_ml.reserve((size_t)n_split * n_pairs * sizeof(float4));
-    if (e == hipSuccess) e = ctx->rank_w.reserve((size_t)n_split * n_pairs * sizeof(float));
+    hipError_t e = ctx->q_rot.reserve((size_t)t_q * d.n_q_heads * d.head_dim * esz, ctx->retired);
+    if (e == hipSuccess) e = ctx->part_o.reserve((size_t)n_split * n_pairs * d.head_dim * 2, ctx->retired);
+    if (e == hipSuccess) e = ctx->part_ml.reserve((size_t)n_split * n_pairs * sizeof(float4), ctx->retired);
+    if (e == hipSuccess) e = ctx->rank_w.reserve((size_t)n_split * n_pairs * sizeof(float), ctx->retired);
+    if (e == hipSuccess)
+        e = ctx->rank_part.reserve((size_t)n_split * (size_t)((n_pairs + 255) / 256) * 128 * sizeof(float), ctx->retired);
     if (e != hipSuccess) return fail_hip(ctx, "rank_shots: workspace", e);
 
     RopeRowsParams rp;
@@ -1010,7 +1046,7 @@ extern "C" adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer,
     ap.part_half = 1;
     ap.no_self = 1;
     ap.v_blocks = 1;  // rank_prepare closes a window after kRankWindowShots = 32 shots: one block of columns
-    ap.split_bounds = (const int64_t*)ctx->rank_bounds.p;
+    ap.split_bounds = ctx->rank_bounds;
     ap.out = nullptr;
     ap.n_ctx = n_tok;
     ap.keys_per_split = 64;
@@ -1027,9 +1063,11 @@ extern "C" adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer,
     rr.part_o = ctx->part_o.p;
     rr.part_mlf = (const float4*)ctx->part_ml.p;
     rr.weights = (float*)ctx->rank_w.p;
+    rr.block_part = (float*)ctx->rank_part.p;
     rr.scores = scores_out;
-    rr.split_shot0 = (const int32_t*)ctx->rank_shot0.p;
-    rr.inv_len = (const float*)ctx->rank_inv_len.p;
+    rr.split_shot0 = ctx->rank_shot0;
+    rr.shot_split = ctx->rank_shot_split;
+    rr.inv_len = ctx->rank_inv_len;
     rr.inv_rows = 1.0f / ((float)t_q * (float)d.n_q_heads);
     rr.n_split = n_split;
     rr.n_pairs = (int32_t)n_pairs;
@@ -1038,6 +1076,8 @@ extern "C" adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer,
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream, [&] { return launch_rank_weights(rr, stream); });
     if (e == hipSuccess)
         e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream, [&] { return launch_rank_reduce(rr, stream); });
+    if (e == hipSuccess)
+        e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream, [&] { return launch_rank_finish(rr, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "rank_shots: reduce launch", e);
     ctx->last_error.clear();
     return ADAPSHOT_OK;
@@ -1074,6 +1114,14 @@ extern "C" adapshot_status adapshot_pick_shots(adapshot_ctx* ctx, const float* e
     return ADAPSHOT_OK;
 }
 
+extern "C" adapshot_status adapshot_set_attn_splits(adapshot_ctx* ctx, int32_t n_split) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    if (n_split < 0 || n_split > 64) return fail(ctx, ADAPSHOT_EINVAL, "set_attn_splits: n_split must be in [0, 64]");
+    ctx->force_splits = n_split;
+    ctx->last_error.clear();
+    return ADAPSHOT_OK;
+}
+
 extern "C" adapshot_status adapshot_profile_enable(adapshot_ctx* ctx, int32_t enable) {
     if (!ctx) return ADAPSHOT_EINVAL;
     ctx->prof.on = enable != 0;
@@ -1086,6 +1134,7 @@ extern "C" adapshot_status adapshot_profile_read(adapshot_ctx* ctx, int32_t kind
         return fail(ctx, ADAPSHOT_EINVAL, "profile_read: bad kind or null pointer");
     double tot = 0.0;
     int64_t n = 0;
+    hipError_t err = hipSuccess;
     std::vector<Profiler::Rec> keep;
     for (auto& r : ctx->prof.recs) {
         if (r.kind != kind) {
@@ -1095,13 +1144,18 @@ extern "C" adapshot_status adapshot_profile_read(adapshot_ctx* ctx, int32_t kind
         hipError_t e = hipEventSynchronize(r.stop);
         float ms = 0.f;
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.start, r.stop);
-        if (e != hipSuccess) return fail_hip(ctx, "profile_read", e);
-        tot += ms;
-        ++n;
+        // a record is consumed whether or not it could be read: its events go back to the free list exactly once
         ctx->prof.free_events.push_back(r.start);
         ctx->prof.free_events.push_back(r.stop);
+        if (e != hipSuccess) {
+            if (err == hipSuccess) err = e;
+            continue;
+        }
+        tot += ms;
+        ++n;
     }
     ctx->prof.recs.swap(keep);
+    if (err != hipSuccess) return fail_hip(ctx, "profile_read", err);
     *total_ms = tot;
     *launches = n;
     return ADAPSHOT_OK;

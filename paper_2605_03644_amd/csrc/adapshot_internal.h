@@ -174,14 +174,17 @@ struct RankReduceParams {
     const void* part_o;       // [n_split][pairs][d] fp16
     const float4* part_mlf;   // [n_split][pairs]
     float* weights;           // [n_split][pairs] scratch
+    float* block_part;        // [n_split][ceil(pairs / 256)][128] scratch: per-row-block sums of every shot slot
     float* scores;            // [n_shots]
     const int32_t* split_shot0;  // [n_split + 1] first shot of every window
+    const int32_t* shot_split;   // [n_shots] window of every shot
     const float* inv_len;     // [n_shots] 1 / T_i
     float inv_rows;           // 1 / (t_q * n_q_heads)
     int32_t n_split, n_pairs, head_dim, n_shots;
 };
 hipError_t launch_rank_weights(const RankReduceParams& p, hipStream_t stream);  // merge weights of the windows
-hipError_t launch_rank_reduce(const RankReduceParams& p, hipStream_t stream);   // weighted sum over rows and heads
+hipError_t launch_rank_reduce(const RankReduceParams& p, hipStream_t stream);   // weighted sum over blocks of rows
+hipError_t launch_rank_finish(const RankReduceParams& p, hipStream_t stream);   // row blocks added in a fixed order
 
 // ---- entropy ------------------------------------------------------------------------
 struct EntropyParams {
@@ -206,7 +209,7 @@ hipError_t launch_entropy_finish_tokens(const EntropyParams& p, const AnswerToke
 struct DevBuf {
     void* p = nullptr;
     size_t bytes = 0;
-    hipError_t reserve(size_t need);  // grow-only
+    hipError_t reserve(size_t need, std::vector<void*>& retired);  // grow-only; an outgrown buffer is parked in `retired`
     void release();
 };
 
@@ -281,8 +284,15 @@ struct adapshot_ctx {
     // ranking state of one pool layer, built on first use
     int32_t rank_layer = -1;
     int32_t rank_n_split = 0;
-    adapshot::DevBuf rank_k, rank_v, rank_tok, rank_bounds, rank_shot0, rank_inv_len, rank_w;
+    adapshot::DevBuf rank_k, rank_v, rank_tab, rank_w, rank_part;
+    const int32_t* rank_tok = nullptr;       // views into rank_tab
+    const int64_t* rank_bounds = nullptr;
+    const int32_t* rank_shot0 = nullptr;
+    const int32_t* rank_shot_split = nullptr;
+    const float* rank_inv_len = nullptr;
+    std::vector<void*> retired;  // outgrown workspaces, freed when the context is destroyed
     adapshot::Profiler prof;
     int n_cu = 256;
+    int32_t force_splits = 0;  // adapshot_set_attn_splits: 0 = the planner chooses
     std::string last_error;
 };

@@ -97,13 +97,15 @@ __device__ __forceinline__ void mst_add_batch(Mst& acc, const float (&z)[N]) {
     acc.t += t;
 }
 
-// grid = (n_chunks, n_rows), 256 threads.  VEC: rows are 16-byte aligned -> float4 loads.
+// grid = n_rows * n_chunks workgroups (chunk fastest), 256 threads.  VEC: rows are 16-byte aligned -> float4 loads.
 template <bool VEC>
 __global__ __launch_bounds__(256) void entropy_chunk_kernel(EntropyParams p) {
     __shared__ Mst red[4];
     const int tid = threadIdx.x;
-    const float* z = p.logits + (int64_t)blockIdx.y * p.row_stride;
-    const int c0 = blockIdx.x * p.chunk;
+    const int row = blockIdx.x / p.n_chunks;
+    const int chunk = blockIdx.x - row * p.n_chunks;
+    const float* z = p.logits + (int64_t)row * p.row_stride;
+    const int c0 = chunk * p.chunk;
     const int c1 = min(c0 + p.chunk, p.vocab);
     Mst acc = {-INFINITY, 0.f, 0.f};
     if (VEC) {
@@ -167,7 +169,7 @@ __global__ __launch_bounds__(256) void entropy_chunk_kernel(EntropyParams p) {
     __syncthreads();
     if (tid == 0) {
         Mst r = mst_merge(mst_merge(red[0], red[1]), mst_merge(red[2], red[3]));
-        float* o = p.partials + ((int64_t)blockIdx.y * p.n_chunks + blockIdx.x) * 3;
+        float* o = p.partials + (int64_t)blockIdx.x * 3;
         o[0] = r.m;
         o[1] = r.s;
         o[2] = r.t;
@@ -238,7 +240,8 @@ hipError_t launch_entropy_finish_tokens(const EntropyParams& p, const AnswerToke
 }
 
 hipError_t launch_entropy_chunk(const EntropyParams& p, hipStream_t stream) {
-    dim3 grid((unsigned)p.n_chunks, (unsigned)p.n_rows);
+    if ((int64_t)p.n_chunks * p.n_rows > INT32_MAX) return hipErrorInvalidValue;  // the host checks this first
+    dim3 grid((unsigned)((int64_t)p.n_chunks * p.n_rows));
     const bool vec = (((uintptr_t)p.logits & 15u) == 0) && (p.row_stride % 4 == 0);
     if (vec)
         launch_kernel(entropy_chunk_kernel<true>, grid, dim3(256), stream, p);

@@ -8,8 +8,10 @@
 //                  stores un-rotated keys; Eq. prefill caches them encoded) and write the one-hot rows;
 //   rank_weights   per (kv head, row): merge the splits' (m, l) into the row's global normaliser and
 //                  leave  w[s][row] = f_s 2^(m_s - M) / L  for every split;
-//   rank_reduce    per (window, shot slot): sum w[s][row] * O'[s][row][slot] over all rows and heads,
-//                  scale by 1 / (T_q H_q T_i) and add into the shot's score.
+//   rank_reduce    per (window, block of 256 rows, shot slot): sum w[s][row] * O'[s][row][slot] over the
+//                  block's rows into a partial;
+//   rank_finish    per shot: add the row blocks' partials in a fixed order (the same query gives the same
+//                  bits every time) and scale by 1 / (T_q H_q T_i).
 #include "adapshot_internal.h"
 
 namespace adapshot {
@@ -74,10 +76,8 @@ hipError_t launch_rank_prepare(const RankPrepareParams& p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-// 16 lanes per (kv head, row) pair, lane sl taking splits sl, sl + 16, ...; also clears the scores.
+// 16 lanes per (kv head, row) pair, lane sl taking splits sl, sl + 16, ...
 __global__ __launch_bounds__(256) void rank_weights_kernel(RankReduceParams p) {
-    const int64_t gtid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    for (int64_t i = gtid; i < p.n_shots; i += (int64_t)gridDim.x * 256) p.scores[i] = 0.f;
     const int sl = threadIdx.x & 15;
     const int64_t pair = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
     const bool on = pair < p.n_pairs;  // whole 16-lane groups are on or off together
@@ -104,7 +104,7 @@ __global__ __launch_bounds__(256) void rank_weights_kernel(RankReduceParams p) {
 
 // grid = (n_split, ceil(n_pairs / 256)); 256 threads = 16 row groups x 16 lanes, a lane owning 8 shot slots
 // (16 bytes of a partial row; head_dim 128).  Row group rg takes rows pair0 + rg, + 16, ...; the 16 partial
-// sums of a slot meet in LDS, and one add per (window, slot, block) goes to the score.
+// sums of a slot meet in LDS and leave as block_part[window][row block][slot].
 __global__ __launch_bounds__(256) void rank_reduce_kernel(RankReduceParams p) {
     typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
     __shared__ float red[16][129];
@@ -131,8 +131,20 @@ __global__ __launch_bounds__(256) void rank_reduce_kernel(RankReduceParams p) {
         float t = 0.f;
 #pragma unroll
         for (int g = 0; g < 16; ++g) t += red[g][c];
-        atomicAdd(p.scores + shot0 + c, t * p.inv_rows * p.inv_len[shot0 + c]);
+        p.block_part[((int64_t)s * gridDim.y + blockIdx.y) * 128 + c] = t;
     }
+}
+
+// One thread per shot: its window's row-block partials added in index order.
+__global__ __launch_bounds__(256) void rank_finish_kernel(RankReduceParams p, int n_blocks) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= p.n_shots) return;
+    const int s = p.shot_split[i];
+    const int c = i - p.split_shot0[s];
+    const float* part = p.block_part + (int64_t)s * n_blocks * 128 + c;
+    float t = 0.f;
+    for (int b = 0; b < n_blocks; ++b) t += part[(int64_t)b * 128];
+    p.scores[i] = t * p.inv_rows * p.inv_len[i];
 }
 
 hipError_t launch_rank_weights(const RankReduceParams& p, hipStream_t stream) {
@@ -145,6 +157,13 @@ hipError_t launch_rank_reduce(const RankReduceParams& p, hipStream_t stream) {
     if (p.n_split <= 0 || p.n_pairs <= 0) return hipSuccess;
     if (p.head_dim != 128) return hipErrorInvalidValue;
     launch_kernel(rank_reduce_kernel, dim3((unsigned)p.n_split, (unsigned)((p.n_pairs + 255) / 256)), dim3(256), stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_rank_finish(const RankReduceParams& p, hipStream_t stream) {
+    if (p.n_split <= 0 || p.n_pairs <= 0 || p.n_shots <= 0) return hipSuccess;
+    launch_kernel(rank_finish_kernel, dim3((unsigned)((p.n_shots + 255) / 256)), dim3(256), stream, p,
+                  (int)((p.n_pairs + 255) / 256));
     return hipGetLastError();
 }
 

@@ -5,18 +5,6 @@ import torch
 from paper_2605_03644_amd import workloads as wl
 
 
-def bf16_bits(t: torch.Tensor) -> np.ndarray:
-    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
-
-
-def bf16_ulp_distance(a_bits: np.ndarray, b_bits: np.ndarray) -> np.ndarray:
-    """Distance in representable bf16 values (sign-magnitude patterns mapped to a line)."""
-    def line(x):
-        x = x.astype(np.int32)
-        return np.where(x & 0x8000, -(x & 0x7FFF), x & 0x7FFF)
-    return np.abs(line(a_bits) - line(b_bits))
-
-
 def check_reencode_f32(k_gpu: np.ndarray, k_exact: np.ndarray, k_src: np.ndarray, rel: float = 1e-5):
     """Per rotation pair (i, i+d/2): |y_gpu - y_exact|_2 <= rel * |x pair|_2  (rotation keeps pair norms)."""
     d = k_gpu.shape[-1]
