@@ -31,7 +31,8 @@
  *     fits the existing workspaces allocates nothing.  adapshot_assemble, the batched calls and
  *     adapshot_rank_shots write small tables into a ring of 8 pinned host buffers (hipHostMalloc
  *     when one must grow); the ninth such call in flight waits for the first one's kernels.  No
- *     call synchronises the device or the stream otherwise.
+ *     call synchronises the device or the stream otherwise.  adapshot_probe_entropy_static is the
+ *     variant of the entropy call that never allocates.
  *   - Every function validates its arguments on the host BEFORE launching
  *     anything: a call that returns an error has written nothing to device
  *     memory.  The reason is kept per context (adapshot_last_error).
@@ -200,6 +201,21 @@ adapshot_status adapshot_decode_append(adapshot_ctx* ctx, adapshot_cache* caches
 adapshot_status adapshot_probe_entropy(adapshot_ctx* ctx, const float* logits, int64_t row_stride,
                                        int32_t n_rows, int32_t vocab, float* entropy_out,
                                        void* hip_stream);
+
+/* adapshot_probe_entropy for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same results; the
+ * chunk partials go to a 768 KiB array that lives in the library's code object on every GPU it runs on
+ * (held until the process ends) instead of a workspace of the context, and nothing is allocated, freed or
+ * waited for, on the host or the device.  The array holds 65536 partials, one per (row, chunk of a row);
+ * rows are cut into chunks of 8192 logits, or of 4096, 2048 or 1024 while that leaves fewer than four
+ * workgroups per compute unit, so e.g. 128 x 128256 logits need 2048 partials and 4096 x 128256 need 65536.
+ * A call that needs more returns ECAPACITY and launches nothing; ESTATE if the context's device is not the
+ * current one.  All contexts of a process share one GPU's array: calls that overlap on the same GPU (two
+ * streams, two contexts) race and must be ordered by the caller; calls in one stream are ordered already.
+ * The launches of this entry point are not recorded by adapshot_profile_enable. */
+adapshot_status adapshot_probe_entropy_static(adapshot_ctx* ctx, const float* logits, int64_t row_stride,
+                                              int32_t n_rows, int32_t vocab, float* entropy_out,
+                                              void* hip_stream);
 
 /* Eq. (entropy) as printed: H = -sum_{c in C} p_c ln p_c over a set C of answer tokens (the probe's
  * "Yes" / "No").  Two readings of p are offered, because the case study prints entropies above ln 2:

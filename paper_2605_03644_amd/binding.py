@@ -28,7 +28,8 @@ EXPORTS = ["adapshot_create", "adapshot_destroy", "adapshot_last_error", "adapsh
            "adapshot_pool_register", "adapshot_assemble", "adapshot_query_attn", "adapshot_probe_entropy",
            "adapshot_profile_enable", "adapshot_profile_read", "adapshot_assemble_batched",
            "adapshot_query_attn_batched", "adapshot_decode_append", "adapshot_probe_entropy_tokens",
-           "adapshot_pick_shots", "adapshot_rank_shots", "adapshot_top_k", "adapshot_set_attn_splits"]
+           "adapshot_pick_shots", "adapshot_rank_shots", "adapshot_top_k", "adapshot_set_attn_splits",
+           "adapshot_probe_entropy_static"]
 ENTROPY_FULL_P, ENTROPY_RENORMALISED = 0, 1
 KERNEL_KINDS = ["assemble_reencode", "rope_rows", "query_attn", "attn_combine", "entropy_chunk", "entropy_finish"]
 
@@ -86,6 +87,8 @@ def load_library() -> ctypes.CDLL:
     L.adapshot_query_attn.argtypes = [vp, ctypes.POINTER(CacheStruct), i32, i64, vp, vp, vp, i32, i64, vp, vp]
     L.adapshot_probe_entropy.restype = ctypes.c_int
     L.adapshot_probe_entropy.argtypes = [vp, vp, i64, i32, i32, vp, vp]
+    L.adapshot_probe_entropy_static.restype = ctypes.c_int
+    L.adapshot_probe_entropy_static.argtypes = [vp, vp, i64, i32, i32, vp, vp]
     L.adapshot_probe_entropy_tokens.restype = ctypes.c_int
     L.adapshot_probe_entropy_tokens.argtypes = [vp, vp, i64, i32, i32, vp, i32, i32, vp, vp]
     L.adapshot_rank_shots.restype = ctypes.c_int
@@ -227,6 +230,17 @@ class Context:
             out = torch.empty(rows, dtype=torch.float32, device=logits.device)
         self._check(self.lib.adapshot_probe_entropy(self._h, logits.data_ptr(), logits.stride(0) if rows > 1 else vocab,
                                                     rows, vocab, out.data_ptr(), _stream_ptr(stream)))
+        return out
+
+    # -- adapshot_probe_entropy_static: `out` is required (the call itself allocates nothing)
+    def probe_entropy_static(self, logits: torch.Tensor, out: torch.Tensor,
+                             stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+        assert logits.dtype == torch.float32 and logits.dim() == 2 and logits.stride(1) == 1
+        rows, vocab = logits.shape
+        assert out.dtype == torch.float32 and out.numel() >= rows
+        self._check(self.lib.adapshot_probe_entropy_static(self._h, logits.data_ptr(),
+                                                           logits.stride(0) if rows > 1 else vocab, rows, vocab,
+                                                           out.data_ptr(), _stream_ptr(stream)))
         return out
 
     # -- adapshot_probe_entropy_tokens

@@ -229,6 +229,7 @@ extern "C" adapshot_status adapshot_create(const adapshot_model_desc* desc, adap
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->tab_hi, hi.size() * sizeof(float2));
     if (e == hipSuccess) e = hipMemcpy(ctx->tab_lo, lo.data(), lo.size() * sizeof(float2), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(ctx->tab_hi, hi.data(), hi.size() * sizeof(float2), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = entropy_static_scratch(&ctx->static_ent);  // set-up: the current device is the context's
     if (e != hipSuccess) {
         (void)hipGetLastError();
         adapshot_destroy(ctx);
@@ -800,24 +801,20 @@ extern "C" adapshot_status adapshot_query_attn_batched(adapshot_ctx* ctx, const 
     return ADAPSHOT_OK;
 }
 
-// Vocabulary-wide pass shared by both entropy entry points; `answer` selects the epilogue.
-static adapshot_status run_probe_entropy(adapshot_ctx* ctx, const float* logits, int64_t row_stride, int32_t n_rows,
-                                         int32_t vocab, const AnswerTokens* answer, float* entropy_out,
-                                         void* hip_stream) {
+// Validation and chunk plan shared by the entropy entry points; nothing is launched.
+static adapshot_status plan_probe_entropy(adapshot_ctx* ctx, const float* logits, int64_t row_stride, int32_t n_rows,
+                                          int32_t vocab, const float* entropy_out, EntropyParams* out) {
     if (n_rows < 0 || vocab < 1) return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy: n_rows < 0 or vocab < 1");
     if (vocab > (1 << 30)) return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy: vocab beyond 2^30");
-    if (n_rows == 0) {
-        ctx->last_error.clear();
-        return ADAPSHOT_OK;
-    }
+    if (n_rows == 0) return ADAPSHOT_OK;
     if (!logits || !entropy_out) return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy: null pointer");
     if (row_stride < vocab) return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy: row_stride < vocab");
     if (((uintptr_t)logits & 3u) || ((uintptr_t)entropy_out & 3u))
         return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy: pointers must be 4-byte aligned");
-
-    EntropyParams p;
+    EntropyParams& p = *out;
     p.logits = logits;
-    p.out = entropy_out;
+    p.out = const_cast<float*>(entropy_out);
+    p.partials = nullptr;
     p.row_stride = row_stride;
     p.n_rows = n_rows;
     p.vocab = vocab;
@@ -829,6 +826,20 @@ static adapshot_status run_probe_entropy(adapshot_ctx* ctx, const float* logits,
     p.n_chunks = (int32_t)((vocab + chunk - 1) / chunk);
     if ((int64_t)n_rows * p.n_chunks > INT32_MAX)
         return fail(ctx, ADAPSHOT_EINVAL, "probe_entropy: n_rows x vocab chunks beyond 2^31 - 1 workgroups");
+    return ADAPSHOT_OK;
+}
+
+// Vocabulary-wide pass shared by both entropy entry points; `answer` selects the epilogue.
+static adapshot_status run_probe_entropy(adapshot_ctx* ctx, const float* logits, int64_t row_stride, int32_t n_rows,
+                                         int32_t vocab, const AnswerTokens* answer, float* entropy_out,
+                                         void* hip_stream) {
+    EntropyParams p;
+    adapshot_status st = plan_probe_entropy(ctx, logits, row_stride, n_rows, vocab, entropy_out, &p);
+    if (st != ADAPSHOT_OK) return st;
+    if (n_rows == 0) {
+        ctx->last_error.clear();
+        return ADAPSHOT_OK;
+    }
     hipError_t e = ctx->ent_part.reserve((size_t)n_rows * p.n_chunks * 3 * sizeof(float), ctx->retired);
     if (e != hipSuccess) return fail_hip(ctx, "probe_entropy: workspace", e);
     p.partials = (float*)ctx->ent_part.p;
@@ -848,6 +859,35 @@ extern "C" adapshot_status adapshot_probe_entropy(adapshot_ctx* ctx, const float
                                                   void* hip_stream) {
     if (!ctx) return ADAPSHOT_EINVAL;
     return run_probe_entropy(ctx, logits, row_stride, n_rows, vocab, nullptr, entropy_out, hip_stream);
+}
+
+// The same two kernels over the file-scope device array instead of a workspace of the context: no
+// allocation of any kind on this path (no hipMalloc, no event creation: the launches are not profiled).
+extern "C" adapshot_status adapshot_probe_entropy_static(adapshot_ctx* ctx, const float* logits, int64_t row_stride,
+                                                         int32_t n_rows, int32_t vocab, float* entropy_out,
+                                                         void* hip_stream) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    EntropyParams p;
+    adapshot_status st = plan_probe_entropy(ctx, logits, row_stride, n_rows, vocab, entropy_out, &p);
+    if (st != ADAPSHOT_OK) return st;
+    if (n_rows == 0) {
+        ctx->last_error.clear();
+        return ADAPSHOT_OK;
+    }
+    if ((int64_t)n_rows * p.n_chunks > kStaticEntropyPartials)
+        return fail(ctx, ADAPSHOT_ECAPACITY,
+                    "probe_entropy_static: %d rows x %d chunks of %d logits need %lld partials, the static scratch holds %d",
+                    n_rows, p.n_chunks, p.chunk, (long long)n_rows * p.n_chunks, kStaticEntropyPartials);
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != ctx->device || !ctx->static_ent)
+        return fail(ctx, ADAPSHOT_ESTATE, "probe_entropy_static: the context's device must be current");
+    p.partials = ctx->static_ent;  // every (row, chunk) triple is written by the first kernel before the second reads it
+    hipStream_t stream = (hipStream_t)hip_stream;
+    hipError_t e = launch_entropy_chunk(p, stream);
+    if (e == hipSuccess) e = launch_entropy_finish(p, stream);
+    if (e != hipSuccess) return fail_hip(ctx, "probe_entropy_static: launch", e);
+    ctx->last_error.clear();
+    return ADAPSHOT_OK;
 }
 
 extern "C" adapshot_status adapshot_probe_entropy_tokens(adapshot_ctx* ctx, const float* logits, int64_t row_stride,

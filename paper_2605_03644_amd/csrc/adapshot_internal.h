@@ -194,6 +194,10 @@ struct EntropyParams {
     int64_t row_stride;
     int32_t n_rows, vocab, chunk, n_chunks;
 };
+// The file-scope device array behind adapshot_probe_entropy_static: room for this many (row, chunk) partials.
+constexpr int kStaticEntropyPartials = 65536;
+// Device address of that array on the CURRENT device (looked up once per device, then remembered).
+hipError_t entropy_static_scratch(float** out);
 hipError_t launch_entropy_chunk(const EntropyParams& p, hipStream_t stream);
 hipError_t launch_entropy_finish(const EntropyParams& p, hipStream_t stream);
 // Eq. (entropy) over a set C of answer tokens, from the same vocabulary-wide partials.
@@ -278,6 +282,7 @@ struct adapshot_ctx {
     // tables
     float2* tab_lo = nullptr;
     float2* tab_hi = nullptr;
+    float* static_ent = nullptr;  // this device's copy of the static entropy scratch array (not owned)
     // scratch
     adapshot::PinnedRing tile_ring;
     adapshot::DevBuf q_rot, k_rot, part_o, part_ml, ent_part, batch_tab;

@@ -5,11 +5,39 @@
 // One HBM pass: a workgroup reduces one chunk of one row to (m, s, t) with an online
 // rescale per 16-element batch; a second tiny kernel merges the chunks of a row.
 // Partials re-base as  s' = s * exp(m - M),  t' = (t + (m - M) * s) * exp(m - M).
+#include <mutex>
+
 #include "adapshot_internal.h"
 
 namespace adapshot {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Chunk partials of the entry point that allocates nothing: kStaticEntropyPartials (row, chunk) triples,
+// 768 KiB, held by every GPU the library runs on until the process ends.  Host code never uses this name as
+// an address: entropy_static_scratch() asks the runtime where the current device keeps its copy.
+static __device__ __align__(256) float g_entropy_scratch[(size_t)kStaticEntropyPartials * 3];
+
+hipError_t entropy_static_scratch(float** out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static float* ptr_of_device[kMaxDevices] = {};
+    *out = nullptr;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr_of_device[dev]) {  // once per device, with that device current
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_entropy_scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptr_of_device[dev] = (float*)p;
+    }
+    *out = ptr_of_device[dev];
+    return hipSuccess;
+}
 
 struct Mst {
     float m, s, t;
