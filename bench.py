@@ -37,6 +37,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 MEASURED_TRAFFIC_BYTES = {
     "llama8b_1layer": {"assemble_reencode": 221.9e6, "query_attn": 130.9e6, "entropy_chunk": 65.8e6},
 }
+PROFILE_WARMUP, PROFILE_STEPS = 50, 200   # the per-kernel pass: untimed steps, then steps with timed dispatches
 METRIC = "re-encoded KV tokens/s (HBM GB/s) + query-over-cache attn TFLOP/s at 26k ctx"
 
 
@@ -453,14 +454,19 @@ def main() -> int:
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
 
-    # Same steps again, every kernel's dispatch carrying a pair of HIP events on the launch stream.
+    # Per-kernel durations: the same steps again, every kernel's dispatch carrying a pair of HIP events on the
+    # launch stream.  This pass has a length of its own, whatever --steps says, so that a short run reports the
+    # same figures as a long one: PROFILE_WARMUP further untimed steps, then PROFILE_STEPS recorded ones.
+    for i in range(PROFILE_WARMUP):
+        step(i)
     ctx.profile_enable(True)
-    for i in range(args.steps):
+    for i in range(PROFILE_STEPS):
         step(i)
     torch.cuda.synchronize()
-    prof = ctx.profile_read()
+    prof = ctx.profile_read_each()
     ctx.profile_enable(False)
-    kern = {k: dict(avg_us=ms / max(n, 1) * 1e3, launches=n) for k, (ms, n) in prof.items()}
+    kern = {k: dict(avg_us=float(ms.mean()) * 1e3, median_us=float(np.median(ms)) * 1e3, min_us=float(ms.min()) * 1e3,
+                    launches=int(ms.size)) for k, ms in prof.items() if ms.size}
 
     t_ctx = tokens / args.steps
     row_bytes = w.kv_bytes_per_token_layer          # K row + V row
@@ -470,17 +476,22 @@ def main() -> int:
     asm_us, attn_us, ent_us = (kern[k]["avg_us"] for k in ("assemble_reencode", "query_attn", "entropy_chunk"))
     rl = {
         "assemble_reencode": dict(bound="hbm", achieved=asm_bytes / asm_us * 1e-3, peak=HBM_PEAK_GBPS, unit="GB/s",
-                                  traffic=None, avg_us=asm_us, algorithmic_bytes=asm_bytes),
+                                  traffic=None, avg_us=asm_us, median_us=kern['assemble_reencode']['median_us'], min_us=kern['assemble_reencode']['min_us'], algorithmic_bytes=asm_bytes),
         "query_attn": dict(bound="mfma", achieved=flops / attn_us * 1e-6, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
-                           traffic=None, avg_us=attn_us, algorithmic_flops=flops),
+                           traffic=None, avg_us=attn_us, median_us=kern['query_attn']['median_us'],
+                           min_us=kern['query_attn']['min_us'], algorithmic_flops=flops),
         "entropy_chunk": dict(bound="hbm", achieved=ent_bytes / ent_us * 1e-3, peak=HBM_PEAK_GBPS, unit="GB/s",
-                              traffic=None, avg_us=ent_us, algorithmic_bytes=ent_bytes),
+                              traffic=None, avg_us=ent_us, median_us=kern['entropy_chunk']['median_us'],
+                              min_us=kern['entropy_chunk']['min_us'], algorithmic_bytes=ent_bytes),
     }
     for name, r in rl.items():
         r["frac"] = r["achieved"] / r["peak"]
         r["traffic"] = MEASURED_TRAFFIC_BYTES.get(w.name, {}).get(name)
+        r["traffic_source"] = "profiles/bench_llama8b_1layer_hbm_traffic.txt (rocprofv3 --pmc of this script), not read in this run"
     dominant = max(rl, key=lambda k: rl[k]["avg_us"])
-    roofline = dict(kernel=dominant, **{k: rl[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")})
+    roofline = dict(kernel=dominant, **{k: rl[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic",
+                                                                       "traffic_source", "avg_us", "median_us", "min_us")},
+                    launches_timed=PROFILE_STEPS, untimed_steps_before=args.warmup + args.steps + PROFILE_WARMUP)
 
     result = {
         "metric": METRIC, "value": tokens / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -493,6 +504,7 @@ def main() -> int:
         "roofline": roofline,
         "roofline_all": rl,
         "kernels_us": {k: round(v["avg_us"], 3) for k, v in kern.items()},
+        "kernels_median_us": {k: round(v["median_us"], 3) for k, v in kern.items()},
         "assemble_gbps": rl["assemble_reencode"]["achieved"],
         "attn_tflops": rl["query_attn"]["achieved"],
         "entropy_gbps": rl["entropy_chunk"]["achieved"],

@@ -285,6 +285,10 @@ typedef enum {
 } adapshot_kernel_kind;
 adapshot_status adapshot_profile_enable(adapshot_ctx* ctx, int32_t enable);
 adapshot_status adapshot_profile_read(adapshot_ctx* ctx, int32_t kind, double* total_ms, int64_t* launches);
+/* The same, every launch on its own: the first min(*launches, capacity) durations in milliseconds, in launch
+ * order, go to ms_out (HOST); *launches is the number recorded, all of which are forgotten. */
+adapshot_status adapshot_profile_read_each(adapshot_ctx* ctx, int32_t kind, float* ms_out, int64_t capacity,
+                                           int64_t* launches);
 
 #ifdef __cplusplus
 }

@@ -26,7 +26,7 @@ KEYS_UNROTATED, KEYS_ROTATED_LOCAL = 0, 1
 # every symbol declared in include/adapshot.h
 EXPORTS = ["adapshot_create", "adapshot_destroy", "adapshot_last_error", "adapshot_version",
            "adapshot_pool_register", "adapshot_assemble", "adapshot_query_attn", "adapshot_probe_entropy",
-           "adapshot_profile_enable", "adapshot_profile_read", "adapshot_assemble_batched",
+           "adapshot_profile_enable", "adapshot_profile_read", "adapshot_profile_read_each", "adapshot_assemble_batched",
            "adapshot_query_attn_batched", "adapshot_decode_append", "adapshot_probe_entropy_tokens",
            "adapshot_pick_shots", "adapshot_rank_shots", "adapshot_top_k", "adapshot_set_attn_splits",
            "adapshot_probe_entropy_static"]
@@ -109,6 +109,8 @@ def load_library() -> ctypes.CDLL:
     L.adapshot_profile_enable.argtypes = [vp, i32]
     L.adapshot_profile_read.restype = ctypes.c_int
     L.adapshot_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    L.adapshot_profile_read_each.restype = ctypes.c_int
+    L.adapshot_profile_read_each.argtypes = [vp, i32, vp, i64, ctypes.POINTER(i64)]
     _lib = L
     return L
 
@@ -359,4 +361,16 @@ class Context:
             ms, n = ctypes.c_double(), ctypes.c_int64()
             self._check(self.lib.adapshot_profile_read(self._h, kind, ctypes.byref(ms), ctypes.byref(n)))
             out[name] = (ms.value, n.value)
+        return out
+
+    def profile_read_each(self, capacity: int = 1 << 16) -> dict:
+        """{kernel kind: float32 array of the durations in ms, in launch order} of the launches recorded since
+        the last read (at most `capacity` per kind are returned)."""
+        out = {}
+        for kind, name in enumerate(KERNEL_KINDS):
+            buf = np.empty(capacity, np.float32)
+            n = ctypes.c_int64()
+            self._check(self.lib.adapshot_profile_read_each(self._h, kind, buf.ctypes.data_as(ctypes.c_void_p),
+                                                            capacity, ctypes.byref(n)))
+            out[name] = buf[:min(n.value, capacity)].copy()
         return out

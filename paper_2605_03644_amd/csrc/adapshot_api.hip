@@ -1168,12 +1168,10 @@ extern "C" adapshot_status adapshot_profile_enable(adapshot_ctx* ctx, int32_t en
     return ADAPSHOT_OK;
 }
 
-extern "C" adapshot_status adapshot_profile_read(adapshot_ctx* ctx, int32_t kind, double* total_ms, int64_t* launches) {
-    if (!ctx) return ADAPSHOT_EINVAL;
-    if (kind < 0 || kind >= ADAPSHOT_KERNEL_KINDS || !total_ms || !launches)
-        return fail(ctx, ADAPSHOT_EINVAL, "profile_read: bad kind or null pointer");
-    double tot = 0.0;
-    int64_t n = 0;
+// Shared by the two read calls: waits for the recorded launches of one kind, hands every duration to `sink`
+// in launch order and forgets the records.
+template <typename Sink>
+static adapshot_status profile_drain(adapshot_ctx* ctx, int32_t kind, Sink&& sink) {
     hipError_t err = hipSuccess;
     std::vector<Profiler::Rec> keep;
     for (auto& r : ctx->prof.recs) {
@@ -1191,12 +1189,38 @@ extern "C" adapshot_status adapshot_profile_read(adapshot_ctx* ctx, int32_t kind
             if (err == hipSuccess) err = e;
             continue;
         }
-        tot += ms;
-        ++n;
+        sink(ms);
     }
     ctx->prof.recs.swap(keep);
     if (err != hipSuccess) return fail_hip(ctx, "profile_read", err);
+    return ADAPSHOT_OK;
+}
+
+extern "C" adapshot_status adapshot_profile_read(adapshot_ctx* ctx, int32_t kind, double* total_ms, int64_t* launches) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    if (kind < 0 || kind >= ADAPSHOT_KERNEL_KINDS || !total_ms || !launches)
+        return fail(ctx, ADAPSHOT_EINVAL, "profile_read: bad kind or null pointer");
+    double tot = 0.0;
+    int64_t n = 0;
+    adapshot_status st = profile_drain(ctx, kind, [&](float ms) {
+        tot += ms;
+        ++n;
+    });
     *total_ms = tot;
     *launches = n;
-    return ADAPSHOT_OK;
+    return st;
+}
+
+extern "C" adapshot_status adapshot_profile_read_each(adapshot_ctx* ctx, int32_t kind, float* ms_out, int64_t capacity,
+                                                      int64_t* launches) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    if (kind < 0 || kind >= ADAPSHOT_KERNEL_KINDS || !launches || capacity < 0 || (capacity > 0 && !ms_out))
+        return fail(ctx, ADAPSHOT_EINVAL, "profile_read_each: bad kind, capacity or null pointer");
+    int64_t n = 0;
+    adapshot_status st = profile_drain(ctx, kind, [&](float ms) {
+        if (n < capacity) ms_out[n] = ms;
+        ++n;
+    });
+    *launches = n;
+    return st;
 }
