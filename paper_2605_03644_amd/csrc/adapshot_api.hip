@@ -198,6 +198,10 @@ extern "C" adapshot_status adapshot_create(const adapshot_model_desc* desc, adap
     ctx->row_bytes = (int64_t)desc->n_kv_heads * desc->head_dim * ctx->elem_bytes;
     ctx->max_position = desc->max_position ? desc->max_position : ((int64_t)1 << 20);
     ctx->desc.max_position = ctx->max_position;
+    // tokens of a tile per assemble workgroup: about 16 KB per layer and operand
+    int wg_tok = kTileTok;
+    while (wg_tok > 1 && (int64_t)wg_tok * ctx->row_bytes > 16384) wg_tok /= 2;
+    ctx->assemble_wg_tok = wg_tok;
 
     hipError_t e = hipGetDevice(&ctx->device);
     if (e != hipSuccess) {
@@ -325,74 +329,97 @@ static adapshot_status check_assemble(adapshot_ctx* ctx, const adapshot_cache* c
     return ADAPSHOT_OK;
 }
 
-// Plan (prefix sums -> tile descriptors) and launch of one validated assemble call.
-static adapshot_status run_assemble(adapshot_ctx* ctx, adapshot_cache* cache, const int32_t* shot_ids,
-                                    const int32_t* order, int32_t m, int64_t pos0, int64_t total, int64_t n_tiles,
+// One validated assemble job of a batch.
+struct AssembleJob {
+    adapshot_cache* cache;
+    const int32_t* shot_ids;
+    const int32_t* order;
+    int32_t m;
+    int64_t total, n_tiles;
+};
+
+// Plan (prefix sums -> tile descriptors) and launch of validated assemble jobs: one launch per group of
+// up to kAssembleBatch caches, the tiles of a group's caches in one descriptor list.
+static adapshot_status run_assemble(adapshot_ctx* ctx, AssembleJob* jobs, int32_t n_jobs, int64_t pos0,
                                     hipStream_t stream) {
-    if (total == 0) return ADAPSHOT_OK;
-    int slot;
-    void* host;
-    hipError_t e = ctx->tile_ring.acquire((size_t)n_tiles * sizeof(TileDesc), &slot, &host);
-    if (e != hipSuccess) return fail_hip(ctx, "assemble: pinned tile buffer", e);
-
-    // slot group j starts at off_j = sum of the lengths before it
-    TileDesc* tiles = (TileDesc*)host;
     const bool local = ctx->desc.key_state == ADAPSHOT_KEYS_ROTATED_LOCAL;
-    int64_t slot0 = cache->len, nt = 0;
-    for (int32_t j = 0; j < m; ++j) {
-        int32_t s = shot_ids[order ? order[j] : j];
-        int64_t src = ctx->shot_offsets[s], len = ctx->shot_offsets[s + 1] - src;
-        for (int64_t t0 = 0; t0 < len; t0 += kTileTok) {
-            TileDesc& d = tiles[nt++];
-            d.src_tok = (int32_t)(src + t0);
-            d.dst_slot = (int32_t)(slot0 + t0);
-            d.pos_first = (int32_t)(pos0 + slot0 + t0);
-            d.angle0 = local ? (int32_t)(pos0 + slot0) : d.pos_first;
-            d.angle_step = local ? 0 : 1;
-            d.n_tok = (int32_t)std::min<int64_t>(kTileTok, len - t0);
-            d.shot = s;
-            d.tok0 = (int32_t)t0;
+    for (int32_t j0 = 0; j0 < n_jobs; j0 += kAssembleBatch) {
+        const int32_t j1 = std::min<int32_t>(n_jobs, j0 + kAssembleBatch);
+        int64_t group_tiles = 0;
+        for (int32_t b = j0; b < j1; ++b) group_tiles += jobs[b].n_tiles;
+        if (group_tiles == 0) continue;
+        if (group_tiles > INT32_MAX / kTileTok) return fail(ctx, ADAPSHOT_EINVAL, "assemble: too many tiles");
+        int slot;
+        void* host;
+        hipError_t e = ctx->tile_ring.acquire((size_t)group_tiles * sizeof(TileDesc), &slot, &host);
+        if (e != hipSuccess) return fail_hip(ctx, "assemble: pinned tile buffer", e);
+        TileDesc* tiles = (TileDesc*)host;
+        AssembleParams p;
+        int64_t nt = 0;
+        for (int32_t b = j0; b < j1; ++b) {
+            const AssembleJob& jb = jobs[b];
+            AssembleDst& dc = p.dst[b - j0];
+            dc.k_out = (char*)jb.cache->k;
+            dc.v_out = (char*)jb.cache->v;
+            dc.slot_shot = jb.cache->slot_shot;
+            dc.slot_tok = jb.cache->slot_tok;
+            dc.slot_pos = jb.cache->slot_pos;
+            dc.layer_stride_bytes = jb.cache->capacity * ctx->row_bytes;
+            dc.pos0 = pos0;
+            // slot group j starts at off_j = sum of the lengths before it
+            int64_t slot0 = jb.cache->len;
+            for (int32_t j = 0; j < jb.m; ++j) {
+                const int32_t s = jb.shot_ids[jb.order ? jb.order[j] : j];
+                const int64_t src = ctx->shot_offsets[s], len = ctx->shot_offsets[s + 1] - src;
+                for (int64_t t0 = 0; t0 < len; t0 += kTileTok) {
+                    TileDesc& d = tiles[nt++];
+                    d.src_tok = (int32_t)(src + t0);
+                    d.dst_slot = (int32_t)(slot0 + t0);
+                    d.angle0 = (int32_t)(local ? pos0 + slot0 : pos0 + slot0 + t0);
+                    d.angle_step = local ? 0 : 1;
+                    d.n_tok = (int32_t)std::min<int64_t>(kTileTok, len - t0);
+                    d.shot = s;
+                    d.tok0 = (int32_t)t0;
+                    d.cache = b - j0;
+                }
+                slot0 += len;
+            }
         }
-        slot0 += len;
+        for (int32_t i = j1 - j0; i < kAssembleBatch; ++i) p.dst[i] = AssembleDst{};
+        p.k_pool = (const char*)ctx->k_pool;
+        p.v_pool = (const char*)ctx->v_pool;
+        p.tiles = tiles;
+        p.tab_lo = ctx->tab_lo;
+        p.tab_hi = ctx->tab_hi;
+        p.pool_layer_stride_bytes = ctx->pool_layer_stride_tokens * ctx->row_bytes;
+        p.n_tiles = (int32_t)nt;
+        p.n_layers = ctx->desc.n_layers;
+        p.n_dst = j1 - j0;
+        p.wg_tok = ctx->assemble_wg_tok;
+        // Enough workgroups to fill the chip several times over; beyond that a group walks its layers
+        // so that the per-token cos/sin are formed once and reused.
+        const int64_t wgs = nt * (kTileTok / p.wg_tok);
+        const int64_t want_groups = ((int64_t)ctx->n_cu * 32 + wgs - 1) / wgs;
+        p.layer_groups = (int32_t)std::max<int64_t>(1, std::min<int64_t>(ctx->desc.n_layers, want_groups));
+        p.n_kv_heads = ctx->desc.n_kv_heads;
+        p.head_dim = ctx->desc.head_dim;
+        p.dtype = ctx->desc.dtype;
+        e = timed_launch(ctx, ADAPSHOT_KERNEL_ASSEMBLE, stream, [&] { return launch_assemble(p, stream); });
+        if (e != hipSuccess) return fail_hip(ctx, "assemble: launch", e);
+        e = ctx->tile_ring.mark_in_use(slot, stream);
+        if (e != hipSuccess) return fail_hip(ctx, "assemble: event record", e);
+        for (int32_t b = j0; b < j1; ++b) jobs[b].cache->len += jobs[b].total;
     }
-
-    AssembleParams p;
-    p.k_pool = (const char*)ctx->k_pool;
-    p.v_pool = (const char*)ctx->v_pool;
-    p.k_out = (char*)cache->k;
-    p.v_out = (char*)cache->v;
-    p.tiles = tiles;
-    p.tab_lo = ctx->tab_lo;
-    p.tab_hi = ctx->tab_hi;
-    p.slot_shot = cache->slot_shot;
-    p.slot_tok = cache->slot_tok;
-    p.slot_pos = cache->slot_pos;
-    p.pool_layer_stride_bytes = ctx->pool_layer_stride_tokens * ctx->row_bytes;
-    p.cache_layer_stride_bytes = cache->capacity * ctx->row_bytes;
-    p.n_tiles = (int32_t)nt;
-    p.n_layers = ctx->desc.n_layers;
-    // Enough workgroups to fill the chip several times over; beyond that a group walks its layers
-    // so that the per-token cos/sin are formed once and reused.
-    int64_t want_groups = ((int64_t)ctx->n_cu * 16 + nt - 1) / nt;
-    p.layer_groups = (int32_t)std::max<int64_t>(1, std::min<int64_t>(ctx->desc.n_layers, want_groups));
-    p.n_kv_heads = ctx->desc.n_kv_heads;
-    p.head_dim = ctx->desc.head_dim;
-    p.dtype = ctx->desc.dtype;
-    e = timed_launch(ctx, ADAPSHOT_KERNEL_ASSEMBLE, stream, [&] { return launch_assemble(p, stream); });
-    if (e != hipSuccess) return fail_hip(ctx, "assemble: launch", e);
-    e = ctx->tile_ring.mark_in_use(slot, stream);
-    if (e != hipSuccess) return fail_hip(ctx, "assemble: event record", e);
-    cache->len += total;
     return ADAPSHOT_OK;
 }
 
 extern "C" adapshot_status adapshot_assemble(adapshot_ctx* ctx, adapshot_cache* cache, const int32_t* shot_ids,
                                              const int32_t* order, int32_t m, int64_t pos0, void* hip_stream) {
     if (!ctx) return ADAPSHOT_EINVAL;
-    int64_t total = 0, n_tiles = 0;
-    adapshot_status st = check_assemble(ctx, cache, shot_ids, order, m, pos0, &total, &n_tiles);
+    AssembleJob job{cache, shot_ids, order, m, 0, 0};
+    adapshot_status st = check_assemble(ctx, cache, shot_ids, order, m, pos0, &job.total, &job.n_tiles);
     if (st != ADAPSHOT_OK) return st;
-    st = run_assemble(ctx, cache, shot_ids, order, m, pos0, total, n_tiles, (hipStream_t)hip_stream);
+    st = run_assemble(ctx, &job, 1, pos0, (hipStream_t)hip_stream);
     if (st == ADAPSHOT_OK) ctx->last_error.clear();
     return st;
 }
@@ -403,20 +430,18 @@ extern "C" adapshot_status adapshot_assemble_batched(adapshot_ctx* ctx, adapshot
     if (!ctx) return ADAPSHOT_EINVAL;
     if (n_caches < 0) return fail(ctx, ADAPSHOT_EINVAL, "assemble_batched: n_caches < 0");
     if (n_caches > 0 && (!caches || !shot_ids || !m)) return fail(ctx, ADAPSHOT_EINVAL, "assemble_batched: null pointer");
-    std::vector<int64_t> total(n_caches), n_tiles(n_caches);
+    std::vector<AssembleJob> jobs((size_t)n_caches);
     for (int32_t b = 0; b < n_caches; ++b) {  // every item is validated before anything is launched
         for (int32_t c = 0; c < b; ++c)
             if (caches[c].k == caches[b].k || caches[c].v == caches[b].v)
                 return fail(ctx, ADAPSHOT_EINVAL, "assemble_batched: caches %d and %d share a buffer", c, b);
+        jobs[(size_t)b] = AssembleJob{&caches[b], shot_ids[b], orders ? orders[b] : nullptr, m[b], 0, 0};
         adapshot_status st = check_assemble(ctx, &caches[b], shot_ids[b], orders ? orders[b] : nullptr, m[b], pos0,
-                                            &total[b], &n_tiles[b]);
+                                            &jobs[(size_t)b].total, &jobs[(size_t)b].n_tiles);
         if (st != ADAPSHOT_OK) return st;
     }
-    for (int32_t b = 0; b < n_caches; ++b) {
-        adapshot_status st = run_assemble(ctx, &caches[b], shot_ids[b], orders ? orders[b] : nullptr, m[b], pos0,
-                                          total[b], n_tiles[b], (hipStream_t)hip_stream);
-        if (st != ADAPSHOT_OK) return st;
-    }
+    adapshot_status st = run_assemble(ctx, jobs.data(), n_caches, pos0, (hipStream_t)hip_stream);
+    if (st != ADAPSHOT_OK) return st;
     ctx->last_error.clear();
     return ADAPSHOT_OK;
 }

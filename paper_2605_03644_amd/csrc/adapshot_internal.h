@@ -22,38 +22,48 @@ constexpr int kRopeLo = 1 << kRopeLoBits;
 // ---- assemble tiles -------------------------------------------------------------
 // One tile = up to kTileTok consecutive tokens of ONE shot: contiguous in the pool
 // and contiguous in the cache.  Angle of token tau in the tile: angle0 + tau*angle_step.
+// A launch serves up to kAssembleBatch caches: a tile names its cache, and the caches'
+// buffers travel in the kernel arguments.
 constexpr int kTileTok = 32;
 struct TileDesc {
     int32_t src_tok;     // first pool token (index inside a layer)
-    int32_t dst_slot;    // first cache slot
+    int32_t dst_slot;    // first cache slot; the token's new position is the cache's pos0 + slot
     int32_t angle0;      // angle multiplier of the first token
     int32_t n_tok;       // 1..kTileTok
     int32_t angle_step;  // 1: keys un-rotated (angle = position); 0: rotated at local positions (angle = shot offset)
     int32_t shot;        // pool shot id
     int32_t tok0;        // index of the first token inside its shot
-    int32_t pos_first;   // new position of the first token
+    int32_t cache;       // index into AssembleParams::dst
 };
 static_assert(sizeof(TileDesc) == 32, "TileDesc is read as two 16-byte words");
+
+constexpr int kAssembleBatch = 48;
+struct AssembleDst {  // one cache of the launch
+    char* k_out;
+    char* v_out;
+    int32_t* slot_shot;
+    int32_t* slot_tok;
+    int64_t* slot_pos;
+    int64_t layer_stride_bytes;
+    int64_t pos0;
+};
 
 struct AssembleParams {
     const char* k_pool;
     const char* v_pool;
-    char* k_out;
-    char* v_out;
     const TileDesc* tiles;  // pinned host memory, read by the kernel
     const float2* tab_lo;
     const float2* tab_hi;
-    int32_t* slot_shot;
-    int32_t* slot_tok;
-    int64_t* slot_pos;
     int64_t pool_layer_stride_bytes;
-    int64_t cache_layer_stride_bytes;
     int32_t n_tiles;
     int32_t n_layers;
     int32_t layer_groups;  // gridDim.y; each group strides over the layers
+    int32_t n_dst;         // caches of this launch (entries of dst in use)
+    int32_t wg_tok;        // tokens of a tile per workgroup: a power of two <= kTileTok (kTileTok / wg_tok workgroups per tile)
     int32_t n_kv_heads;
     int32_t head_dim;
     int32_t dtype;
+    AssembleDst dst[kAssembleBatch];
 };
 hipError_t launch_assemble(const AssembleParams& p, hipStream_t stream);
 
@@ -298,6 +308,7 @@ struct adapshot_ctx {
     std::vector<void*> retired;  // outgrown workspaces, freed when the context is destroyed
     adapshot::Profiler prof;
     int n_cu = 256;
+    int32_t assemble_wg_tok = adapshot::kTileTok;  // tokens of a tile per assemble workgroup
     int32_t force_splits = 0;  // adapshot_set_attn_splits: 0 = the planner chooses
     std::string last_error;
 };

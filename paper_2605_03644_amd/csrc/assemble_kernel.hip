@@ -6,7 +6,13 @@
 // wavefront access is a run of full 128-byte lines.  HBM-bound: per token and layer
 // the kernel reads one K row and one V row and writes one of each.
 //
-//   blockIdx.x = tile, blockIdx.y = layer group (strides over layers), blockIdx.z = 0: K, 1: V.
+//   blockIdx.x = (tile, part of the tile), blockIdx.y = layer group (strides over layers), blockIdx.z = 0: K, 1: V.
+// A workgroup takes wg_tok consecutive tokens of a tile, about 16 KB per layer and operand, and keeps 64 bytes
+// per lane in flight with 58 registers (8 wavefronts per SIMD): many small workgroups stream faster on this part
+// than few large ones (plain gather copies into 2 GB: 5.5 TB/s in 16 KB blocks, 5.2 TB/s in 64 KB and larger
+// blocks).  The tile's cache -- its buffers, its
+// layer stride, its position base -- comes from the table in the kernel arguments, so one launch fills the
+// caches of a whole batch of queries.
 //
 // K workgroups first form cos/sin(a*theta_i) for every (token, frequency) of the tile
 // ONCE into LDS -- one fp32 angle addition of two fp64-built table entries,
@@ -72,11 +78,17 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
     __shared__ float2 cs[kTileTok * HALF];
 
     const int tid = threadIdx.x;
-    const TileDesc td = p.tiles[blockIdx.x];
-    const int n_tok = td.n_tok;
+    const int parts = kTileTok / p.wg_tok;
+    const TileDesc td = p.tiles[blockIdx.x / parts];
+    const int t_first = (int)(blockIdx.x % parts) * p.wg_tok;  // this workgroup's tokens of the tile: t_first .. t_first + n_tok - 1
+    const int n_tok = td.n_tok - t_first < p.wg_tok ? td.n_tok - t_first : p.wg_tok;
+    if (n_tok <= 0) return;  // a ragged tile's last parts are empty (workgroup-uniform)
+    // the first cache's entry is read without waiting for the descriptor: a launch for one cache needs no other
+    AssembleDst dc = p.dst[0];
+    if (p.n_dst != 1) dc = p.dst[__builtin_amdgcn_readfirstlane(td.cache)];
     const int64_t row_bytes = (int64_t)p.n_kv_heads * HEAD_BYTES;
-    const int64_t src_off = (int64_t)td.src_tok * row_bytes;
-    const int64_t dst_off = (int64_t)td.dst_slot * row_bytes;
+    const int64_t src_off = (int64_t)(td.src_tok + t_first) * row_bytes;
+    const int64_t dst_off = (int64_t)(td.dst_slot + t_first) * row_bytes;
 
     if (blockIdx.z == 1) {
         // ---- V: dense copy of n_tok rows per layer, one step (4 x 16 bytes per lane) ahead ----
@@ -88,7 +100,7 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
                 if (i0 + 256 * u < n16) r[u] = ld16(src + ((int64_t)(i0 + 256 * u) << 4));
         };
         auto vstore = [&](int l, int i0, u32x4(&r)[4]) __attribute__((always_inline)) {
-            char* dst = p.v_out + (int64_t)l * p.cache_layer_stride_bytes + dst_off;
+            char* dst = dc.v_out + (int64_t)l * dc.layer_stride_bytes + dst_off;
 #pragma unroll
             for (int u = 0; u < 4; ++u)
                 if (i0 + 256 * u < n16) st16(dst + ((int64_t)(i0 + 256 * u) << 4), r[u]);
@@ -118,22 +130,25 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
 
     // ---- K ----
     if (blockIdx.y == 0 && tid < n_tok) {
-        if (p.slot_shot) p.slot_shot[td.dst_slot + tid] = td.shot;
-        if (p.slot_tok) p.slot_tok[td.dst_slot + tid] = td.tok0 + tid;
-        if (p.slot_pos) p.slot_pos[td.dst_slot + tid] = (int64_t)td.pos_first + tid;
+        const int slot = td.dst_slot + t_first + tid;
+        if (dc.slot_shot) dc.slot_shot[slot] = td.shot;
+        if (dc.slot_tok) dc.slot_tok[slot] = td.tok0 + t_first + tid;
+        if (dc.slot_pos) dc.slot_pos[slot] = dc.pos0 + slot;
     }
 
     const int rpt = p.n_kv_heads * CH;  // lane items per token: (head, chunk)
     const int n_items = n_tok * rpt;
-    // One step of the K stream: up to 4 (head, chunk) items per lane, both pair partners of each.
+    // One step of the K stream: up to KI (head, chunk) items per lane, both pair partners of each
+    // (2 * KI 16-byte loads in flight per lane, the same as a V step).
+    constexpr int KI = 2;
     struct Step {
-        u32x4 a[4], b[4];
-        int64_t off[4];
-        int csi[4];
+        u32x4 a[KI], b[KI];
+        int64_t off[KI];
+        int csi[KI];
     };
     auto load_step = [&](const char* src, int base, Step& st) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < KI; ++u) {
             const int f = base + u * 256 + tid;
             if (f < n_items) {
                 const int tau = f / rpt;
@@ -149,7 +164,7 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
     };
     auto store_step = [&](char* dst, int base, Step& st) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < KI; ++u) {
             const int f = base + u * 256 + tid;
             if (f < n_items) {
                 rotate_chunks<DTYPE>(st.a[u], st.b[u], cs + st.csi[u]);
@@ -168,7 +183,7 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
     for (int it = tid; it < n_tok * (HALF / 2); it += 256) {
         const int tau = it / (HALF / 2);
         const int f2 = it - tau * (HALF / 2);
-        const int a = td.angle0 + tau * td.angle_step;
+        const int a = td.angle0 + (t_first + tau) * td.angle_step;
         const f32x4 h = *(const f32x4*)(p.tab_hi + (int64_t)(a >> kRopeLoBits) * HALF + 2 * f2);
         const f32x4 l = *(const f32x4*)(p.tab_lo + (a & (kRopeLo - 1)) * HALF + 2 * f2);
         f32x4 r;
@@ -186,7 +201,7 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
     bool have = l0 < p.n_layers;
     Step cur = first;
     while (have) {
-        int ln = l, bn = base + 1024;
+        int ln = l, bn = base + KI * 256;
         if (bn >= n_items) {
             bn = 0;
             ln += p.layer_groups;
@@ -194,7 +209,7 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
         const bool more = ln < p.n_layers;
         Step nxt;
         if (more) load_step(p.k_pool + (int64_t)ln * p.pool_layer_stride_bytes + src_off, bn, nxt);
-        store_step(p.k_out + (int64_t)l * p.cache_layer_stride_bytes + dst_off, base, cur);
+        store_step(dc.k_out + (int64_t)l * dc.layer_stride_bytes + dst_off, base, cur);
         cur = nxt;
         l = ln;
         base = bn;
@@ -204,7 +219,7 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
 
 template <int DTYPE, int CH>
 static hipError_t launch_t(const AssembleParams& p, hipStream_t stream) {
-    dim3 grid((unsigned)p.n_tiles, (unsigned)p.layer_groups, 2);
+    dim3 grid((unsigned)p.n_tiles * (unsigned)(kTileTok / p.wg_tok), (unsigned)p.layer_groups, 2);
     launch_kernel((assemble_reencode_kernel<DTYPE, CH>), grid, dim3(256), stream, p);
     return hipGetLastError();
 }
@@ -213,6 +228,8 @@ hipError_t launch_assemble(const AssembleParams& p, hipStream_t stream) {
     const int e = p.dtype == ADAPSHOT_BF16 ? 2 : 4;
     const int ch = p.head_dim / 2 * e / 16;
     if (p.n_tiles <= 0) return hipSuccess;
+    if (p.wg_tok < 1 || p.wg_tok > kTileTok || (p.wg_tok & (p.wg_tok - 1)) != 0) return hipErrorInvalidValue;
+    if ((int64_t)p.n_tiles * (kTileTok / p.wg_tok) > INT32_MAX) return hipErrorInvalidValue;
     if (p.dtype == ADAPSHOT_BF16) {
         switch (ch) {
             case 1: return launch_t<ADAPSHOT_BF16, 1>(p, stream);

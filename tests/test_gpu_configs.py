@@ -277,3 +277,44 @@ def test_byte_offsets_beyond_4gib_in_pool_and_cache(ad, oracle_mod):
         assert np.array_equal(H.to_storage(cache.v[layer, total]), vn[layer, 0])
         assert not cache.k[layer, total + 1:total + 4096].any()
     ctx.close()
+
+
+def test_assemble_batched_many_caches_one_call(ad, oracle_mod):
+    """53 caches in one adapshot_assemble_batched call (more than one launch's table of caches holds): ragged
+    selections, an empty one, duplicates, appended after a first call; every cache against the oracle."""
+    w = wl.WORKLOADS["tiny_fp32"]
+    L = 2
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=L)
+    ctx = ad.Context.for_workload(w, n_layers=L)
+    ctx.pool_register(k_pool, v_pool, off)
+    rng = np.random.default_rng(53)
+    n_c = 53
+    first = [rng.integers(0, w.n_shots, rng.integers(0, 4)).astype(np.int32) for _ in range(n_c)]
+    second = [rng.integers(0, w.n_shots, rng.integers(1, 5)).astype(np.int32) for _ in range(n_c)]
+    first[7] = np.zeros(0, np.int32)                      # nothing to append for this cache
+    lens = lambda ids: int(sum(off[i + 1] - off[i] for i in ids))
+    caches = [ad.Cache(ctx, lens(a) + lens(b) + 3) for a, b in zip(first, second)]
+    ctx.assemble_batched(caches, first, None, pos0=5)
+    ctx.assemble_batched(caches, second, [np.argsort(rng.random(len(b))).astype(np.int32) for b in second], pos0=5)
+    torch.cuda.synchronize()
+    kp, vp = H.to_storage(k_pool), H.to_storage(v_pool)
+    rng = np.random.default_rng(53)                        # replay the draws to recover the second call's orders
+    _ = [rng.integers(0, w.n_shots, rng.integers(0, 4)) for _ in range(n_c)]
+    _ = [rng.integers(0, w.n_shots, rng.integers(1, 5)) for _ in range(n_c)]
+    orders = [np.argsort(rng.random(len(b))).astype(np.int32) for b in second]
+    for ci in range(n_c):
+        n1, n2 = lens(first[ci]), lens(second[ci])
+        assert caches[ci].len == n1 + n2
+        cap = caches[ci].capacity
+        pl1 = oracle_mod.plan(off, first[ci], None, slot0=0, pos0=5)
+        pl2 = oracle_mod.plan(off, second[ci], orders[ci], slot0=n1, pos0=5)
+        ko, vo, _ = oracle_mod.assemble(kp, vp, w.dtype, w.rope_theta, 0, pl1, 0, cap, want_exact=False)
+        ko, vo, _ = oracle_mod.assemble(kp, vp, w.dtype, w.rope_theta, 0, pl2, n1, cap, k_out=ko, v_out=vo)
+        kg, vg = H.to_storage(caches[ci].k), H.to_storage(caches[ci].v)
+        assert np.array_equal(vg, vo), ci
+        assert np.abs(kg.astype(np.float64) - ko.astype(np.float64)).max() <= 2e-5, ci   # fp32 keys, |k| < 6
+        want_pos = np.concatenate([pl1["slot_pos"], pl2["slot_pos"]])
+        assert np.array_equal(caches[ci].slot_pos[:n1 + n2].cpu().numpy(), want_pos), ci
+        assert np.array_equal(caches[ci].slot_shot[:n1 + n2].cpu().numpy(), np.concatenate([pl1["slot_shot"], pl2["slot_shot"]]))
+        assert (caches[ci].slot_pos[n1 + n2:] == -1).all()
+    ctx.close()
