@@ -167,8 +167,9 @@ adapshot_status adapshot_assemble_batched(adapshot_ctx* ctx, adapshot_cache* cac
  * of caches[cache_index] plus their own tokens, as in adapshot_query_attn.  Several items may use the
  * same cache with different n_ctx: probes over nested prefixes (tree-structured multi-probe of the
  * Probe-based Dynamic Evaluation section) need no re-assembly because a prefix keeps its positions.
- * For bf16 models with head_dim 128 the whole batch runs as three launches (rotation of all items' rows,
- * one attention grid over all items, one combine grid): the context splits have one common length, so
+ * For bf16 models with head_dim 128 the whole batch runs as two launches (one attention grid over all items,
+ * whose workgroups rotate the query rows they need themselves, and one combine grid): the context splits
+ * have one common length, so
  * probes over nested prefixes of one cache read identical leading slices, and those workgroups are
  * scheduled next to each other.  Other shapes run item by item.  The outputs of distinct items must not
  * overlap; inputs may be shared between items. */

@@ -551,8 +551,11 @@ static adapshot_status run_query_attn(adapshot_ctx* ctx, const adapshot_cache* c
     }
 
     const size_t esz = (size_t)ctx->elem_bytes;
-    hipError_t e = ctx->q_rot.reserve((size_t)t_q * d.n_q_heads * d.head_dim * esz, ctx->retired);
-    if (e == hipSuccess) e = ctx->k_rot.reserve((size_t)t_q * d.n_kv_heads * d.head_dim * esz, ctx->retired);
+    hipError_t e = hipSuccess;
+    if (!mfma) {  // the MFMA kernel rotates its rows itself
+        e = ctx->q_rot.reserve((size_t)t_q * d.n_q_heads * d.head_dim * esz, ctx->retired);
+        if (e == hipSuccess) e = ctx->k_rot.reserve((size_t)t_q * d.n_kv_heads * d.head_dim * esz, ctx->retired);
+    }
     if (e == hipSuccess)
         e = ctx->part_o.reserve((size_t)(n_split + 1) * d.n_kv_heads * rows * d.head_dim * (mfma ? 2 : 4), ctx->retired);
     if (e == hipSuccess) e = ctx->part_ml.reserve((size_t)(n_split + 1) * d.n_kv_heads * rows * sizeof(float4), ctx->retired);
@@ -572,8 +575,10 @@ static adapshot_status run_query_attn(adapshot_ctx* ctx, const adapshot_cache* c
     rp.head_dim = d.head_dim;
     rp.dtype = d.dtype;
     rp.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
-    e = timed_launch(ctx, ADAPSHOT_KERNEL_ROPE_ROWS, stream, [&] { return launch_rope_rows(rp, stream); });
-    if (e != hipSuccess) return fail_hip(ctx, "query_attn: rope launch", e);
+    if (!mfma) {
+        e = timed_launch(ctx, ADAPSHOT_KERNEL_ROPE_ROWS, stream, [&] { return launch_rope_rows(rp, stream); });
+        if (e != hipSuccess) return fail_hip(ctx, "query_attn: rope launch", e);
+    }
 
     AttnParams ap;
     const int64_t layer_off = (int64_t)layer * cache->capacity * ctx->row_bytes;
@@ -582,6 +587,12 @@ static adapshot_status run_query_attn(adapshot_ctx* ctx, const adapshot_cache* c
     ap.q_rot = ctx->q_rot.p;
     ap.k_self_rot = ctx->k_rot.p;
     ap.v_self = v_self;
+    ap.q_raw = q;
+    ap.k_self_raw = k_self;
+    ap.tab_lo = ctx->tab_lo;
+    ap.tab_hi = ctx->tab_hi;
+    ap.q_pos0 = q_pos0;
+    ap.q_scale = rp.q_scale;
     ap.part_o = ctx->part_o.p;
     ap.part_mlf = (float4*)ctx->part_ml.p;
     ap.part_half = mfma ? 1 : 0;
@@ -605,8 +616,8 @@ static adapshot_status run_query_attn(adapshot_ctx* ctx, const adapshot_cache* c
     return ADAPSHOT_OK;
 }
 
-// All items of a batch in three launches: rotate every item's rows, one MFMA attention grid over the
-// work list of all (item, kv head, row tile, split) workgroups, one combine grid.  Items are validated
+// All items of a batch in two launches: one MFMA attention grid over the work list of all (item, kv head,
+// row tile, split) workgroups (each rotates the query rows it needs itself), one combine grid.  Items are validated
 // by the caller.  The context is cut into splits of one common length, chosen so that the whole batch
 // makes about two rounds of workgroups over the chip (long splits keep the partial traffic low, two
 // rounds even out items of different length); the work list is ordered longest first.
@@ -633,11 +644,11 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
 
     struct Plan {
         int64_t rows, n_row_tiles, n_split, keys_per_split;
-        size_t q_off, k_off, po_off, pml_off;
+        size_t po_off, pml_off;
     };
     std::vector<Plan> plan((size_t)n_items);
-    size_t q_bytes = 0, k_bytes = 0, po_bytes = 0, pml_bytes = 0;
-    int64_t n_attn = 0, n_comb = 0, n_rope = 0;
+    size_t po_bytes = 0, pml_bytes = 0;
+    int64_t n_attn = 0, n_comb = 0;
     for (int32_t i = 0; i < n_items; ++i) {
         const adapshot_attn_item& it = items[i];
         Plan& pl = plan[(size_t)i];
@@ -653,31 +664,23 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
             pl.n_split = (it.n_ctx + pl.keys_per_split - 1) / pl.keys_per_split;
         }
         auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
-        pl.q_off = q_bytes;
-        q_bytes += up((size_t)it.t_q * d.n_q_heads * d.head_dim * esz);
-        pl.k_off = k_bytes;
-        k_bytes += up((size_t)it.t_q * d.n_kv_heads * d.head_dim * esz);
         pl.po_off = po_bytes;
         po_bytes += up((size_t)(pl.n_split + 1) * d.n_kv_heads * pl.rows * d.head_dim * 2);  // fp16 rows
         pl.pml_off = pml_bytes;
         pml_bytes += up((size_t)(pl.n_split + 1) * d.n_kv_heads * pl.rows * sizeof(float4));
         n_attn += d.n_kv_heads * pl.n_row_tiles * (pl.n_split + 1);
         n_comb += (d.n_kv_heads * pl.rows + 15) / 16;
-        n_rope += ((int64_t)it.t_q * (d.n_q_heads + d.n_kv_heads) * (d.head_dim / 2 / (16 / (int)esz)) + 255) / 256;
     }
-    if (n_attn > INT32_MAX || n_comb > INT32_MAX || n_rope > INT32_MAX)
+    if (n_attn > INT32_MAX || n_comb > INT32_MAX)
         return fail(ctx, ADAPSHOT_EINVAL, "query_attn_batched: batch too large for one launch");
 
     // ---- workspace and tables
-    hipError_t e = ctx->q_rot.reserve(q_bytes, ctx->retired);
-    if (e == hipSuccess) e = ctx->k_rot.reserve(k_bytes, ctx->retired);
-    if (e == hipSuccess) e = ctx->part_o.reserve(po_bytes, ctx->retired);
+    hipError_t e = ctx->part_o.reserve(po_bytes, ctx->retired);
     if (e == hipSuccess) e = ctx->part_ml.reserve(pml_bytes, ctx->retired);
     const size_t items_bytes = (size_t)n_items * sizeof(AttnBatchItem);
     const size_t attn_off = (items_bytes + 255) & ~(size_t)255;
     const size_t comb_off = (attn_off + (size_t)n_attn * sizeof(AttnWork) + 255) & ~(size_t)255;
-    const size_t rope_off = (comb_off + (size_t)n_comb * sizeof(CombineWork) + 255) & ~(size_t)255;
-    const size_t tab_bytes = (rope_off + (size_t)n_rope * sizeof(RopeWork) + 15) & ~(size_t)15;
+    const size_t tab_bytes = (comb_off + (size_t)n_comb * sizeof(CombineWork) + 15) & ~(size_t)15;
     if (e == hipSuccess) e = ctx->batch_tab.reserve(tab_bytes, ctx->retired);
     if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: workspace", e);
     int slot = -1;
@@ -688,7 +691,6 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
     AttnBatchItem* hit = (AttnBatchItem*)host;
     AttnWork* haw = (AttnWork*)((char*)host + attn_off);
     CombineWork* hcw = (CombineWork*)((char*)host + comb_off);
-    RopeWork* hrw = (RopeWork*)((char*)host + rope_off);
     struct Key {
         int64_t tiles;
         int32_t cache;
@@ -696,31 +698,24 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
     };
     std::vector<Key> keys;
     keys.reserve((size_t)n_attn);
-    int64_t ic = 0, ir = 0;
+    int64_t ic = 0;
     for (int32_t i = 0; i < n_items; ++i) {
         const adapshot_attn_item& it = items[i];
         const adapshot_cache& c = caches[it.cache_index];
         const Plan& pl = plan[(size_t)i];
         AttnBatchItem& b = hit[i];
-        b.rope.q = it.q;
-        b.rope.k_self = it.k_self;
-        b.rope.q_rot = (char*)ctx->q_rot.p + pl.q_off;
-        b.rope.k_rot = (char*)ctx->k_rot.p + pl.k_off;
-        b.rope.tab_lo = ctx->tab_lo;
-        b.rope.tab_hi = ctx->tab_hi;
-        b.rope.q_pos0 = it.q_pos0;
-        b.rope.t_q = it.t_q;
-        b.rope.n_q_heads = d.n_q_heads;
-        b.rope.n_kv_heads = d.n_kv_heads;
-        b.rope.head_dim = d.head_dim;
-        b.rope.dtype = d.dtype;
-        b.rope.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
         const int64_t layer_off = (int64_t)layer * c.capacity * ctx->row_bytes;
         b.attn.k_cache = (const char*)c.k + layer_off;
         b.attn.v_cache = (const char*)c.v + layer_off;
-        b.attn.q_rot = b.rope.q_rot;
-        b.attn.k_self_rot = b.rope.k_rot;
+        b.attn.q_rot = nullptr;
+        b.attn.k_self_rot = nullptr;
         b.attn.v_self = it.v_self;
+        b.attn.q_raw = it.q;
+        b.attn.k_self_raw = it.k_self;
+        b.attn.tab_lo = ctx->tab_lo;
+        b.attn.tab_hi = ctx->tab_hi;
+        b.attn.q_pos0 = it.q_pos0;
+        b.attn.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
         b.attn.part_o = (char*)ctx->part_o.p + pl.po_off;
         b.attn.part_mlf = (float4*)((char*)ctx->part_ml.p + pl.pml_off);
         b.attn.part_half = 1;
@@ -746,8 +741,6 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
         }
         const int64_t pairs = d.n_kv_heads * pl.rows;
         for (int64_t p0 = 0; p0 < pairs; p0 += 16) hcw[ic++] = CombineWork{i, (int32_t)p0};
-        const int64_t rb = ((int64_t)it.t_q * (d.n_q_heads + d.n_kv_heads) * (d.head_dim / 2 / (16 / (int)esz)) + 255) / 256;
-        for (int64_t bk = 0; bk < rb; ++bk) hrw[ir++] = RopeWork{i, (int32_t)bk};
     }
     // Longest workgroups first.  Among equal lengths, the workgroups that read the same slice of the same
     // cache (probes over nested prefixes of one ordering share their leading splits, because the split
@@ -768,10 +761,6 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
     const AttnBatchItem* dit = (const AttnBatchItem*)ctx->batch_tab.p;
     const AttnWork* daw = (const AttnWork*)((const char*)ctx->batch_tab.p + attn_off);
     const CombineWork* dcw = (const CombineWork*)((const char*)ctx->batch_tab.p + comb_off);
-    const RopeWork* drw = (const RopeWork*)((const char*)ctx->batch_tab.p + rope_off);
-    e = timed_launch(ctx, ADAPSHOT_KERNEL_ROPE_ROWS, stream,
-                     [&] { return launch_rope_rows_batched(dit, drw, (int)n_rope, d.dtype, stream); });
-    if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: rope launch", e);
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream,
                      [&] { return launch_attn_mfma_batched(dit, daw, (int)n_attn, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: attention launch", e);
@@ -1073,39 +1062,27 @@ extern "C" adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer,
     const int64_t n_pairs = rows * d.n_kv_heads;
     const int32_t n_split = ctx->rank_n_split;
     const size_t esz = (size_t)ctx->elem_bytes;
-    hipError_t e = ctx->q_rot.reserve((size_t)t_q * d.n_q_heads * d.head_dim * esz, ctx->retired);
-    if (e == hipSuccess) e = ctx->part_o.reserve((size_t)n_split * n_pairs * d.head_dim * 2, ctx->retired);
+    hipError_t e = ctx->part_o.reserve((size_t)n_split * n_pairs * d.head_dim * 2, ctx->retired);
     if (e == hipSuccess) e = ctx->part_ml.reserve((size_t)n_split * n_pairs * sizeof(float4), ctx->retired);
     if (e == hipSuccess) e = ctx->rank_w.reserve((size_t)n_split * n_pairs * sizeof(float), ctx->retired);
     if (e == hipSuccess)
         e = ctx->rank_part.reserve((size_t)n_split * (size_t)((n_pairs + 255) / 256) * 128 * sizeof(float), ctx->retired);
     if (e != hipSuccess) return fail_hip(ctx, "rank_shots: workspace", e);
 
-    RopeRowsParams rp;
-    rp.q = q;
-    rp.k_self = nullptr;
-    rp.q_rot = ctx->q_rot.p;
-    rp.k_rot = nullptr;
-    rp.tab_lo = ctx->tab_lo;
-    rp.tab_hi = ctx->tab_hi;
-    rp.q_pos0 = q_pos0;
-    rp.t_q = t_q;
-    rp.n_q_heads = d.n_q_heads;
-    rp.n_kv_heads = d.n_kv_heads;
-    rp.head_dim = d.head_dim;
-    rp.dtype = d.dtype;
-    rp.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
-    e = timed_launch(ctx, ADAPSHOT_KERNEL_ROPE_ROWS, stream, [&] { return launch_rope_rows(rp, stream); });
-    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: rope launch", e);
-
     AttnParams ap;
     ap.k_cache = d.key_state == ADAPSHOT_KEYS_UNROTATED
                      ? ctx->rank_k.p
                      : (const void*)((const char*)ctx->k_pool + (int64_t)layer * ctx->pool_layer_stride_tokens * ctx->row_bytes);
     ap.v_cache = ctx->rank_v.p;
-    ap.q_rot = ctx->q_rot.p;
+    ap.q_rot = nullptr;
     ap.k_self_rot = nullptr;
     ap.v_self = nullptr;
+    ap.q_raw = q;
+    ap.k_self_raw = nullptr;
+    ap.tab_lo = ctx->tab_lo;
+    ap.tab_hi = ctx->tab_hi;
+    ap.q_pos0 = q_pos0;
+    ap.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
     ap.part_o = ctx->part_o.p;
     ap.part_mlf = (float4*)ctx->part_ml.p;
     ap.part_half = 1;

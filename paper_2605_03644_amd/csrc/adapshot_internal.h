@@ -108,9 +108,18 @@ hipError_t launch_rope_rows(const RopeRowsParams& p, hipStream_t stream);
 struct AttnParams {
     const void* k_cache;  // one layer [>=n_ctx][h_kv][d]
     const void* v_cache;
-    const void* q_rot;
-    const void* k_self_rot;
+    const void* q_rot;       // generic kernel: rows rotated and scaled by rope_rows
+    const void* k_self_rot;  // generic kernel: the query's own keys rotated by rope_rows
     const void* v_self;
+    // MFMA kernel: it rotates the rows it needs itself (Eq. rope_encoding at position q_pos0 + j), the
+    // query rows scaled by q_scale = log2(e)/sqrt(d) on the way into its fragments, the query's own keys
+    // on the way into LDS
+    const void* q_raw;       // [t_q][h_q][d] as the caller gave it
+    const void* k_self_raw;  // [t_q][h_kv][d] as the caller gave it
+    const float2* tab_lo;
+    const float2* tab_hi;
+    int64_t q_pos0;
+    float q_scale;
     // Partials, indexed [n_split+1][h_kv][rows]: part_mlf = (reference maximum in log2 units, row sum l,
     // factor f, unused) and a row O' of d values with  sum_k p_k v_k = f * O'.
     //   part_half = 0: O' is the unnormalised fp32 accumulator, f = 1 (generic kernel);
@@ -137,12 +146,11 @@ hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream);
 bool attn_mfma_supported(const adapshot_model_desc& d);
 hipError_t launch_attn_combine(const AttnParams& p, hipStream_t stream);
 
-// ---- a batch of attention problems in three launches (rotate, attend, combine) -------------
+// ---- a batch of attention problems in two launches (attend, combine) ------------------------
 // The tables live in device memory for the duration of the launches; every workgroup reads its own
 // entry.  The probes of one query over nested prefixes of one cache, the queries of a decode step and
 // the queries of a probe sweep are all such batches (Probe-based Dynamic Evaluation).
 struct AttnBatchItem {
-    RopeRowsParams rope;
     AttnParams attn;
 };
 struct AttnWork {  // one workgroup of the batched MFMA kernel
@@ -151,14 +159,9 @@ struct AttnWork {  // one workgroup of the batched MFMA kernel
 struct CombineWork {  // one workgroup of the batched combine kernel: 16 (kv head, row) pairs from pair0 on (fp16 partials)
     int32_t item, pair0;
 };
-struct RopeWork {  // one workgroup of the batched rotation kernel: 256 chunk pairs from 256 * block on
-    int32_t item, block;
-};
 // Tables written by the host into pinned memory are brought to device memory by a kernel (a DMA copy
 // between two kernels of a stream costs more than the copy itself).  bytes is a multiple of 16.
 hipError_t launch_copy_table(void* dst, const void* src_pinned, size_t bytes, hipStream_t stream);
-hipError_t launch_rope_rows_batched(const AttnBatchItem* items, const RopeWork* work, int n_work, int dtype,
-                                    hipStream_t stream);
 hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, hipStream_t stream);
 hipError_t launch_attn_combine_batched(const AttnBatchItem* items, const CombineWork* work, int n_work, int dtype,
                                        hipStream_t stream);

@@ -1,7 +1,8 @@
 // Query-over-cache attention, the parts shared by every shape:
 //   rope_rows     -- rotate the probe/query rows and their own keys to positions
 //                    q_pos0 + j (Eq. rope_encoding) and fold the softmax scale
-//                    log2(e)/sqrt(d) (Eq. attention_score's 1/sqrt(d)) into q;
+//                    log2(e)/sqrt(d) (Eq. attention_score's 1/sqrt(d)) into q, for the
+//                    generic kernel (the MFMA kernel rotates its rows itself);
 //   attn_generic  -- a straightforward fp32 split-K kernel (one wavefront per query
 //                    row, head and split) used for fp32 models and for shapes the
 //                    MFMA kernel does not cover;
@@ -101,12 +102,6 @@ __global__ __launch_bounds__(256) void rope_rows_kernel(RopeRowsParams p) {
     rope_rows_block<DTYPE>(p, blockIdx.x);
 }
 
-template <int DTYPE>
-__global__ __launch_bounds__(256) void rope_rows_batched_kernel(const AttnBatchItem* items, const RopeWork* work) {
-    const RopeWork w = work[blockIdx.x];
-    rope_rows_block<DTYPE>(items[w.item].rope, w.block);
-}
-
 hipError_t launch_rope_rows(const RopeRowsParams& p, hipStream_t stream) {
     const int np = p.dtype == ADAPSHOT_BF16 ? 8 : 4;
     const int64_t n = (int64_t)p.t_q * (p.n_q_heads + (p.k_self ? p.n_kv_heads : 0)) * (p.head_dim / 2 / np);
@@ -127,16 +122,6 @@ hipError_t launch_copy_table(void* dst, const void* src_pinned, size_t bytes, hi
     if (n16 == 0) return hipSuccess;
     const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 512);
     launch_kernel(copy_table_kernel, dim3(blocks), dim3(256), stream, (u32x4_t*)dst, (const u32x4_t*)src_pinned, n16);
-    return hipGetLastError();
-}
-
-hipError_t launch_rope_rows_batched(const AttnBatchItem* items, const RopeWork* work, int n_work, int dtype,
-                                    hipStream_t stream) {
-    if (n_work <= 0) return hipSuccess;
-    if (dtype == ADAPSHOT_BF16)
-        launch_kernel(rope_rows_batched_kernel<ADAPSHOT_BF16>, dim3((unsigned)n_work), dim3(256), stream, items, work);
-    else
-        launch_kernel(rope_rows_batched_kernel<ADAPSHOT_F32>, dim3((unsigned)n_work), dim3(256), stream, items, work);
     return hipGetLastError();
 }
 

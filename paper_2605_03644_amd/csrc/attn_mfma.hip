@@ -2,7 +2,8 @@
 //
 // The probe/query rows of one KV head (all g query heads of its group packed as rows
 // j*g + h%g) attend over a slice of the assembled cache; Eq. (attention_score) gives the
-// 1/sqrt(d) scale, folded with log2(e) into q by rope_rows, so p = 2^(s - m).
+// 1/sqrt(d) scale, folded with log2(e) into q when a workgroup rotates its query rows to their positions
+// (Eq. rope_encoding) on the way into the fragments, so p = 2^(s - m).
 //
 // Work decomposition: workgroup = (kv head, tile of 256 rows, split of the context);
 // 8 wavefronts (two per SIMD), each owning 32 rows for the whole key loop.  The extra split
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     }
 
     // ---- key range of this split
-    const char* kbase = (const char*)(self ? p.k_self_rot : p.k_cache) + hk * kRowBytes;
+    const char* kbase = (const char*)(self ? p.k_self_raw : p.k_cache) + hk * kRowBytes;
     const char* vbase = (const char*)(self ? p.v_self : p.v_cache) + hk * kRowBytes;
     const int64_t kv_stride = (int64_t)p.n_kv_heads * kRowBytes;
     int64_t k0, k1;
@@ -254,22 +255,62 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
         }
         ++next_v_tile;
     };
-    // K(0) and V(0) start now; the other tiles of the pipeline follow once these have landed
-    issue_k(0);
-    issue_v(0);
+    // K(0) and V(0) of a context split start now; the other tiles of the pipeline follow once these have
+    // landed.  (The split over the query's own tokens moves its tiles through registers, see below.)
+    if (!self) {
+        issue_k(0);
+        issue_v(0);
+    }
 
-    // ---- Q fragments (B operand): lane holds row l32, d = 16*kk + 8*hh .. +7
+    // Eight (cos, sin) of position `a` for the frequencies f0 .. f0+7: one fp32 angle addition of the two
+    // fp64-built table entries (a = 64*hi + lo).
+    auto cos_sin8 = [&](int64_t a, int f0, float (&c)[8], float (&sn)[8]) __attribute__((always_inline)) {
+        const f32x4* th = (const f32x4*)(p.tab_hi + (a >> kRopeLoBits) * (kD / 2) + f0);
+        const f32x4* tl = (const f32x4*)(p.tab_lo + (a & (kRopeLo - 1)) * (kD / 2) + f0);
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+            const f32x4 h = th[e2], l = tl[e2];  // two frequencies: (cos, sin, cos, sin)
+            c[2 * e2] = h[0] * l[0] - h[1] * l[1];
+            sn[2 * e2] = h[1] * l[0] + h[0] * l[1];
+            c[2 * e2 + 1] = h[2] * l[2] - h[3] * l[3];
+            sn[2 * e2 + 1] = h[3] * l[2] + h[2] * l[3];
+        }
+    };
+    // Rotate the pair partners held in two 16-byte chunks (elements i .. i+7 and i+64 .. i+71 of a row),
+    // scale, round to bf16 (nearest even).
+    auto rotate8 = [&](u32x4& x1, u32x4& x2, const float (&c)[8], const float (&sn)[8], float sc) __attribute__((always_inline)) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float a1l = __uint_as_float(x1[w] << 16), a1h = __uint_as_float(x1[w] & 0xffff0000u);
+            const float a2l = __uint_as_float(x2[w] << 16), a2h = __uint_as_float(x2[w] & 0xffff0000u);
+            const float y1l = (a1l * c[2 * w] - a2l * sn[2 * w]) * sc, y2l = (a2l * c[2 * w] + a1l * sn[2 * w]) * sc;
+            const float y1h = (a1h * c[2 * w + 1] - a2h * sn[2 * w + 1]) * sc, y2h = (a2h * c[2 * w + 1] + a1h * sn[2 * w + 1]) * sc;
+            x1[w] = pack2_bf16(y1l, y1h);
+            x2[w] = pack2_bf16(y2l, y2h);
+        }
+    };
+
+    // ---- Q fragments (B operand): lane holds row l32, d = 16*kk + 8*hh .. +7.  Fragments kk and kk + 4 hold
+    // rotation partners (d, d + 64), so a lane rotates its own row to position q_pos0 + j and folds the
+    // softmax scale in, without another pass over Q in memory.
     bf16x8 qf[8];
     {
         const bool valid = row[0] < rows;
         const int j = valid ? jrow[0] : 0;
         const int gq = valid ? row[0] - j * g : 0;
-        const char* qrow = (const char*)p.q_rot + ((int64_t)(j * p.n_q_heads + hk * g + gq) * kD) * 2;
+        const char* qrow = (const char*)p.q_raw + ((int64_t)(j * p.n_q_heads + hk * g + gq) * kD) * 2;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            u32x4 w = {0u, 0u, 0u, 0u};
-            if (valid) w = *(const u32x4*)(qrow + (16 * kk + 8 * hh) * 2);
-            qf[kk] = __builtin_bit_cast(bf16x8, w);
+        for (int kk = 0; kk < 4; ++kk) {
+            u32x4 x1 = {0u, 0u, 0u, 0u}, x2 = {0u, 0u, 0u, 0u};
+            if (valid) {
+                x1 = *(const u32x4*)(qrow + (16 * kk + 8 * hh) * 2);
+                x2 = *(const u32x4*)(qrow + (16 * (kk + 4) + 8 * hh) * 2);
+                float c[8], sn[8];
+                cos_sin8(p.q_pos0 + j, 16 * kk + 8 * hh, c, sn);
+                rotate8(x1, x2, c, sn, p.q_scale);
+            }
+            qf[kk] = __builtin_bit_cast(bf16x8, x1);
+            qf[kk + 4] = __builtin_bit_cast(bf16x8, x2);
         }
     }
 
@@ -437,6 +478,45 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
                  :
                  : "memory");
     __syncthreads();
+    // A wavefront whose 32 rows all lie past the last query row (a decode step has fewer rows than one
+    // wavefront owns) only moves tiles and keeps the barriers.
+    const bool wave_idle = row_tile * kAttnRowTile + wave * NR * 32 >= rows;
+    if (self) {
+        // ---- the query's own tokens: a few tiles at most, moved through registers so that the keys can be
+        // rotated to their positions q_pos0 + u on the way (the caller gives them un-rotated).  One tile at a
+        // time in buffer 0, two workgroup barriers per tile.  Thread = (row r, chunk pair cp) for K, two
+        // (row, chunk) items for V; rows past the last token are zero-filled (and masked by the softmax).
+        const int r = tid >> 3, cp = tid & 7;
+        for (int t = 0; t < n_tiles; ++t) {
+            const int u = t * kTileKeys + r;
+            u32x4 x1 = {0u, 0u, 0u, 0u}, x2 = {0u, 0u, 0u, 0u};
+            if (u < n_keys) {
+                const char* krow = kbase + (int64_t)u * kv_stride;
+                x1 = *(const u32x4*)(krow + cp * 16);
+                x2 = *(const u32x4*)(krow + (cp + 8) * 16);
+                float c[8], sn[8];
+                cos_sin8(p.q_pos0 + u, 8 * cp, c, sn);
+                rotate8(x1, x2, c, sn, 1.0f);
+            }
+            *(u32x4*)(k_s[0] + r * kRowBytes + ((cp ^ (r & 15)) << 4)) = x1;
+            *(u32x4*)(k_s[0] + r * kRowBytes + (((cp + 8) ^ (r & 15)) << 4)) = x2;
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps) {
+                const int rv = 4 * (ps * WAVES + wave) + (lane >> 4), cv = lane & 15;
+                const int uv = t * kTileKeys + rv;
+                u32x4 xv = {0u, 0u, 0u, 0u};
+                if (uv < n_keys) xv = *(const u32x4*)(vbase + (int64_t)uv * kv_stride + cv * 16);
+                *(u32x4*)(v_s[0] + rv * kRowBytes + ((cv ^ ((rv & 3) << 2)) << 4)) = xv;
+            }
+            __syncthreads();
+            if (!wave_idle) {
+                s_phase(0);
+                softmax_phase(t);
+                pv_phase(0);
+            }
+            __syncthreads();
+        }
+    } else {
     issue_k(1);
     issue_v(1);
     issue_k(2);
@@ -445,9 +525,6 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
 
     // The key loop is unrolled four times so that the LDS buffer of every access is a compile-time constant;
     // the last n_tiles % 4 tiles take the buffer index at run time.
-    // A wavefront whose 32 rows all lie past the last query row (a decode step has fewer rows than one
-    // wavefront owns) only moves tiles and keeps the barriers.
-    const bool wave_idle = row_tile * kAttnRowTile + wave * NR * 32 >= rows;
     if (wave_idle) {
         for (int t = 0; t < n_tiles; ++t) end_of_tile(t & 3);
     } else if (wave < WAVES / 2) {
@@ -486,6 +563,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
         }
         for (; t < n_tiles; ++t) tile_b(t, t & 3);
         pv_phase((n_tiles - 1) & 3);
+    }
     }
     __builtin_amdgcn_s_waitcnt(kWaitVm0);  // the loads of the tiles past the end must land before LDS is released
 
