@@ -24,12 +24,12 @@
  *     split partials), so calls on ONE context must be issued in stream order on
  *     one stream at a time; use one context per concurrent stream.
  *   - Allocation and waiting.  adapshot_create allocates the RoPE tables (hipMalloc and two
- *     blocking copies).  adapshot_query_attn, adapshot_query_attn_batched, adapshot_probe_entropy,
+ *     blocking copies).  adapshot_query_attn, adapshot_query_attn_pool, adapshot_query_attn_batched, adapshot_probe_entropy,
  *     adapshot_probe_entropy_tokens and adapshot_rank_shots keep grow-only workspaces: a call that
  *     needs more than any earlier call on the context calls hipMalloc (an outgrown buffer is kept
  *     until adapshot_destroy, never freed in a call, so no call waits for the device); a call that
- *     fits the existing workspaces allocates nothing.  adapshot_assemble, the batched calls and
- *     adapshot_rank_shots write small tables into a ring of 8 pinned host buffers (hipHostMalloc
+ *     fits the existing workspaces allocates nothing.  adapshot_assemble, adapshot_query_attn_pool, the batched
+ *     calls and adapshot_rank_shots write small tables into a ring of 8 pinned host buffers (hipHostMalloc
  *     when one must grow); the ninth such call in flight waits for the first one's kernels.  No
  *     call synchronises the device or the stream otherwise.  adapshot_probe_entropy_static is the
  *     variant of the entropy call that never allocates.
@@ -151,6 +151,23 @@ adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot_cache* cac
                                     int64_t n_ctx, const void* q, const void* k_self,
                                     const void* v_self, int32_t t_q, int64_t q_pos0, void* out,
                                     void* hip_stream);
+
+/* Zero-copy form of steps 1-3 for one layer: the query rows attend over the selected shots where they lie in
+ * the pool, without an assembled cache.  The result is what adapshot_assemble(shot_ids, order, m, pos0) into an
+ * empty cache followed by adapshot_query_attn over all of it (n_ctx = the shots' total length) gives, up to
+ * rounding: the attention kernel gathers every 64-slot tile of the context row by row through a slot -> pool
+ * token table and rotates its keys to the positions pos0 + slot inside the key loop, in LDS, before the first
+ * product reads them (Position Decoupling and Re-encoding: R(a)R(b) = R(a+b), so the rotation of a tile's
+ * first position and the rotation of the row's index inside the tile compose; Eq. rope_compensation).  Worth
+ * it for a context that is attended once; a context that is attended again (further layers' probes, every
+ * decode step) is cheaper assembled once.  shot_ids, order: HOST int32[m] as in adapshot_assemble; q, k_self,
+ * v_self, out, q_pos0 as in adapshot_query_attn.  Two launches besides the merge of the split partials: a small
+ * one that expands the plan, and the attention.  bf16 models with head_dim 128 and pools registered with
+ * ADAPSHOT_KEYS_UNROTATED only (ESTATE otherwise); a pool layer must stay below 4 GiB (ECAPACITY). */
+adapshot_status adapshot_query_attn_pool(adapshot_ctx* ctx, int32_t layer, const int32_t* shot_ids,
+                                         const int32_t* order, int32_t m, int64_t pos0, const void* q,
+                                         const void* k_self, const void* v_self, int32_t t_q, int64_t q_pos0,
+                                         void* out, void* hip_stream);
 
 /* Batched forms (several independent queries per call, e.g. the adaptive probe sweep over nested
  * prefixes, or the queries of a decode batch).  Every item is validated before anything is launched:

@@ -29,7 +29,7 @@ EXPORTS = ["adapshot_create", "adapshot_destroy", "adapshot_last_error", "adapsh
            "adapshot_profile_enable", "adapshot_profile_read", "adapshot_profile_read_each", "adapshot_assemble_batched",
            "adapshot_query_attn_batched", "adapshot_decode_append", "adapshot_probe_entropy_tokens",
            "adapshot_pick_shots", "adapshot_rank_shots", "adapshot_top_k", "adapshot_set_attn_splits",
-           "adapshot_probe_entropy_static"]
+           "adapshot_probe_entropy_static", "adapshot_query_attn_pool"]
 ENTROPY_FULL_P, ENTROPY_RENORMALISED = 0, 1
 KERNEL_KINDS = ["assemble_reencode", "rope_rows", "query_attn", "attn_combine", "entropy_chunk", "entropy_finish"]
 
@@ -85,6 +85,8 @@ def load_library() -> ctypes.CDLL:
     L.adapshot_assemble.argtypes = [vp, ctypes.POINTER(CacheStruct), vp, vp, i32, i64, vp]
     L.adapshot_query_attn.restype = ctypes.c_int
     L.adapshot_query_attn.argtypes = [vp, ctypes.POINTER(CacheStruct), i32, i64, vp, vp, vp, i32, i64, vp, vp]
+    L.adapshot_query_attn_pool.restype = ctypes.c_int
+    L.adapshot_query_attn_pool.argtypes = [vp, i32, vp, vp, i32, i64, vp, vp, vp, i32, i64, vp, vp]
     L.adapshot_probe_entropy.restype = ctypes.c_int
     L.adapshot_probe_entropy.argtypes = [vp, vp, i64, i32, i32, vp, vp]
     L.adapshot_probe_entropy_static.restype = ctypes.c_int
@@ -221,6 +223,21 @@ class Context:
         self._check(self.lib.adapshot_query_attn(self._h, ctypes.byref(cache.c), layer, n_ctx, q.data_ptr(),
                                                  k_self.data_ptr(), v_self.data_ptr(), q.shape[0], q_pos0,
                                                  out.data_ptr(), _stream_ptr(stream)))
+        return out
+
+    # -- adapshot_query_attn_pool (zero-copy form)
+    def query_attn_pool(self, layer: int, shot_ids: Sequence[int], order: Optional[Sequence[int]], q: torch.Tensor,
+                        k_self: torch.Tensor, v_self: torch.Tensor, q_pos0: int, pos0: int = 0,
+                        out: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+        assert q.is_contiguous() and k_self.is_contiguous() and v_self.is_contiguous()
+        ids = np.ascontiguousarray(shot_ids, dtype=np.int32)
+        od = None if order is None else np.ascontiguousarray(order, dtype=np.int32)
+        if out is None:
+            out = torch.empty_like(q)
+        self._check(self.lib.adapshot_query_attn_pool(self._h, layer, ids.ctypes.data,
+                                                      None if od is None else od.ctypes.data, ids.shape[0], pos0,
+                                                      q.data_ptr(), k_self.data_ptr(), v_self.data_ptr(), q.shape[0],
+                                                      q_pos0, out.data_ptr(), _stream_ptr(stream)))
         return out
 
     # -- adapshot_probe_entropy

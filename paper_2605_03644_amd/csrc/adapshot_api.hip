@@ -254,6 +254,8 @@ extern "C" void adapshot_destroy(adapshot_ctx* ctx) {
     ctx->part_ml.release();
     ctx->ent_part.release();
     ctx->batch_tab.release();
+    ctx->pool_src.release();
+    ctx->pool_rot.release();
     ctx->rank_k.release();
     ctx->rank_v.release();
     ctx->rank_w.release();
@@ -525,9 +527,25 @@ static adapshot_status check_query_attn(adapshot_ctx* ctx, const adapshot_cache*
     return ADAPSHOT_OK;
 }
 
+// k_ctx / v_ctx: one layer of the context the rows attend over -- the assembled cache, or, for the zero-copy form
+// (slot_src and tile_rot given), one layer of the pool.
+static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, const void* v_ctx, int64_t n_ctx,
+                                         const void* q, const void* k_self, const void* v_self, int32_t t_q,
+                                         int64_t q_pos0, void* out, const int32_t* slot_src, const float2* tile_rot,
+                                         hipStream_t stream);
+
 static adapshot_status run_query_attn(adapshot_ctx* ctx, const adapshot_cache* cache, int32_t layer, int64_t n_ctx,
                                       const void* q, const void* k_self, const void* v_self, int32_t t_q,
                                       int64_t q_pos0, void* out, hipStream_t stream) {
+    const int64_t layer_off = (int64_t)layer * cache->capacity * ctx->row_bytes;
+    return run_query_attn_on(ctx, (const char*)cache->k + layer_off, (const char*)cache->v + layer_off, n_ctx, q, k_self,
+                             v_self, t_q, q_pos0, out, nullptr, nullptr, stream);
+}
+
+static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, const void* v_ctx, int64_t n_ctx,
+                                         const void* q, const void* k_self, const void* v_self, int32_t t_q,
+                                         int64_t q_pos0, void* out, const int32_t* slot_src, const float2* tile_rot,
+                                         hipStream_t stream) {
     const adapshot_model_desc& d = ctx->desc;
     const int g = d.n_q_heads / d.n_kv_heads;
     const int64_t rows = (int64_t)t_q * g;
@@ -581,9 +599,10 @@ static adapshot_status run_query_attn(adapshot_ctx* ctx, const adapshot_cache* c
     }
 
     AttnParams ap;
-    const int64_t layer_off = (int64_t)layer * cache->capacity * ctx->row_bytes;
-    ap.k_cache = (const char*)cache->k + layer_off;
-    ap.v_cache = (const char*)cache->v + layer_off;
+    ap.k_cache = k_ctx;
+    ap.v_cache = v_ctx;
+    ap.slot_src = slot_src;
+    ap.tile_rot = tile_rot;
     ap.q_rot = ctx->q_rot.p;
     ap.k_self_rot = ctx->k_rot.p;
     ap.v_self = v_self;
@@ -608,8 +627,10 @@ static adapshot_status run_query_attn(adapshot_ctx* ctx, const adapshot_cache* c
     ap.n_kv_heads = d.n_kv_heads;
     ap.head_dim = d.head_dim;
     ap.dtype = d.dtype;
-    e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream,
-                     [&] { return mfma ? launch_attn_mfma(ap, stream) : launch_attn_generic(ap, stream); });
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream, [&] {
+        if (slot_src) return launch_attn_mfma_pool(ap, stream);
+        return mfma ? launch_attn_mfma(ap, stream) : launch_attn_generic(ap, stream);
+    });
     if (e != hipSuccess) return fail_hip(ctx, "query_attn: attention launch", e);
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(ap, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "query_attn: combine launch", e);
@@ -707,6 +728,8 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
         const int64_t layer_off = (int64_t)layer * c.capacity * ctx->row_bytes;
         b.attn.k_cache = (const char*)c.k + layer_off;
         b.attn.v_cache = (const char*)c.v + layer_off;
+        b.attn.slot_src = nullptr;
+        b.attn.tile_rot = nullptr;
         b.attn.q_rot = nullptr;
         b.attn.k_self_rot = nullptr;
         b.attn.v_self = it.v_self;
@@ -778,6 +801,91 @@ extern "C" adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot
     adapshot_status st = check_query_attn(ctx, cache, layer, n_ctx, q, k_self, v_self, t_q, q_pos0, out);
     if (st != ADAPSHOT_OK) return st;
     st = run_query_attn(ctx, cache, layer, n_ctx, q, k_self, v_self, t_q, q_pos0, out, (hipStream_t)hip_stream);
+    if (st == ADAPSHOT_OK) ctx->last_error.clear();
+    return st;
+}
+
+// Zero-copy form: the rows attend over the selected shots where they lie in the pool.
+extern "C" adapshot_status adapshot_query_attn_pool(adapshot_ctx* ctx, int32_t layer, const int32_t* shot_ids,
+                                                    const int32_t* order, int32_t m, int64_t pos0, const void* q,
+                                                    const void* k_self, const void* v_self, int32_t t_q,
+                                                    int64_t q_pos0, void* out, void* hip_stream) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    const adapshot_model_desc& d = ctx->desc;
+    if (!attn_mfma_supported(d))
+        return fail(ctx, ADAPSHOT_ESTATE, "query_attn_pool: needs a bf16 model with head_dim 128 (matrix-core kernel)");
+    if (d.key_state != ADAPSHOT_KEYS_UNROTATED)
+        return fail(ctx, ADAPSHOT_ESTATE, "query_attn_pool: needs a pool registered with ADAPSHOT_KEYS_UNROTATED");
+    if (!ctx->k_pool) return fail(ctx, ADAPSHOT_ESTATE, "query_attn_pool: no pool registered");
+    if (m < 0 || (m > 0 && !shot_ids)) return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool: bad shot list");
+    if (!q || !k_self || !v_self || !out) return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool: null pointer");
+    if (!aligned16(q) || !aligned16(k_self) || !aligned16(v_self) || !aligned16(out))
+        return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool: pointers must be 16-byte aligned");
+    if (t_q < 1) return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool: t_q < 1");
+    if (layer < 0 || layer >= d.n_layers) return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool: layer out of range");
+    if (pos0 < 0 || q_pos0 < 0) return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool: negative position");
+    if (q_pos0 + t_q > ctx->max_position)
+        return fail(ctx, ADAPSHOT_ECAPACITY, "query_attn_pool: query positions exceed max_position");
+    int64_t total = 0;
+    for (int32_t j = 0; j < m; ++j) {
+        const int32_t oj = order ? order[j] : j;
+        if (oj < 0 || oj >= m) return fail(ctx, ADAPSHOT_ESHOT, "query_attn_pool: order[%d] = %d out of range", j, oj);
+        const int32_t s = shot_ids[oj];
+        if (s < 0 || s >= ctx->n_shots) return fail(ctx, ADAPSHOT_ESHOT, "query_attn_pool: shot id %d out of range", s);
+        total += ctx->shot_offsets[s + 1] - ctx->shot_offsets[s];
+    }
+    if (total > INT32_MAX) return fail(ctx, ADAPSHOT_ECAPACITY, "query_attn_pool: context longer than 2^31 - 1 tokens");
+    if (pos0 + total > ctx->max_position)
+        return fail(ctx, ADAPSHOT_ECAPACITY, "query_attn_pool: position %lld exceeds max_position %lld",
+                    (long long)(pos0 + total), (long long)ctx->max_position);
+    // a lane addresses its key row by a 32-bit byte offset inside the pool's layer
+    if ((uint64_t)ctx->shot_offsets[(size_t)ctx->n_shots] * (uint64_t)ctx->row_bytes > 0xffffffffull ||
+        (uint64_t)std::max<int64_t>(total, t_q) * (uint64_t)ctx->row_bytes > 0xffffffffull)
+        return fail(ctx, ADAPSHOT_ECAPACITY, "query_attn_pool: a pool layer of 4 GiB or more is not supported");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const int64_t layer_off = (int64_t)layer * ctx->pool_layer_stride_tokens * ctx->row_bytes;
+    const char* k_layer = (const char*)ctx->k_pool + layer_off;
+    const char* v_layer = (const char*)ctx->v_pool + layer_off;
+    if (total == 0) {  // nothing but the query's own tokens
+        adapshot_status st = run_query_attn_on(ctx, k_layer, v_layer, 0, q, k_self, v_self, t_q, q_pos0, out, nullptr, nullptr,
+                                               stream);
+        if (st == ADAPSHOT_OK) ctx->last_error.clear();
+        return st;
+    }
+
+    const int64_t n_tiles = (total + 63) / 64;
+    hipError_t e = ctx->pool_src.reserve((size_t)total * sizeof(int32_t), ctx->retired);
+    if (e == hipSuccess) e = ctx->pool_rot.reserve((size_t)n_tiles * (d.head_dim / 2) * sizeof(float2), ctx->retired);
+    if (e != hipSuccess) return fail_hip(ctx, "query_attn_pool: workspace", e);
+    int slot = -1;
+    void* host = nullptr;
+    e = ctx->tile_ring.acquire((size_t)std::max<int32_t>(m, 1) * sizeof(PoolSeg), &slot, &host);
+    if (e != hipSuccess) return fail_hip(ctx, "query_attn_pool: pinned segments", e);
+    PoolSeg* segs = (PoolSeg*)host;
+    int64_t slot0 = 0;
+    int32_t n_segs = 0;
+    for (int32_t j = 0; j < m; ++j) {  // slot group j starts at off_j = sum of the lengths before it
+        const int32_t s = shot_ids[order ? order[j] : j];
+        const int64_t src = ctx->shot_offsets[s], len = ctx->shot_offsets[s + 1] - src;
+        if (len > 0) segs[n_segs++] = PoolSeg{(int32_t)slot0, (int32_t)src, (int32_t)len, 0};
+        slot0 += len;
+    }
+    PoolPlanParams pp;
+    pp.segs = segs;
+    pp.slot_src = (int32_t*)ctx->pool_src.p;
+    pp.tile_rot = (float2*)ctx->pool_rot.p;
+    pp.tab_lo = ctx->tab_lo;
+    pp.tab_hi = ctx->tab_hi;
+    pp.pos0 = pos0;
+    pp.n_segs = n_segs;
+    pp.n_tiles = (int32_t)n_tiles;
+    pp.head_dim = d.head_dim;
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ROPE_ROWS, stream, [&] { return launch_pool_plan(pp, stream); });
+    if (e != hipSuccess) return fail_hip(ctx, "query_attn_pool: plan launch", e);
+    e = ctx->tile_ring.mark_in_use(slot, stream);
+    if (e != hipSuccess) return fail_hip(ctx, "query_attn_pool: event record", e);
+    adapshot_status st = run_query_attn_on(ctx, k_layer, v_layer, total, q, k_self, v_self, t_q, q_pos0, out,
+                                           (const int32_t*)ctx->pool_src.p, (const float2*)ctx->pool_rot.p, stream);
     if (st == ADAPSHOT_OK) ctx->last_error.clear();
     return st;
 }
@@ -1074,6 +1182,8 @@ extern "C" adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer,
                      ? ctx->rank_k.p
                      : (const void*)((const char*)ctx->k_pool + (int64_t)layer * ctx->pool_layer_stride_tokens * ctx->row_bytes);
     ap.v_cache = ctx->rank_v.p;
+    ap.slot_src = nullptr;
+    ap.tile_rot = nullptr;
     ap.q_rot = nullptr;
     ap.k_self_rot = nullptr;
     ap.v_self = nullptr;

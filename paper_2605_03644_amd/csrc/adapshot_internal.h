@@ -120,6 +120,11 @@ struct AttnParams {
     const float2* tab_hi;
     int64_t q_pos0;
     float q_scale;
+    // Zero-copy form (MFMA kernel, template parameter POOL): k_cache / v_cache are the POOL's layer, context slot u
+    // holds pool token slot_src[u], and its key is rotated to position pos0 + u inside the key loop;
+    // tile_rot[i][f] = (cos, sin)((pos0 + 64 i) theta_f) for every 64-slot tile of the context.
+    const int32_t* slot_src;
+    const float2* tile_rot;
     // Partials, indexed [n_split+1][h_kv][rows]: part_mlf = (reference maximum in log2 units, row sum l,
     // factor f, unused) and a row O' of d values with  sum_k p_k v_k = f * O'.
     //   part_half = 0: O' is the unnormalised fp32 accumulator, f = 1 (generic kernel);
@@ -143,6 +148,21 @@ struct AttnParams {
 constexpr int kAttnRowTile = 256;  // query rows per workgroup of the MFMA kernel
 hipError_t launch_attn_generic(const AttnParams& p, hipStream_t stream);
 hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream);
+hipError_t launch_attn_mfma_pool(const AttnParams& p, hipStream_t stream);  // zero-copy form
+// Expands the per-shot segments of a zero-copy context into slot_src and builds tile_rot.
+struct PoolSeg {
+    int32_t slot0, src_tok0, len, pad;
+};
+struct PoolPlanParams {
+    const PoolSeg* segs;  // pinned host memory, read by the kernel
+    int32_t* slot_src;
+    float2* tile_rot;
+    const float2* tab_lo;
+    const float2* tab_hi;
+    int64_t pos0;
+    int32_t n_segs, n_tiles, head_dim;
+};
+hipError_t launch_pool_plan(const PoolPlanParams& p, hipStream_t stream);
 bool attn_mfma_supported(const adapshot_model_desc& d);
 hipError_t launch_attn_combine(const AttnParams& p, hipStream_t stream);
 
@@ -298,7 +318,7 @@ struct adapshot_ctx {
     float* static_ent = nullptr;  // this device's copy of the static entropy scratch array (not owned)
     // scratch
     adapshot::PinnedRing tile_ring;
-    adapshot::DevBuf q_rot, k_rot, part_o, part_ml, ent_part, batch_tab;
+    adapshot::DevBuf q_rot, k_rot, part_o, part_ml, ent_part, batch_tab, pool_src, pool_rot;
     // ranking state of one pool layer, built on first use
     int32_t rank_layer = -1;
     int32_t rank_n_split = 0;

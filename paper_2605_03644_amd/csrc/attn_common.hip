@@ -125,6 +125,35 @@ hipError_t launch_copy_table(void* dst, const void* src_pinned, size_t bytes, hi
     return hipGetLastError();
 }
 
+// ---- plan of a zero-copy context ----------------------------------------------------------
+// Blocks 0 .. n_segs-1 expand one shot each into slot_src (context slot -> pool token); the blocks after them
+// form tile_rot[i][f] = (cos, sin)((pos0 + 64 i) theta_f) for every 64-slot tile, one fp32 angle addition of the
+// two fp64-built table entries.
+__global__ __launch_bounds__(256) void pool_plan_kernel(PoolPlanParams p) {
+    if ((int)blockIdx.x < p.n_segs) {
+        const PoolSeg sg = p.segs[blockIdx.x];
+        for (int t = threadIdx.x; t < sg.len; t += 256) p.slot_src[sg.slot0 + t] = sg.src_tok0 + t;
+        return;
+    }
+    const int half = p.head_dim >> 1;
+    const int64_t idx = (int64_t)(blockIdx.x - p.n_segs) * 256 + threadIdx.x;
+    if (idx >= (int64_t)p.n_tiles * half) return;
+    const int64_t tile = idx / half;
+    const int f = (int)(idx - tile * half);
+    const int64_t a = p.pos0 + tile * 64;
+    const float2 h = p.tab_hi[(a >> kRopeLoBits) * half + f], l = p.tab_lo[(a & (kRopeLo - 1)) * half + f];
+    p.tile_rot[idx] = make_float2(h.x * l.x - h.y * l.y, h.y * l.x + h.x * l.y);
+}
+
+hipError_t launch_pool_plan(const PoolPlanParams& p, hipStream_t stream) {
+    const int64_t rot_blocks = ((int64_t)p.n_tiles * (p.head_dim / 2) + 255) / 256;
+    const int64_t blocks = p.n_segs + rot_blocks;
+    if (blocks <= 0) return hipSuccess;
+    if (blocks > INT32_MAX) return hipErrorInvalidValue;
+    launch_kernel(pool_plan_kernel, dim3((unsigned)blocks), dim3(256), stream, p);
+    return hipGetLastError();
+}
+
 // ---- wavefront reductions --------------------------------------------------------------
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll

@@ -138,7 +138,14 @@ __device__ __forceinline__ T load_uniform(const T* ptr) {
 // WAVES wavefronts, each owning NR blocks of 32 rows for the whole key loop.  BATCHED: the workgroup takes
 // its problem and its (kv head, row tile, split) from the work list instead of the launch arguments.
 // PVB: 32-column blocks of V that carry data (4 = the whole head; ranking's one-hot rows use 1).
-template <int WAVES, int NR, bool BATCHED, int PVB>
+// POOL: the zero-copy form.  The context is not an assembled cache but the pool itself, read through the
+// table slot_src (context slot -> pool token): every 64-slot tile is gathered row by row into LDS, and its
+// keys are rotated there, in place, to the positions pos0 + slot before the first product reads them
+// (R(a)R(b) = R(a+b): tile_rot holds (cos, sin) of the tile's first position, the copy of the 64-row
+// second-level table in LDS adds the row's index inside the tile).  Two tiles in LDS per operand, two
+// workgroup barriers per tile (tile landed -> rotate -> rotated keys visible), every wavefront in the order
+// S, softmax, PV.  What a context split computes is what the plain form computes over the assembled cache.
+template <int WAVES, int NR, bool BATCHED, int PVB, bool POOL>
 __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg, int n_row_tiles_arg,
                                                                const AttnBatchItem* items, const AttnWork* work) {
     constexpr int PASSES = (kTileKeys * 16) / (WAVES * 64);  // 1 KB blocks of a tile per wavefront
@@ -257,9 +264,88 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     };
     // K(0) and V(0) of a context split start now; the other tiles of the pipeline follow once these have
     // landed.  (The split over the query's own tokens moves its tiles through registers, see below.)
+    // ---- zero-copy form: gathered tile loads.  LDS roles: k_s[0..1] and v_s[0..1] are the K and V rings, k_s[2]
+    // holds the two tiles' rotation rows (1 KB slots), v_s[2..3] the 32 KB second-level table.
+    char* const rot_s = k_s[2];
+    char* const lo_s = v_s[2];
+    unsigned pool_idx[PASSES];  // byte offsets of this lane's rows of the next tile to request
+    auto pool_index = [&](int t) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps) {
+            const int r = 4 * (ps * WAVES + wave) + (lane >> 4);
+            int64_t key = k0 + (int64_t)t * kTileKeys + r;
+            key = key < k1 ? key : k1 - 1;  // rows past the end (masked by the softmax) repeat the last key
+            pool_idx[ps] = (unsigned)p.slot_src[key] * (unsigned)kv_stride;  // the host keeps a pool layer below 4 GiB
+        }
+    };
+    auto pool_issue = [&](int t, int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps) {
+            const int r = 4 * (ps * WAVES + wave) + (lane >> 4);
+            load_lds_16(kbase, pool_idx[ps] + (((lane & 15) ^ (r & 15)) << 4),
+                        __builtin_amdgcn_readfirstlane(lds_addr(k_s[buf] + (ps * WAVES + wave) * 1024)));
+        }
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps) {
+            const int r = 4 * (ps * WAVES + wave) + (lane >> 4);
+            load_lds_16(vbase, pool_idx[ps] + (((lane & 15) ^ ((r & 3) << 2)) << 4),
+                        __builtin_amdgcn_readfirstlane(lds_addr(v_s[buf] + (ps * WAVES + wave) * 1024)));
+        }
+        if (wave == 0) {  // the tile's rotation row: 512 bytes (lanes 0-31); lanes 32-63 bring the next row along
+            const int64_t last = (p.n_ctx - 1) / kTileKeys;
+            int64_t gt = k0 / kTileKeys + t + (lane >> 5);
+            gt = gt < last ? gt : last;
+            load_lds_16((const char*)p.tile_rot, (unsigned)(gt * 512 + (lane & 31) * 16),
+                        __builtin_amdgcn_readfirstlane(lds_addr(rot_s + buf * 1024)));
+        }
+    };
+    // rotate the keys of the tile in buffer `buf` in place: thread = (row r, chunk pair cp), the same
+    // pairing as the assemble kernel; position of row r = (tile's first position) + r
+    auto pool_rotate = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = tid >> 3; r < kTileKeys; r += WAVES * 8) {
+            const int cp = tid & 7;
+            const f32x4* hi = (const f32x4*)(rot_s + buf * 1024 + cp * 64);
+            const f32x4* lo = (const f32x4*)(lo_s + r * 512 + cp * 64);
+            float c[8], sn[8];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const f32x4 h = hi[e2], l = lo[e2];
+                c[2 * e2] = h[0] * l[0] - h[1] * l[1];
+                sn[2 * e2] = h[1] * l[0] + h[0] * l[1];
+                c[2 * e2 + 1] = h[2] * l[2] - h[3] * l[3];
+                sn[2 * e2 + 1] = h[3] * l[2] + h[2] * l[3];
+            }
+            u32x4* a1 = (u32x4*)(k_s[buf] + r * kRowBytes + ((cp ^ (r & 15)) << 4));
+            u32x4* a2 = (u32x4*)(k_s[buf] + r * kRowBytes + (((cp + 8) ^ (r & 15)) << 4));
+            u32x4 x1 = *a1, x2 = *a2;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float a1l = __uint_as_float(x1[w] << 16), a1h = __uint_as_float(x1[w] & 0xffff0000u);
+                const float a2l = __uint_as_float(x2[w] << 16), a2h = __uint_as_float(x2[w] & 0xffff0000u);
+                x1[w] = pack2_bf16(a1l * c[2 * w] - a2l * sn[2 * w], a1h * c[2 * w + 1] - a2h * sn[2 * w + 1]);
+                x2[w] = pack2_bf16(a2l * c[2 * w] + a1l * sn[2 * w], a2h * c[2 * w + 1] + a1h * sn[2 * w + 1]);
+            }
+            *a1 = x1;
+            *a2 = x2;
+        }
+    };
     if (!self) {
-        issue_k(0);
-        issue_v(0);
+        if (POOL) {
+            // the second-level table (32 KB), then tiles 0 and 1; the row indices of tile 2 stay in registers
+#pragma unroll
+            for (int blk = wave; blk < 32; blk += WAVES)
+                load_lds_16((const char*)p.tab_lo, (unsigned)(blk * 1024 + lane * 16),
+                            __builtin_amdgcn_readfirstlane(lds_addr(lo_s + blk * 1024)));
+            pool_index(0);
+            pool_issue(0, 0);
+            pool_index(1);
+            pool_issue(1, 1);
+            pool_index(2);
+        } else {
+            issue_k(0);
+            issue_v(0);
+        }
     }
 
     // Eight (cos, sin) of position `a` for the frequencies f0 .. f0+7: one fp32 angle addition of the two
@@ -516,6 +602,29 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
             }
             __syncthreads();
         }
+    } else if (POOL) {
+        // ---- zero-copy key loop.  Tiles 0 and 1 and the table have landed (wait and barrier above).
+        pool_rotate(0);
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        auto tile_z = [&](int t, int b) __attribute__((always_inline)) {
+            if (!wave_idle) {
+                s_phase(b);
+                softmax_phase(t);
+                pv_phase(b);
+            }
+            // tile t+1, requested a tile ago, has landed for every wavefront; buffer b is free
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            pool_issue(t + 2, b);
+            pool_index(t + 3);
+            if (t + 1 < n_tiles) pool_rotate(b ^ 1);
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        };
+        int t = 0;
+        for (; t + 2 <= n_tiles; t += 2) {
+            tile_z(t, 0);
+            tile_z(t + 1, 1);
+        }
+        if (t < n_tiles) tile_z(t, 0);
     } else {
     issue_k(1);
     issue_v(1);
@@ -601,19 +710,32 @@ hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream) {
     const unsigned blocks = (unsigned)(p.n_kv_heads * n_row_tiles * (p.n_split + (p.no_self ? 0 : 1)));
     if (blocks == 0) return hipSuccess;
     if (p.v_blocks == 1)
-        launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 1>), dim3(blocks),
+        launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 1, false>), dim3(blocks),
                       dim3(kAttnWaves * 64), stream, p, n_row_tiles, (const AttnBatchItem*)nullptr,
                       (const AttnWork*)nullptr);
     else
-        launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 4>), dim3(blocks),
+        launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 4, false>), dim3(blocks),
                       dim3(kAttnWaves * 64), stream, p, n_row_tiles, (const AttnBatchItem*)nullptr,
                       (const AttnWork*)nullptr);
     return hipGetLastError();
 }
 
+hipError_t launch_attn_mfma_pool(const AttnParams& p, hipStream_t stream) {
+    const int g = p.n_q_heads / p.n_kv_heads;
+    const int rows = p.t_q * g;
+    const int n_row_tiles = (rows + kAttnRowTile - 1) / kAttnRowTile;
+    const unsigned blocks = (unsigned)(p.n_kv_heads * n_row_tiles * (p.n_split + 1));
+    if (blocks == 0) return hipSuccess;
+    if (p.no_self || p.split_bounds || !p.slot_src || !p.tile_rot || p.keys_per_split % kTileKeys != 0)
+        return hipErrorInvalidValue;
+    launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 4, true>), dim3(blocks),
+                  dim3(kAttnWaves * 64), stream, p, n_row_tiles, (const AttnBatchItem*)nullptr, (const AttnWork*)nullptr);
+    return hipGetLastError();
+}
+
 hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, hipStream_t stream) {
     if (n_work <= 0) return hipSuccess;
-    launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), true, 4>), dim3((unsigned)n_work),
+    launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), true, 4, false>), dim3((unsigned)n_work),
                        dim3(kAttnWaves * 64), stream, AttnParams{}, 0, items, work);
     return hipGetLastError();
 }

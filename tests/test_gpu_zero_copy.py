@@ -1,0 +1,120 @@
+"""The zero-copy form (adapshot_query_attn_pool): attention straight over the pool through a slot table, keys
+re-encoded inside the key loop.  Checked against the oracle chain plan -> assemble -> attention (the oracle needs
+no change: by R(a)R(b) = R(a+b) the result is that of the assembled cache), and against the two-pass GPU path."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_03644_amd import workloads as wl
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ad():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2605_03644_amd import binding
+    binding.load_library()
+    return binding
+
+
+def _case(ad, oracle_mod, w, ids, order, t_q, pos0=0, q_pos0=None, layer=0, n_layers=1, pairs=None, splits=0):
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=n_layers)
+    ctx = ad.Context.for_workload(w, n_layers=n_layers)
+    ctx.pool_register(k_pool, v_pool, off)
+    seq = [int(ids[o]) for o in order] if order is not None else [int(i) for i in ids]
+    total = int(sum(off[s + 1] - off[s] for s in seq))
+    q_pos0 = pos0 + total if q_pos0 is None else q_pos0
+    q, ks, vs = wl.make_query(w, "cuda", t_q=t_q, layer=layer)
+    ctx.set_attn_splits(splits)
+    out = ctx.query_attn_pool(layer, ids, order, q, ks, vs, q_pos0, pos0=pos0)
+    # the two-pass path on the same inputs
+    cache = ad.Cache(ctx, max(total, 1), with_index=False)
+    ctx.assemble(cache, ids, order, pos0=pos0)
+    two = ctx.query_attn(cache, layer, total, q, ks, vs, q_pos0)
+    torch.cuda.synchronize()
+    kp, vp = H.to_storage(k_pool[layer:layer + 1]), H.to_storage(v_pool[layer:layer + 1])
+    pl = oracle_mod.plan(off, ids, order, slot0=0, pos0=pos0)
+    ko, vo, _ = oracle_mod.assemble(kp, vp, w.dtype, w.rope_theta, 0, pl, 0, max(total, 1))
+    ref = oracle_mod.query_attn(ko[0], vo[0], w.dtype, total, H.to_storage(q), H.to_storage(ks), H.to_storage(vs),
+                                w.rope_theta, q_pos0, pairs=pairs)
+    got, got2 = out.float().cpu().numpy(), two.float().cpu().numpy()
+    assert np.isfinite(got).all()
+    assert float(np.abs(got - got2).max()) <= 2.0 ** -6 * max(1.0, float(np.abs(got2).max()))   # both within rounding of one result
+    if pairs is not None:
+        got = np.stack([got[j, h] for j, h in pairs])
+    res = H.check_attention(got, ref)
+    ctx.close()
+    return res
+
+
+def test_zero_copy_llama8b_full_size(ad, oracle_mod):
+    """Config 2 at full size: 256 shots in a seeded order (~27k tokens), 128 query tokens, every output."""
+    w = wl.WORKLOADS["llama8b_1layer"]
+    ids, order = wl.selection(w)
+    err, fro = _case(ad, oracle_mod, w, ids, order, w.t_q)
+    assert err < 2e-2
+
+
+@pytest.mark.parametrize("n_sel,t_q,pos0,splits", [(1, 1, 0, 0), (3, 16, 0, 0), (9, 128, 11, 0), (5, 37, 100000, 1),
+                                                   (40, 64, 777, 7), (17, 300, 64, 2), (2, 5, 1048576 - 400, 0)])
+def test_zero_copy_small_cases(ad, oracle_mod, n_sel, t_q, pos0, splits):
+    """Ragged contexts, one and several tiles, positions near the table's end, forced split counts, duplicates."""
+    w = wl.WORKLOADS["llama8b_1layer"]
+    ids, order = wl.selection(w, variant=n_sel)
+    ids, order = ids[:n_sel].copy(), np.argsort(np.argsort(order[:n_sel])).astype(np.int32)
+    if n_sel >= 3:
+        ids[1] = ids[0]                                    # a shot selected twice
+    _case(ad, oracle_mod, w, ids, order, t_q, pos0=pos0, splits=splits)
+
+
+def test_zero_copy_other_shapes_layers_and_identity_order(ad, oracle_mod):
+    """g = 7 rows per kv head (Qwen2 shape) on layer 1 of two, order = NULL; g = 8 (70B shape), sampled outputs."""
+    w = wl.WORKLOADS["qwen7b_decode"]
+    ids, _ = wl.selection(w)
+    _case(ad, oracle_mod, w, ids[:30], None, 1, layer=1, n_layers=2)
+    _case(ad, oracle_mod, w, ids[:30], None, 19, layer=1, n_layers=2)
+    w = wl.WORKLOADS["llama70b_128k"]
+    ids, order = wl.selection(w)
+    ids, order = ids[:200], np.argsort(np.argsort(order[:200])).astype(np.int32)
+    rng = np.random.default_rng(5)
+    pairs = np.stack([rng.integers(0, 64, 300), rng.integers(0, w.n_q_heads, 300)], axis=1).astype(np.int32)
+    _case(ad, oracle_mod, w, ids, order, 64, pairs=pairs)
+
+
+def test_zero_copy_empty_context_and_errors(ad, oracle_mod):
+    w = wl.WORKLOADS["llama8b_1layer"]
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=1)
+    ctx = ad.Context.for_workload(w, n_layers=1)
+    q, ks, vs = wl.make_query(w, "cuda", t_q=9)
+    out = torch.full_like(q, 3.0)
+    with pytest.raises(ad.AdapshotError) as e:             # no pool yet
+        ctx.query_attn_pool(0, [1, 2], None, q, ks, vs, 0, out=out)
+    assert e.value.status == ad.ESTATE
+    ctx.pool_register(k_pool, v_pool, off)
+    for bad_ids, bad_order, status in (([1, w.n_shots], None, ad.ESHOT), ([1, 2], [0, 2], ad.ESHOT), ([-1], None, ad.ESHOT)):
+        with pytest.raises(ad.AdapshotError) as e:
+            ctx.query_attn_pool(0, bad_ids, bad_order, q, ks, vs, 0, out=out)
+        assert e.value.status == status
+    with pytest.raises(ad.AdapshotError) as e:             # positions beyond the tables
+        ctx.query_attn_pool(0, [1, 2], None, q, ks, vs, 0, pos0=(1 << 20) - 10, out=out)
+    assert e.value.status == ad.ECAPACITY
+    with pytest.raises(ad.AdapshotError):
+        ctx.query_attn_pool(1, [1, 2], None, q, ks, vs, 0, out=out)
+    torch.cuda.synchronize()
+    assert float(out.float().min()) == 3.0 and float(out.float().max()) == 3.0     # nothing was launched
+    # no shots: the query attends to its own tokens only
+    got = ctx.query_attn_pool(0, [], None, q, ks, vs, 0)
+    ref = oracle_mod.query_attn(H.to_storage(k_pool[0]), H.to_storage(v_pool[0]), w.dtype, 0, H.to_storage(q),
+                                H.to_storage(ks), H.to_storage(vs), w.rope_theta, 0)
+    H.check_attention(got.float().cpu().numpy(), ref)
+    ctx.close()
+    # a pool whose keys were stored rotated is refused (the kernel re-encodes from position-free keys)
+    ctx = ad.Context.for_workload(w, key_state=ad.KEYS_ROTATED_LOCAL, n_layers=1)
+    ctx.pool_register(k_pool, v_pool, off)
+    with pytest.raises(ad.AdapshotError) as e:
+        ctx.query_attn_pool(0, [1, 2], None, q, ks, vs, 0, out=out)
+    assert e.value.status == ad.ESTATE
+    ctx.close()
