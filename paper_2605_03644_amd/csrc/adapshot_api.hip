@@ -570,7 +570,8 @@ static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, c
 
     const size_t esz = (size_t)ctx->elem_bytes;
     hipError_t e = hipSuccess;
-    if (!mfma) {  // the MFMA kernel rotates its rows itself
+    const bool fold = slot_src != nullptr;  // the zero-copy kernel rotates its rows itself
+    if (!fold) {
         e = ctx->q_rot.reserve((size_t)t_q * d.n_q_heads * d.head_dim * esz, ctx->retired);
         if (e == hipSuccess) e = ctx->k_rot.reserve((size_t)t_q * d.n_kv_heads * d.head_dim * esz, ctx->retired);
     }
@@ -593,7 +594,7 @@ static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, c
     rp.head_dim = d.head_dim;
     rp.dtype = d.dtype;
     rp.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
-    if (!mfma) {
+    if (!fold) {
         e = timed_launch(ctx, ADAPSHOT_KERNEL_ROPE_ROWS, stream, [&] { return launch_rope_rows(rp, stream); });
         if (e != hipSuccess) return fail_hip(ctx, "query_attn: rope launch", e);
     }
@@ -601,17 +602,18 @@ static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, c
     AttnParams ap;
     ap.k_cache = k_ctx;
     ap.v_cache = v_ctx;
-    ap.slot_src = slot_src;
-    ap.tile_rot = tile_rot;
+    AttnFold af;
+    af.slot_src = slot_src;
+    af.tile_rot = tile_rot;
     ap.q_rot = ctx->q_rot.p;
     ap.k_self_rot = ctx->k_rot.p;
     ap.v_self = v_self;
-    ap.q_raw = q;
-    ap.k_self_raw = k_self;
-    ap.tab_lo = ctx->tab_lo;
-    ap.tab_hi = ctx->tab_hi;
-    ap.q_pos0 = q_pos0;
-    ap.q_scale = rp.q_scale;
+    af.q_raw = q;
+    af.k_self_raw = k_self;
+    af.tab_lo = ctx->tab_lo;
+    af.tab_hi = ctx->tab_hi;
+    af.q_pos0 = q_pos0;
+    af.q_scale = rp.q_scale;
     ap.part_o = ctx->part_o.p;
     ap.part_mlf = (float4*)ctx->part_ml.p;
     ap.part_half = mfma ? 1 : 0;
@@ -628,8 +630,8 @@ static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, c
     ap.head_dim = d.head_dim;
     ap.dtype = d.dtype;
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream, [&] {
-        if (slot_src) return launch_attn_mfma_pool(ap, stream);
-        return mfma ? launch_attn_mfma(ap, stream) : launch_attn_generic(ap, stream);
+        if (slot_src) return launch_attn_mfma_pool(ap, af, stream);
+        return mfma ? launch_attn_mfma(ap, af, stream) : launch_attn_generic(ap, stream);
     });
     if (e != hipSuccess) return fail_hip(ctx, "query_attn: attention launch", e);
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(ap, stream); });
@@ -646,7 +648,6 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
                                             const adapshot_attn_item* items, int32_t n_items, hipStream_t stream) {
     const adapshot_model_desc& d = ctx->desc;
     const int g = d.n_q_heads / d.n_kv_heads;
-    const size_t esz = (size_t)ctx->elem_bytes;
 
     // ---- split plan
     int64_t tile_units = 0;
@@ -728,17 +729,17 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
         const int64_t layer_off = (int64_t)layer * c.capacity * ctx->row_bytes;
         b.attn.k_cache = (const char*)c.k + layer_off;
         b.attn.v_cache = (const char*)c.v + layer_off;
-        b.attn.slot_src = nullptr;
-        b.attn.tile_rot = nullptr;
+        b.fold.slot_src = nullptr;
+        b.fold.tile_rot = nullptr;
         b.attn.q_rot = nullptr;
         b.attn.k_self_rot = nullptr;
         b.attn.v_self = it.v_self;
-        b.attn.q_raw = it.q;
-        b.attn.k_self_raw = it.k_self;
-        b.attn.tab_lo = ctx->tab_lo;
-        b.attn.tab_hi = ctx->tab_hi;
-        b.attn.q_pos0 = it.q_pos0;
-        b.attn.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
+        b.fold.q_raw = it.q;
+        b.fold.k_self_raw = it.k_self;
+        b.fold.tab_lo = ctx->tab_lo;
+        b.fold.tab_hi = ctx->tab_hi;
+        b.fold.q_pos0 = it.q_pos0;
+        b.fold.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
         b.attn.part_o = (char*)ctx->part_o.p + pl.po_off;
         b.attn.part_mlf = (float4*)((char*)ctx->part_ml.p + pl.pml_off);
         b.attn.part_half = 1;
@@ -1170,29 +1171,48 @@ extern "C" adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer,
     const int64_t n_pairs = rows * d.n_kv_heads;
     const int32_t n_split = ctx->rank_n_split;
     const size_t esz = (size_t)ctx->elem_bytes;
-    hipError_t e = ctx->part_o.reserve((size_t)n_split * n_pairs * d.head_dim * 2, ctx->retired);
+    hipError_t e = ctx->q_rot.reserve((size_t)t_q * d.n_q_heads * d.head_dim * esz, ctx->retired);
+    if (e == hipSuccess) e = ctx->part_o.reserve((size_t)n_split * n_pairs * d.head_dim * 2, ctx->retired);
     if (e == hipSuccess) e = ctx->part_ml.reserve((size_t)n_split * n_pairs * sizeof(float4), ctx->retired);
     if (e == hipSuccess) e = ctx->rank_w.reserve((size_t)n_split * n_pairs * sizeof(float), ctx->retired);
     if (e == hipSuccess)
         e = ctx->rank_part.reserve((size_t)n_split * (size_t)((n_pairs + 255) / 256) * 128 * sizeof(float), ctx->retired);
     if (e != hipSuccess) return fail_hip(ctx, "rank_shots: workspace", e);
 
+    RopeRowsParams rp;  // the query rows rotated to q_pos0 + j and scaled, in a launch of their own
+    rp.q = q;
+    rp.k_self = nullptr;
+    rp.q_rot = ctx->q_rot.p;
+    rp.k_rot = nullptr;
+    rp.tab_lo = ctx->tab_lo;
+    rp.tab_hi = ctx->tab_hi;
+    rp.q_pos0 = q_pos0;
+    rp.t_q = t_q;
+    rp.n_q_heads = d.n_q_heads;
+    rp.n_kv_heads = d.n_kv_heads;
+    rp.head_dim = d.head_dim;
+    rp.dtype = d.dtype;
+    rp.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ROPE_ROWS, stream, [&] { return launch_rope_rows(rp, stream); });
+    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: rope launch", e);
+
     AttnParams ap;
     ap.k_cache = d.key_state == ADAPSHOT_KEYS_UNROTATED
                      ? ctx->rank_k.p
                      : (const void*)((const char*)ctx->k_pool + (int64_t)layer * ctx->pool_layer_stride_tokens * ctx->row_bytes);
     ap.v_cache = ctx->rank_v.p;
-    ap.slot_src = nullptr;
-    ap.tile_rot = nullptr;
-    ap.q_rot = nullptr;
+    AttnFold af;
+    af.slot_src = nullptr;
+    af.tile_rot = nullptr;
+    ap.q_rot = ctx->q_rot.p;
     ap.k_self_rot = nullptr;
     ap.v_self = nullptr;
-    ap.q_raw = q;
-    ap.k_self_raw = nullptr;
-    ap.tab_lo = ctx->tab_lo;
-    ap.tab_hi = ctx->tab_hi;
-    ap.q_pos0 = q_pos0;
-    ap.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
+    af.q_raw = q;
+    af.k_self_raw = nullptr;
+    af.tab_lo = ctx->tab_lo;
+    af.tab_hi = ctx->tab_hi;
+    af.q_pos0 = q_pos0;
+    af.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
     ap.part_o = ctx->part_o.p;
     ap.part_mlf = (float4*)ctx->part_ml.p;
     ap.part_half = 1;
@@ -1208,7 +1228,7 @@ extern "C" adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer,
     ap.n_kv_heads = d.n_kv_heads;
     ap.head_dim = d.head_dim;
     ap.dtype = d.dtype;
-    e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream, [&] { return launch_attn_mfma(ap, stream); });
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream, [&] { return launch_attn_mfma(ap, af, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "rank_shots: attention launch", e);
 
     RankReduceParams rr;

@@ -105,26 +105,30 @@ hipError_t launch_rope_rows(const RopeRowsParams& p, hipStream_t stream);
 // Split plan: splits 0..n_split-1 cover context keys [s*keys_per_split, ...) and
 // split n_split is the causal self part.  Partials are indexed [split][kv head][row]
 // with row = j*g + (h % g).
-struct AttnParams {
-    const void* k_cache;  // one layer [>=n_ctx][h_kv][d]
-    const void* v_cache;
-    const void* q_rot;       // generic kernel: rows rotated and scaled by rope_rows
-    const void* k_self_rot;  // generic kernel: the query's own keys rotated by rope_rows
-    const void* v_self;
-    // MFMA kernel: it rotates the rows it needs itself (Eq. rope_encoding at position q_pos0 + j), the
-    // query rows scaled by q_scale = log2(e)/sqrt(d) on the way into its fragments, the query's own keys
-    // on the way into LDS
+// What only the MFMA kernel's prologue (and its zero-copy form) reads.  Kept apart from AttnParams so that none
+// of it occupies scalar registers during the key loop.
+struct AttnFold {
+    // The kernel rotates the rows it needs itself (Eq. rope_encoding at position q_pos0 + j), the query rows
+    // scaled by q_scale = log2(e)/sqrt(d) on the way into its fragments, the query's own keys on the way into LDS.
     const void* q_raw;       // [t_q][h_q][d] as the caller gave it
     const void* k_self_raw;  // [t_q][h_kv][d] as the caller gave it
     const float2* tab_lo;
     const float2* tab_hi;
     int64_t q_pos0;
     float q_scale;
-    // Zero-copy form (MFMA kernel, template parameter POOL): k_cache / v_cache are the POOL's layer, context slot u
-    // holds pool token slot_src[u], and its key is rotated to position pos0 + u inside the key loop;
+    // Zero-copy form (template parameter POOL): k_cache / v_cache are the POOL's layer, context slot u holds pool
+    // token slot_src[u], and its key is rotated to position pos0 + u inside the key loop;
     // tile_rot[i][f] = (cos, sin)((pos0 + 64 i) theta_f) for every 64-slot tile of the context.
     const int32_t* slot_src;
     const float2* tile_rot;
+};
+
+struct AttnParams {
+    const void* k_cache;  // one layer [>=n_ctx][h_kv][d]
+    const void* v_cache;
+    const void* q_rot;       // generic kernel: rows rotated and scaled by rope_rows
+    const void* k_self_rot;  // generic kernel: the query's own keys rotated by rope_rows
+    const void* v_self;
     // Partials, indexed [n_split+1][h_kv][rows]: part_mlf = (reference maximum in log2 units, row sum l,
     // factor f, unused) and a row O' of d values with  sum_k p_k v_k = f * O'.
     //   part_half = 0: O' is the unnormalised fp32 accumulator, f = 1 (generic kernel);
@@ -147,8 +151,8 @@ struct AttnParams {
 };
 constexpr int kAttnRowTile = 256;  // query rows per workgroup of the MFMA kernel
 hipError_t launch_attn_generic(const AttnParams& p, hipStream_t stream);
-hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream);
-hipError_t launch_attn_mfma_pool(const AttnParams& p, hipStream_t stream);  // zero-copy form
+hipError_t launch_attn_mfma(const AttnParams& p, const AttnFold& f, hipStream_t stream);
+hipError_t launch_attn_mfma_pool(const AttnParams& p, const AttnFold& f, hipStream_t stream);  // zero-copy form
 // Expands the per-shot segments of a zero-copy context into slot_src and builds tile_rot.
 struct PoolSeg {
     int32_t slot0, src_tok0, len, pad;
@@ -172,6 +176,7 @@ hipError_t launch_attn_combine(const AttnParams& p, hipStream_t stream);
 // the queries of a probe sweep are all such batches (Probe-based Dynamic Evaluation).
 struct AttnBatchItem {
     AttnParams attn;
+    AttnFold fold;
 };
 struct AttnWork {  // one workgroup of the batched MFMA kernel
     int32_t item, hk, row_tile, split;

@@ -145,9 +145,14 @@ __device__ __forceinline__ T load_uniform(const T* ptr) {
 // second-level table in LDS adds the row's index inside the tile).  Two tiles in LDS per operand, two
 // workgroup barriers per tile (tile landed -> rotate -> rotated keys visible), every wavefront in the order
 // S, softmax, PV.  What a context split computes is what the plain form computes over the assembled cache.
-template <int WAVES, int NR, bool BATCHED, int PVB, bool POOL>
-__global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg, int n_row_tiles_arg,
-                                                               const AttnBatchItem* items, const AttnWork* work) {
+// FOLD: the workgroup rotates its query rows (and the self split its keys) itself; otherwise rope_rows has
+// done that in a launch of its own and the kernel reads q_rot / k_self_rot.  Folding saves the launch and is
+// what the batched calls use (decode steps and probes have few rows per kv head); for one query with hundreds of
+// rows per kv head the rotation repeated in every context split costs the kernel more than the launch did.
+template <int WAVES, int NR, bool BATCHED, int PVB, bool POOL, bool FOLD>
+__global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg, AttnFold f_arg,
+                                                               int n_row_tiles_arg, const AttnBatchItem* items,
+                                                               const AttnWork* work) {
     constexpr int PASSES = (kTileKeys * 16) / (WAVES * 64);  // 1 KB blocks of a tile per wavefront
     static_assert(PASSES * WAVES * 64 == kTileKeys * 16, "tile must divide over the threads");
     static_assert(WAVES * NR * 32 == kAttnRowTile && NR == 1, "row tile");
@@ -162,8 +167,10 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
 
     AttnParams p;
     int hk, row_tile, split;
+    int item = 0;
     if (BATCHED) {
         const AttnWork w = load_uniform(work + blockIdx.x);
+        item = w.item;
         p = load_uniform(&items[w.item].attn);
         hk = w.hk;
         row_tile = w.row_tile;
@@ -178,6 +185,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
         split = rest / n_row_tiles_arg;
     }
     const bool self = !p.no_self && split == p.n_split;
+    // the prologue-only arguments are fetched where they are used, not held through the key loop
+    auto fold = [&]() __attribute__((always_inline)) -> AttnFold {
+        if (BATCHED) return load_uniform(&items[item].fold);
+        return f_arg;
+    };
 
     const int g = p.n_q_heads / p.n_kv_heads;
     const int rows = p.t_q * g;
@@ -189,7 +201,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     }
 
     // ---- key range of this split
-    const char* kbase = (const char*)(self ? p.k_self_raw : p.k_cache) + hk * kRowBytes;
+    // context splits; a folding kernel's self split has a path of its own
+    const char* kbase = (const char*)(!FOLD && self ? p.k_self_rot : p.k_cache) + hk * kRowBytes;
     const char* vbase = (const char*)(self ? p.v_self : p.v_cache) + hk * kRowBytes;
     const int64_t kv_stride = (int64_t)p.n_kv_heads * kRowBytes;
     int64_t k0, k1;
@@ -268,6 +281,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     // holds the two tiles' rotation rows (1 KB slots), v_s[2..3] the 32 KB second-level table.
     char* const rot_s = k_s[2];
     char* const lo_s = v_s[2];
+    AttnFold pf{};
+    if (POOL) pf = fold();
     unsigned pool_idx[PASSES];  // byte offsets of this lane's rows of the next tile to request
     auto pool_index = [&](int t) __attribute__((always_inline)) {
 #pragma unroll
@@ -275,7 +290,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
             const int r = 4 * (ps * WAVES + wave) + (lane >> 4);
             int64_t key = k0 + (int64_t)t * kTileKeys + r;
             key = key < k1 ? key : k1 - 1;  // rows past the end (masked by the softmax) repeat the last key
-            pool_idx[ps] = (unsigned)p.slot_src[key] * (unsigned)kv_stride;  // the host keeps a pool layer below 4 GiB
+            pool_idx[ps] = (unsigned)pf.slot_src[key] * (unsigned)kv_stride;  // the host keeps a pool layer below 4 GiB
         }
     };
     auto pool_issue = [&](int t, int buf) __attribute__((always_inline)) {
@@ -295,7 +310,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
             const int64_t last = (p.n_ctx - 1) / kTileKeys;
             int64_t gt = k0 / kTileKeys + t + (lane >> 5);
             gt = gt < last ? gt : last;
-            load_lds_16((const char*)p.tile_rot, (unsigned)(gt * 512 + (lane & 31) * 16),
+            load_lds_16((const char*)pf.tile_rot, (unsigned)(gt * 512 + (lane & 31) * 16),
                         __builtin_amdgcn_readfirstlane(lds_addr(rot_s + buf * 1024)));
         }
     };
@@ -330,12 +345,12 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
             *a2 = x2;
         }
     };
-    if (!self) {
+    if (!self || !FOLD) {
         if (POOL) {
             // the second-level table (32 KB), then tiles 0 and 1; the row indices of tile 2 stay in registers
 #pragma unroll
             for (int blk = wave; blk < 32; blk += WAVES)
-                load_lds_16((const char*)p.tab_lo, (unsigned)(blk * 1024 + lane * 16),
+                load_lds_16((const char*)pf.tab_lo, (unsigned)(blk * 1024 + lane * 16),
                             __builtin_amdgcn_readfirstlane(lds_addr(lo_s + blk * 1024)));
             pool_index(0);
             pool_issue(0, 0);
@@ -350,9 +365,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
 
     // Eight (cos, sin) of position `a` for the frequencies f0 .. f0+7: one fp32 angle addition of the two
     // fp64-built table entries (a = 64*hi + lo).
-    auto cos_sin8 = [&](int64_t a, int f0, float (&c)[8], float (&sn)[8]) __attribute__((always_inline)) {
-        const f32x4* th = (const f32x4*)(p.tab_hi + (a >> kRopeLoBits) * (kD / 2) + f0);
-        const f32x4* tl = (const f32x4*)(p.tab_lo + (a & (kRopeLo - 1)) * (kD / 2) + f0);
+    auto cos_sin8 = [&](const AttnFold& f, int64_t a, int f0, float (&c)[8], float (&sn)[8]) __attribute__((always_inline)) {
+        const f32x4* th = (const f32x4*)(f.tab_hi + (a >> kRopeLoBits) * (kD / 2) + f0);
+        const f32x4* tl = (const f32x4*)(f.tab_lo + (a & (kRopeLo - 1)) * (kD / 2) + f0);
 #pragma unroll
         for (int e2 = 0; e2 < 4; ++e2) {
             const f32x4 h = th[e2], l = tl[e2];  // two frequencies: (cos, sin, cos, sin)
@@ -381,19 +396,23 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     // softmax scale in, without another pass over Q in memory.
     bf16x8 qf[8];
     {
+        AttnFold f{};
+        if (FOLD) f = fold();
         const bool valid = row[0] < rows;
         const int j = valid ? jrow[0] : 0;
         const int gq = valid ? row[0] - j * g : 0;
-        const char* qrow = (const char*)p.q_raw + ((int64_t)(j * p.n_q_heads + hk * g + gq) * kD) * 2;
+        const char* qrow = (const char*)(FOLD ? f.q_raw : p.q_rot) + ((int64_t)(j * p.n_q_heads + hk * g + gq) * kD) * 2;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             u32x4 x1 = {0u, 0u, 0u, 0u}, x2 = {0u, 0u, 0u, 0u};
             if (valid) {
                 x1 = *(const u32x4*)(qrow + (16 * kk + 8 * hh) * 2);
                 x2 = *(const u32x4*)(qrow + (16 * (kk + 4) + 8 * hh) * 2);
-                float c[8], sn[8];
-                cos_sin8(p.q_pos0 + j, 16 * kk + 8 * hh, c, sn);
-                rotate8(x1, x2, c, sn, p.q_scale);
+                if (FOLD) {
+                    float c[8], sn[8];
+                    cos_sin8(f, f.q_pos0 + j, 16 * kk + 8 * hh, c, sn);
+                    rotate8(x1, x2, c, sn, f.q_scale);
+                }
             }
             qf[kk] = __builtin_bit_cast(bf16x8, x1);
             qf[kk + 4] = __builtin_bit_cast(bf16x8, x2);
@@ -567,21 +586,23 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     // A wavefront whose 32 rows all lie past the last query row (a decode step has fewer rows than one
     // wavefront owns) only moves tiles and keeps the barriers.
     const bool wave_idle = row_tile * kAttnRowTile + wave * NR * 32 >= rows;
-    if (self) {
+    if (self && FOLD) {
         // ---- the query's own tokens: a few tiles at most, moved through registers so that the keys can be
         // rotated to their positions q_pos0 + u on the way (the caller gives them un-rotated).  One tile at a
         // time in buffer 0, two workgroup barriers per tile.  Thread = (row r, chunk pair cp) for K, two
         // (row, chunk) items for V; rows past the last token are zero-filled (and masked by the softmax).
+        const AttnFold f = fold();
+        const char* ksbase = (const char*)f.k_self_raw + hk * kRowBytes;
         const int r = tid >> 3, cp = tid & 7;
         for (int t = 0; t < n_tiles; ++t) {
             const int u = t * kTileKeys + r;
             u32x4 x1 = {0u, 0u, 0u, 0u}, x2 = {0u, 0u, 0u, 0u};
             if (u < n_keys) {
-                const char* krow = kbase + (int64_t)u * kv_stride;
+                const char* krow = ksbase + (int64_t)u * kv_stride;
                 x1 = *(const u32x4*)(krow + cp * 16);
                 x2 = *(const u32x4*)(krow + (cp + 8) * 16);
                 float c[8], sn[8];
-                cos_sin8(p.q_pos0 + u, 8 * cp, c, sn);
+                cos_sin8(f, f.q_pos0 + u, 8 * cp, c, sn);
                 rotate8(x1, x2, c, sn, 1.0f);
             }
             *(u32x4*)(k_s[0] + r * kRowBytes + ((cp ^ (r & 15)) << 4)) = x1;
@@ -703,40 +724,40 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     }
 }
 
-hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream) {
+hipError_t launch_attn_mfma(const AttnParams& p, const AttnFold& f, hipStream_t stream) {
     const int g = p.n_q_heads / p.n_kv_heads;
     const int rows = p.t_q * g;
     const int n_row_tiles = (rows + kAttnRowTile - 1) / kAttnRowTile;
     const unsigned blocks = (unsigned)(p.n_kv_heads * n_row_tiles * (p.n_split + (p.no_self ? 0 : 1)));
     if (blocks == 0) return hipSuccess;
     if (p.v_blocks == 1)
-        launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 1, false>), dim3(blocks),
-                      dim3(kAttnWaves * 64), stream, p, n_row_tiles, (const AttnBatchItem*)nullptr,
+        launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 1, false, false>), dim3(blocks),
+                      dim3(kAttnWaves * 64), stream, p, f, n_row_tiles, (const AttnBatchItem*)nullptr,
                       (const AttnWork*)nullptr);
     else
-        launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 4, false>), dim3(blocks),
-                      dim3(kAttnWaves * 64), stream, p, n_row_tiles, (const AttnBatchItem*)nullptr,
+        launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 4, false, false>), dim3(blocks),
+                      dim3(kAttnWaves * 64), stream, p, f, n_row_tiles, (const AttnBatchItem*)nullptr,
                       (const AttnWork*)nullptr);
     return hipGetLastError();
 }
 
-hipError_t launch_attn_mfma_pool(const AttnParams& p, hipStream_t stream) {
+hipError_t launch_attn_mfma_pool(const AttnParams& p, const AttnFold& f, hipStream_t stream) {
     const int g = p.n_q_heads / p.n_kv_heads;
     const int rows = p.t_q * g;
     const int n_row_tiles = (rows + kAttnRowTile - 1) / kAttnRowTile;
     const unsigned blocks = (unsigned)(p.n_kv_heads * n_row_tiles * (p.n_split + 1));
     if (blocks == 0) return hipSuccess;
-    if (p.no_self || p.split_bounds || !p.slot_src || !p.tile_rot || p.keys_per_split % kTileKeys != 0)
+    if (p.no_self || p.split_bounds || !f.slot_src || !f.tile_rot || p.keys_per_split % kTileKeys != 0)
         return hipErrorInvalidValue;
-    launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 4, true>), dim3(blocks),
-                  dim3(kAttnWaves * 64), stream, p, n_row_tiles, (const AttnBatchItem*)nullptr, (const AttnWork*)nullptr);
+    launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 4, true, true>), dim3(blocks),
+                  dim3(kAttnWaves * 64), stream, p, f, n_row_tiles, (const AttnBatchItem*)nullptr, (const AttnWork*)nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, hipStream_t stream) {
     if (n_work <= 0) return hipSuccess;
-    launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), true, 4, false>), dim3((unsigned)n_work),
-                       dim3(kAttnWaves * 64), stream, AttnParams{}, 0, items, work);
+    launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), true, 4, false, true>), dim3((unsigned)n_work),
+                       dim3(kAttnWaves * 64), stream, AttnParams{}, AttnFold{}, 0, items, work);
     return hipGetLastError();
 }
 
