@@ -318,3 +318,36 @@ def test_assemble_batched_many_caches_one_call(ad, oracle_mod):
         assert np.array_equal(caches[ci].slot_shot[:n1 + n2].cpu().numpy(), np.concatenate([pl1["slot_shot"], pl2["slot_shot"]]))
         assert (caches[ci].slot_pos[n1 + n2:] == -1).all()
     ctx.close()
+
+
+def test_context_at_the_4gib_per_layer_limit(ad, oracle_mod):
+    """The attention kernels address a key row by a 32-bit byte offset inside its layer.  A context of 2 097 151
+    Llama-shaped rows (4 GiB - 2 KiB per operand) is the largest one accepted: its sampled outputs are checked
+    against the oracle (the last context split works at offsets just below 2^32); one more row is refused
+    before anything is launched."""
+    w = wl.WORKLOADS["llama8b_1layer"]
+    n_max = (1 << 32) // (w.n_kv_heads * w.head_dim * 2) - 1
+    assert n_max == 2097151
+    ctx = ad.Context.for_workload(w, n_layers=1, max_position=1 << 22)
+    cache = ad.Cache(ctx, n_max + 17, with_index=False)
+    cache.k = wl.normal_tensor(tuple(cache.k.shape), torch.bfloat16, "cuda", 901)     # any keys will do: the oracle sees the same bits
+    cache.v = wl.normal_tensor(tuple(cache.v.shape), torch.bfloat16, "cuda", 902)
+    cache.c.k, cache.c.v = cache.k.data_ptr(), cache.v.data_ptr()
+    cache.c.len = n_max + 17
+    t_q = 3
+    q, ks, vs = wl.make_query(w, "cuda", t_q=t_q)
+    q[1, 5] = (cache.k[0, n_max - 1, 1].float() * 0.5).bfloat16()     # a row that looks at the very last key (un-rotated: close enough to matter)
+    out = torch.full_like(q, 7.0)
+    with pytest.raises(ad.AdapshotError) as e:
+        ctx.query_attn(cache, 0, n_max + 1, q, ks, vs, n_max + 1, out=out)
+    assert e.value.status == ad.EINVAL and "4 GiB" in e.value.message
+    torch.cuda.synchronize()
+    assert float(out.float().min()) == 7.0 and float(out.float().max()) == 7.0
+    ctx.query_attn(cache, 0, n_max, q, ks, vs, n_max, out=out)
+    torch.cuda.synchronize()
+    pairs = np.array([[0, 0], [1, 5], [2, 31], [0, 17], [2, 8], [1, 30]], np.int32)
+    ref = oracle_mod.query_attn(H.to_storage(cache.k[0]), H.to_storage(cache.v[0]), w.dtype, n_max, H.to_storage(q),
+                                H.to_storage(ks), H.to_storage(vs), w.rope_theta, n_max, pairs=pairs)
+    o = out.float().cpu().numpy()
+    H.check_attention(np.stack([o[j, h] for j, h in pairs]), ref)
+    ctx.close()
