@@ -170,7 +170,7 @@ extern "C" const char* adapshot_last_error(const adapshot_ctx* ctx) {
 
 // Validation of a model description; no device access.
 static const char* check_desc(const adapshot_model_desc& d) {
-    if (d.n_layers < 1) return "n_layers must be >= 1";
+    if (d.n_layers < 1 || d.n_layers > 65535) return "n_layers must be in [1, 65535]";
     if (d.n_kv_heads < 1 || d.n_q_heads < 1) return "head counts must be >= 1";
     if (d.n_q_heads % d.n_kv_heads != 0) return "n_q_heads must be a multiple of n_kv_heads";
     if (d.dtype != ADAPSHOT_F32 && d.dtype != ADAPSHOT_BF16) return "dtype must be ADAPSHOT_F32 or ADAPSHOT_BF16";
@@ -398,11 +398,6 @@ static adapshot_status run_assemble(adapshot_ctx* ctx, AssembleJob* jobs, int32_
         p.n_layers = ctx->desc.n_layers;
         p.n_dst = j1 - j0;
         p.wg_tok = ctx->assemble_wg_tok;
-        // Enough workgroups to fill the chip several times over; beyond that a group walks its layers
-        // so that the per-token cos/sin are formed once and reused.
-        const int64_t wgs = nt * (kTileTok / p.wg_tok);
-        const int64_t want_groups = ((int64_t)ctx->n_cu * 32 + wgs - 1) / wgs;
-        p.layer_groups = (int32_t)std::max<int64_t>(1, std::min<int64_t>(ctx->desc.n_layers, want_groups));
         p.n_kv_heads = ctx->desc.n_kv_heads;
         p.head_dim = ctx->desc.head_dim;
         p.dtype = ctx->desc.dtype;

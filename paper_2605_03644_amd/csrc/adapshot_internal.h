@@ -57,7 +57,6 @@ struct AssembleParams {
     int64_t pool_layer_stride_bytes;
     int32_t n_tiles;
     int32_t n_layers;
-    int32_t layer_groups;  // gridDim.y; each group strides over the layers
     int32_t n_dst;         // caches of this launch (entries of dst in use)
     int32_t wg_tok;        // tokens of a tile per workgroup: a power of two <= kTileTok (kTileTok / wg_tok workgroups per tile)
     int32_t n_kv_heads;

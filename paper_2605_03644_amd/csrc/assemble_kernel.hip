@@ -6,7 +6,10 @@
 // wavefront access is a run of full 128-byte lines.  HBM-bound: per token and layer
 // the kernel reads one K row and one V row and writes one of each.
 //
-//   blockIdx.x = (tile, part of the tile), blockIdx.y = layer group (strides over layers), blockIdx.z = 0: K, 1: V.
+//   blockIdx.x = (tile, part of the tile), blockIdx.y = layer, blockIdx.z = 0: K, 1: V.
+// One layer per workgroup, layer slowest in the dispatch order: the workgroups in flight then work on one or two
+// layers, i.e. on two narrow address windows, instead of walking all layers each at its own pace (a multi-layer
+// gather copy of the same blocks: 5.47 TB/s against 5.10 TB/s; this kernel on 28..32 layers: +1.5 .. +6 %).
 // A workgroup takes wg_tok consecutive tokens of a tile, about 16 KB per layer and operand, and keeps 64 bytes
 // per lane in flight with 58 registers (8 wavefronts per SIMD): many small workgroups stream faster on this part
 // than few large ones (plain gather copies into 2 GB: 5.5 TB/s in 16 KB blocks, 5.2 TB/s in 64 KB and larger
@@ -19,7 +22,7 @@
 // a = 64*hi + lo -- and then stream all heads and layers through it: a lane owns the
 // two 16-byte chunks that hold the pair partners (i, i + d/2), rotates them in fp32 and
 // stores both.  V workgroups are a plain 128-bit copy.  Both streams keep their loads one step ahead of
-// their stores (the first K step is requested before the angle table is built): -8 % on a 27k-token launch.
+// their stores, and the first K step is requested before the angle table is built.
 #include "adapshot_internal.h"
 
 namespace adapshot {
@@ -105,25 +108,16 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
             for (int u = 0; u < 4; ++u)
                 if (i0 + 256 * u < n16) st16(dst + ((int64_t)(i0 + 256 * u) << 4), r[u]);
         };
-        int l = blockIdx.y, i0 = tid;
-        bool have = l < p.n_layers;
+        const int l = blockIdx.y;
         u32x4 cur[4];
-        if (have) vload(l, i0, cur);
-        while (have) {
-            int ln = l, in = i0 + 1024;
-            if (in - tid >= n16) {  // this layer's rows are done (workgroup-uniform test)
-                in = tid;
-                ln += p.layer_groups;
-            }
-            const bool more = ln < p.n_layers;
+        vload(l, tid, cur);
+        for (int i0 = tid; i0 - tid < n16; i0 += 1024) {
+            const bool more = i0 + 1024 - tid < n16;  // workgroup-uniform
             u32x4 nxt[4];
-            if (more) vload(ln, in, nxt);
+            if (more) vload(l, i0 + 1024, nxt);
             vstore(l, i0, cur);
 #pragma unroll
             for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
-            l = ln;
-            i0 = in;
-            have = more;
         }
         return;
     }
@@ -175,9 +169,11 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
     };
     // The first keys are requested before the angle table is built, so that the table's own loads and
     // arithmetic run under their latency.
-    const int l0 = blockIdx.y;
+    const int l = blockIdx.y;
+    const char* ksrc = p.k_pool + (int64_t)l * p.pool_layer_stride_bytes + src_off;
+    char* kdst = dc.k_out + (int64_t)l * dc.layer_stride_bytes + dst_off;
     Step first;
-    if (l0 < p.n_layers) load_step(p.k_pool + (int64_t)l0 * p.pool_layer_stride_bytes + src_off, 0, first);
+    load_step(ksrc, 0, first);
 
     // cos/sin of every (token, frequency) of the tile, two frequencies per step.
     for (int it = tid; it < n_tok * (HALF / 2); it += 256) {
@@ -195,31 +191,21 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
     }
     __syncthreads();
 
-    // The stream runs one step ahead: the loads of the next step (the next 1024 items of this layer, or the
-    // first of the next layer) are in flight while the current one is rotated and stored.
-    int l = l0, base = 0;
-    bool have = l0 < p.n_layers;
+    // The stream runs one step ahead: the loads of the next KI * 256 items are in flight while the current ones
+    // are rotated and stored.
     Step cur = first;
-    while (have) {
-        int ln = l, bn = base + KI * 256;
-        if (bn >= n_items) {
-            bn = 0;
-            ln += p.layer_groups;
-        }
-        const bool more = ln < p.n_layers;
+    for (int base = 0; base < n_items; base += KI * 256) {
+        const bool more = base + KI * 256 < n_items;
         Step nxt;
-        if (more) load_step(p.k_pool + (int64_t)ln * p.pool_layer_stride_bytes + src_off, bn, nxt);
-        store_step(dc.k_out + (int64_t)l * dc.layer_stride_bytes + dst_off, base, cur);
+        if (more) load_step(ksrc, base + KI * 256, nxt);
+        store_step(kdst, base, cur);
         cur = nxt;
-        l = ln;
-        base = bn;
-        have = more;
     }
 }
 
 template <int DTYPE, int CH>
 static hipError_t launch_t(const AssembleParams& p, hipStream_t stream) {
-    dim3 grid((unsigned)p.n_tiles * (unsigned)(kTileTok / p.wg_tok), (unsigned)p.layer_groups, 2);
+    dim3 grid((unsigned)p.n_tiles * (unsigned)(kTileTok / p.wg_tok), (unsigned)p.n_layers, 2);
     launch_kernel((assemble_reencode_kernel<DTYPE, CH>), grid, dim3(256), stream, p);
     return hipGetLastError();
 }
