@@ -522,6 +522,43 @@ static adapshot_status check_query_attn(adapshot_ctx* ctx, const adapshot_cache*
     return ADAPSHOT_OK;
 }
 
+// Split count of one MFMA attention launch.  The grid is `units` (kv head, row tile) pairs times the context
+// splits, plus one workgroup per unit for the query's own tokens; one workgroup occupies a compute unit, and
+// the self workgroups are dispatched first.  A handful of candidate counts -- everything in one round beside
+// the self workgroups, one context split per compute unit with the last of them starting when the self
+// workgroups are done, and two to four rounds of that -- are priced in 64-key tiles plus a fixed
+// per-workgroup cost, and the cheapest wins (the smaller count on a tie).  A short context fits everything into
+// one round (26k tokens, 16 units: 15 splits of 29 tiles beside the 16 self workgroups); a long one does not
+// leave the self workgroups' compute units idle (127k tokens, 64 units: 4 splits of 495 tiles, not 3 of 660).
+static int64_t plan_mfma_splits(int64_t n_cu, int64_t units, int64_t key_tiles, int64_t self_tiles) {
+    const double fixed = 2.5;  // launch, first tile round trip and partial write-out of a workgroup, in tiles
+    const int64_t s_max = std::min<int64_t>(key_tiles, 64);
+    const double ls = (double)self_tiles + fixed;
+    auto price = [&](int64_t s) {
+        const double l = (double)((key_tiles + s - 1) / s) + fixed;
+        const int64_t n = units * s;
+        double t;
+        if (units + n <= n_cu) t = std::max(l, ls);          // one round
+        else if (n <= n_cu && units <= n_cu) t = ls + l;      // the context workgroups that do not fit wait for the self ones
+        else t = ceil(((double)n * l + (double)units * ls) / ((double)n_cu * l)) * l;  // whole rounds
+        return t + 0.02 * (double)s;                           // partials cost a little too
+    };
+    const int64_t one_round = (n_cu - units) / units, per_cu = n_cu / units;
+    const int64_t cand[6] = {1, one_round, per_cu, 2 * per_cu, 3 * per_cu, 4 * per_cu};
+    int64_t best = 1;
+    double best_t = price(1);
+    for (int64_t c : cand) {
+        int64_t sc = std::max<int64_t>(1, std::min<int64_t>(c, s_max));
+        sc = (key_tiles + ((key_tiles + sc - 1) / sc) - 1) / ((key_tiles + sc - 1) / sc);  // the count this split length gives
+        const double t = price(sc);
+        if (t < best_t - 1e-9 || (t < best_t + 1e-9 && sc < best)) {
+            best = sc;
+            best_t = t;
+        }
+    }
+    return best;
+}
+
 // k_ctx / v_ctx: one layer of the context the rows attend over -- the assembled cache, or, for the zero-copy form
 // (slot_src and tile_rot given), one layer of the pool.
 static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, const void* v_ctx, int64_t n_ctx,
@@ -554,10 +591,12 @@ static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, c
     const int64_t key_tiles = (n_ctx + 63) / 64;
     int64_t n_split = 0, keys_per_split = 64;
     if (key_tiles > 0) {
-        // MFMA kernel: one workgroup per compute unit including the self-part workgroups (one per unit)
-        const int64_t want = mfma ? std::max<int64_t>(units, (int64_t)ctx->n_cu - units) : (int64_t)ctx->n_cu * 8;
-        const int64_t target = std::max<int64_t>(1, want / units);
-        n_split = std::min<int64_t>(std::min<int64_t>(target, key_tiles), 64);
+        if (mfma) {
+            n_split = plan_mfma_splits(ctx->n_cu, units, key_tiles, ((int64_t)t_q + 63) / 64);
+        } else {
+            const int64_t target = std::max<int64_t>(1, (int64_t)ctx->n_cu * 8 / units);
+            n_split = std::min<int64_t>(std::min<int64_t>(target, key_tiles), 64);
+        }
         if (ctx->force_splits > 0) n_split = std::min<int64_t>(ctx->force_splits, key_tiles);
         keys_per_split = ((key_tiles + n_split - 1) / n_split) * 64;
         n_split = (n_ctx + keys_per_split - 1) / keys_per_split;

@@ -183,6 +183,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
         const int rest = blockIdx.x / p.n_kv_heads;
         row_tile = rest % n_row_tiles_arg;
         split = rest / n_row_tiles_arg;
+        // the self split is dispatched first: its workgroups are short, and what the grid has beyond one
+        // workgroup per compute unit then starts as soon as they are done
+        if (!p.no_self) split = split == 0 ? p.n_split : split - 1;
     }
     const bool self = !p.no_self && split == p.n_split;
     // the prologue-only arguments are fetched where they are used, not held through the key loop
