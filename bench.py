@@ -286,6 +286,20 @@ def extras(ad, dev) -> dict:
             "assemble_ms": best * 1e3, "assemble_gbps": moved / best * 1e-9,
             "assemble_frac_of_hbm_peak": moved / best * 1e-9 / HBM_PEAK_GBPS,
             "sweep_attention_all_layers_ms": dta * 1e3, "attention_tflops": flops * w.n_layers / dta * 1e-12}
+        # the same 48 probes with no assembled caches at all: one zero-copy batched call per layer over the 8 ranked
+        # lists where they lie in the pool (the items are the same, their cache index read as a list index)
+        lists = ctx.pack_shot_lists([s[0] for s in sels], [s[1] for s in sels])
+        for layer in (0, 1):
+            ctx.query_attn_pool_batched(layer, lists, packed)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for layer in range(w.n_layers):
+            ctx.query_attn_pool_batched(layer, lists, packed)
+        torch.cuda.synchronize()
+        dtz = time.perf_counter() - t0
+        out["llama8b_sweep_full_size"].update({
+            "zero_copy_sweep_all_layers_ms": dtz * 1e3, "zero_copy_tflops": flops * w.n_layers / dtz * 1e-12,
+            "assemble_plus_attention_ms": (best + dta) * 1e3, "zero_copy_over_two_pass": dtz / (best + dta)})
         # the same sweep with every (query, prefix) assembled from scratch into a cache of its own, as the
         # workload is worded: 1008 shots per query instead of 512
         del caches, items, packed

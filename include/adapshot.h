@@ -24,7 +24,7 @@
  *     split partials), so calls on ONE context must be issued in stream order on
  *     one stream at a time; use one context per concurrent stream.
  *   - Allocation and waiting.  adapshot_create allocates the RoPE tables (hipMalloc and two
- *     blocking copies).  adapshot_query_attn, adapshot_query_attn_pool, adapshot_query_attn_batched, adapshot_probe_entropy,
+ *     blocking copies).  adapshot_query_attn, adapshot_query_attn_pool, the batched attention calls, adapshot_probe_entropy,
  *     adapshot_probe_entropy_tokens and adapshot_rank_shots keep grow-only workspaces: a call that
  *     needs more than any earlier call on the context calls hipMalloc (an outgrown buffer is kept
  *     until adapshot_destroy, never freed in a call, so no call waits for the device); a call that
@@ -203,6 +203,22 @@ typedef struct {
 adapshot_status adapshot_query_attn_batched(adapshot_ctx* ctx, const adapshot_cache* caches, int32_t n_caches,
                                             int32_t layer, const adapshot_attn_item* items, int32_t n_items,
                                             void* hip_stream);
+
+/* Zero-copy form of adapshot_query_attn_batched: the items' contexts are prefixes of n_lists shot lists, read
+ * where the shots lie in the pool (no assembled cache; keys re-encoded inside the attention kernel by the
+ * composition property of Position Decoupling and Re-encoding, as in adapshot_query_attn_pool).  List l is
+ * shot_ids[l][orders[l][j]], j = 0..m[l]-1, its first token at position pos0 (shot_ids / orders / m: HOST arrays
+ * of n_lists entries; orders, or any orders[l], may be NULL).  An item's cache_index names its list and its
+ * n_ctx is a token count, at most the list's length: the probes of one query over nested prefixes of its ranked
+ * list (Probe-based Dynamic Evaluation) are items of one list, and no shot is copied for a prefix that the stopping
+ * rule then rejects.  Out[i] is what adapshot_query_attn_batched gives over caches assembled from the same lists
+ * (same kernels' arithmetic; parity bar of adapshot_query_attn).  Three launches: the plan of all lists, the
+ * attention grid over all items, the merge of the partials.  bf16 models with head_dim 128 and pools registered
+ * with ADAPSHOT_KEYS_UNROTATED only (ESTATE otherwise); a pool layer must stay below 4 GiB (ECAPACITY). */
+adapshot_status adapshot_query_attn_pool_batched(adapshot_ctx* ctx, int32_t layer, const int32_t* const* shot_ids,
+                                                 const int32_t* const* orders, const int32_t* m, int32_t n_lists,
+                                                 int64_t pos0, const adapshot_attn_item* items, int32_t n_items,
+                                                 void* hip_stream);
 
 /* Decode step (final answer generation after the shot count is chosen): append ONE new token to each
  * cache.  k_new, v_new: DEVICE [n_layers][n_caches][n_kv_heads][head_dim], keys WITHOUT rotation (as the

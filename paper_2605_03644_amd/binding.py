@@ -29,7 +29,7 @@ EXPORTS = ["adapshot_create", "adapshot_destroy", "adapshot_last_error", "adapsh
            "adapshot_profile_enable", "adapshot_profile_read", "adapshot_profile_read_each", "adapshot_assemble_batched",
            "adapshot_query_attn_batched", "adapshot_decode_append", "adapshot_probe_entropy_tokens",
            "adapshot_pick_shots", "adapshot_rank_shots", "adapshot_top_k", "adapshot_set_attn_splits",
-           "adapshot_probe_entropy_static", "adapshot_query_attn_pool"]
+           "adapshot_probe_entropy_static", "adapshot_query_attn_pool", "adapshot_query_attn_pool_batched"]
 ENTROPY_FULL_P, ENTROPY_RENORMALISED = 0, 1
 KERNEL_KINDS = ["assemble_reencode", "rope_rows", "query_attn", "attn_combine", "entropy_chunk", "entropy_finish"]
 
@@ -101,6 +101,8 @@ def load_library() -> ctypes.CDLL:
     L.adapshot_pick_shots.argtypes = [vp, vp, vp, i32, ctypes.c_float, vp]
     L.adapshot_assemble_batched.restype = ctypes.c_int
     L.adapshot_assemble_batched.argtypes = [vp, ctypes.POINTER(CacheStruct), i32, vp, vp, vp, i64, vp]
+    L.adapshot_query_attn_pool_batched.restype = ctypes.c_int
+    L.adapshot_query_attn_pool_batched.argtypes = [vp, i32, vp, vp, vp, i32, i64, ctypes.POINTER(AttnItem), i32, vp]
     L.adapshot_query_attn_batched.restype = ctypes.c_int
     L.adapshot_query_attn_batched.argtypes = [vp, ctypes.POINTER(CacheStruct), i32, i32, ctypes.POINTER(AttnItem), i32, vp]
     L.adapshot_decode_append.restype = ctypes.c_int
@@ -351,6 +353,30 @@ class Context:
         its = items if isinstance(items, ctypes.Array) else self.pack_attn_items(items)
         self._check(self.lib.adapshot_query_attn_batched(self._h, arr, len(caches), layer, its, len(its),
                                                          _stream_ptr(stream)))
+
+    # -- adapshot_query_attn_pool_batched (zero-copy form): an item's cache_index names a shot list
+    def pack_shot_lists(self, shot_ids, orders=None):
+        """The C arrays of n shot lists (and their orders); reusable across calls (one per layer)."""
+        n = len(shot_ids)
+        ids = [np.ascontiguousarray(x, dtype=np.int32) for x in shot_ids]
+        ods = None if orders is None else [None if o is None else np.ascontiguousarray(o, dtype=np.int32) for o in orders]
+        id_ptrs = (ctypes.c_void_p * n)(*[x.ctypes.data for x in ids])
+        od_ptrs = None if ods is None else (ctypes.c_void_p * n)(*[None if o is None else o.ctypes.data for o in ods])
+        m = np.array([x.shape[0] for x in ids], dtype=np.int32)
+        return (ids, ods, id_ptrs, od_ptrs, m)
+
+    def query_attn_pool_batched(self, layer: int, lists, items, pos0: int = 0,
+                                stream: Optional[torch.cuda.Stream] = None) -> None:
+        """lists: what pack_shot_lists returned, or (shot_ids, orders); items as in query_attn_batched with the list
+        index in place of the cache index."""
+        if len(lists) == 2:
+            lists = self.pack_shot_lists(lists[0], lists[1])
+        _, _, id_ptrs, od_ptrs, m = lists
+        its = items if isinstance(items, ctypes.Array) else self.pack_attn_items(items)
+        self._check(self.lib.adapshot_query_attn_pool_batched(
+            self._h, layer, ctypes.cast(id_ptrs, ctypes.c_void_p),
+            None if od_ptrs is None else ctypes.cast(od_ptrs, ctypes.c_void_p), m.ctypes.data, m.shape[0], pos0,
+            its, len(its), _stream_ptr(stream)))
 
     # -- adapshot_decode_append: k_new, v_new [L, n_caches, H_kv, d]
     def decode_append(self, caches, k_new: torch.Tensor, v_new: torch.Tensor, pos0: int = 0,

@@ -678,8 +678,18 @@ static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, c
 // by the caller.  The context is cut into splits of one common length, chosen so that the whole batch
 // makes about two rounds of workgroups over the chip (long splits keep the partial traffic low, two
 // rounds even out items of different length); the work list is ordered longest first.
+// With `pool` given the items' contexts are shot lists read where they lie in the pool (zero-copy form): an item's
+// cache_index names a list, and its context is the first n_ctx slots of that list's slot table.
+struct PoolBatch {
+    const char* k_layer;        // one layer of the pool
+    const char* v_layer;
+    const int32_t* slot_src;    // device: the lists' slot tables, one after the other
+    const int64_t* list_base;   // host: first entry of every list in slot_src
+    const float2* tile_rot;     // device: (cos, sin) of position pos0 + 64 i for every 64-slot tile, shared by the lists
+};
 static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_cache* caches, int32_t layer,
-                                            const adapshot_attn_item* items, int32_t n_items, hipStream_t stream) {
+                                            const adapshot_attn_item* items, int32_t n_items, hipStream_t stream,
+                                            const PoolBatch* pool = nullptr) {
     const adapshot_model_desc& d = ctx->desc;
     const int g = d.n_q_heads / d.n_kv_heads;
 
@@ -757,14 +767,21 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
     int64_t ic = 0;
     for (int32_t i = 0; i < n_items; ++i) {
         const adapshot_attn_item& it = items[i];
-        const adapshot_cache& c = caches[it.cache_index];
         const Plan& pl = plan[(size_t)i];
         AttnBatchItem& b = hit[i];
-        const int64_t layer_off = (int64_t)layer * c.capacity * ctx->row_bytes;
-        b.attn.k_cache = (const char*)c.k + layer_off;
-        b.attn.v_cache = (const char*)c.v + layer_off;
-        b.fold.slot_src = nullptr;
-        b.fold.tile_rot = nullptr;
+        if (pool) {
+            b.attn.k_cache = pool->k_layer;
+            b.attn.v_cache = pool->v_layer;
+            b.fold.slot_src = pool->slot_src + pool->list_base[it.cache_index];
+            b.fold.tile_rot = pool->tile_rot;
+        } else {
+            const adapshot_cache& c = caches[it.cache_index];
+            const int64_t layer_off = (int64_t)layer * c.capacity * ctx->row_bytes;
+            b.attn.k_cache = (const char*)c.k + layer_off;
+            b.attn.v_cache = (const char*)c.v + layer_off;
+            b.fold.slot_src = nullptr;
+            b.fold.tile_rot = nullptr;
+        }
         b.attn.q_rot = nullptr;
         b.attn.k_self_rot = nullptr;
         b.attn.v_self = it.v_self;
@@ -820,7 +837,7 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
     const AttnWork* daw = (const AttnWork*)((const char*)ctx->batch_tab.p + attn_off);
     const CombineWork* dcw = (const CombineWork*)((const char*)ctx->batch_tab.p + comb_off);
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream,
-                     [&] { return launch_attn_mfma_batched(dit, daw, (int)n_attn, stream); });
+                     [&] { return launch_attn_mfma_batched(dit, daw, (int)n_attn, pool != nullptr, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: attention launch", e);
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream,
                      [&] { return launch_attn_combine_batched(dit, dcw, (int)n_comb, d.dtype, stream); });
@@ -921,6 +938,130 @@ extern "C" adapshot_status adapshot_query_attn_pool(adapshot_ctx* ctx, int32_t l
     if (e != hipSuccess) return fail_hip(ctx, "query_attn_pool: event record", e);
     adapshot_status st = run_query_attn_on(ctx, k_layer, v_layer, total, q, k_self, v_self, t_q, q_pos0, out,
                                            (const int32_t*)ctx->pool_src.p, (const float2*)ctx->pool_rot.p, stream);
+    if (st == ADAPSHOT_OK) ctx->last_error.clear();
+    return st;
+}
+
+// Zero-copy form of the batched call: every item attends over a prefix of one of n_lists shot lists, read where
+// the shots lie in the pool.
+extern "C" adapshot_status adapshot_query_attn_pool_batched(adapshot_ctx* ctx, int32_t layer,
+                                                            const int32_t* const* shot_ids,
+                                                            const int32_t* const* orders, const int32_t* m,
+                                                            int32_t n_lists, int64_t pos0,
+                                                            const adapshot_attn_item* items, int32_t n_items,
+                                                            void* hip_stream) {
+    if (!ctx) return ADAPSHOT_EINVAL;
+    const adapshot_model_desc& d = ctx->desc;
+    if (!attn_mfma_supported(d))
+        return fail(ctx, ADAPSHOT_ESTATE, "query_attn_pool_batched: needs a bf16 model with head_dim 128 (matrix-core kernel)");
+    if (d.key_state != ADAPSHOT_KEYS_UNROTATED)
+        return fail(ctx, ADAPSHOT_ESTATE, "query_attn_pool_batched: needs a pool registered with ADAPSHOT_KEYS_UNROTATED");
+    if (!ctx->k_pool) return fail(ctx, ADAPSHOT_ESTATE, "query_attn_pool_batched: no pool registered");
+    if (n_items < 0 || n_lists < 0) return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool_batched: negative count");
+    if (n_lists > 0 && (!shot_ids || !m)) return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool_batched: null list arrays");
+    if (n_items > 0 && !items) return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool_batched: null items");
+    if (layer < 0 || layer >= d.n_layers) return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool_batched: layer out of range");
+    if (pos0 < 0) return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool_batched: negative position");
+    if ((uint64_t)ctx->shot_offsets[(size_t)ctx->n_shots] * (uint64_t)ctx->row_bytes > 0xffffffffull)
+        return fail(ctx, ADAPSHOT_ECAPACITY, "query_attn_pool_batched: a pool layer of 4 GiB or more is not supported");
+
+    // ---- the lists: lengths, and where each one's slot table starts
+    std::vector<int64_t> list_base((size_t)n_lists + 1, 0);
+    int64_t n_segs = 0, longest = 0;
+    for (int32_t l = 0; l < n_lists; ++l) {
+        if (m[l] < 0 || (m[l] > 0 && !shot_ids[l]))
+            return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool_batched: list %d: bad shot list", l);
+        const int32_t* order = orders ? orders[l] : nullptr;
+        int64_t total = 0;
+        for (int32_t j = 0; j < m[l]; ++j) {
+            const int32_t oj = order ? order[j] : j;
+            if (oj < 0 || oj >= m[l])
+                return fail(ctx, ADAPSHOT_ESHOT, "query_attn_pool_batched: list %d: order[%d] = %d out of range", l, j, oj);
+            const int32_t s = shot_ids[l][oj];
+            if (s < 0 || s >= ctx->n_shots)
+                return fail(ctx, ADAPSHOT_ESHOT, "query_attn_pool_batched: list %d: shot id %d out of range", l, s);
+            total += ctx->shot_offsets[s + 1] - ctx->shot_offsets[s];
+        }
+        if (pos0 + total > ctx->max_position)
+            return fail(ctx, ADAPSHOT_ECAPACITY, "query_attn_pool_batched: list %d: position %lld exceeds max_position %lld", l,
+                        (long long)(pos0 + total), (long long)ctx->max_position);
+        if ((uint64_t)total * (uint64_t)ctx->row_bytes > 0xffffffffull)
+            return fail(ctx, ADAPSHOT_ECAPACITY, "query_attn_pool_batched: list %d: context rows span more than 4 GiB", l);
+        list_base[(size_t)l + 1] = list_base[(size_t)l] + total;
+        n_segs += m[l];
+        longest = std::max(longest, total);
+    }
+    if (list_base[(size_t)n_lists] > INT32_MAX || n_segs > INT32_MAX)
+        return fail(ctx, ADAPSHOT_ECAPACITY, "query_attn_pool_batched: the lists hold more than 2^31 - 1 tokens");
+    // ---- the items, each against its list standing in for an assembled cache of the list's length
+    for (int32_t i = 0; i < n_items; ++i) {
+        const adapshot_attn_item& it = items[i];
+        if (it.cache_index < 0 || it.cache_index >= n_lists)
+            return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool_batched: item %d: list index out of range", i);
+        adapshot_cache as_cache{};
+        as_cache.k = const_cast<void*>(ctx->k_pool);
+        as_cache.v = const_cast<void*>(ctx->v_pool);
+        as_cache.len = as_cache.capacity = list_base[(size_t)it.cache_index + 1] - list_base[(size_t)it.cache_index];
+        adapshot_status st = check_query_attn(ctx, &as_cache, layer, it.n_ctx, it.q, it.k_self, it.v_self, it.t_q, it.q_pos0,
+                                              it.out);
+        if (st != ADAPSHOT_OK) {
+            ctx->last_error = "query_attn_pool_batched: item " + std::to_string(i) + ": " + ctx->last_error;
+            return st;
+        }
+    }
+    if (n_items == 0) {
+        ctx->last_error.clear();
+        return ADAPSHOT_OK;
+    }
+
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const int64_t layer_off = (int64_t)layer * ctx->pool_layer_stride_tokens * ctx->row_bytes;
+    PoolBatch pb;
+    pb.k_layer = (const char*)ctx->k_pool + layer_off;
+    pb.v_layer = (const char*)ctx->v_pool + layer_off;
+    pb.list_base = list_base.data();
+    pb.slot_src = nullptr;
+    pb.tile_rot = nullptr;
+    if (longest > 0) {
+        const int64_t n_tiles = (longest + 63) / 64;
+        hipError_t e = ctx->pool_src.reserve((size_t)list_base[(size_t)n_lists] * sizeof(int32_t), ctx->retired);
+        if (e == hipSuccess) e = ctx->pool_rot.reserve((size_t)n_tiles * (d.head_dim / 2) * sizeof(float2), ctx->retired);
+        if (e != hipSuccess) return fail_hip(ctx, "query_attn_pool_batched: workspace", e);
+        int slot = -1;
+        void* host = nullptr;
+        e = ctx->tile_ring.acquire((size_t)std::max<int64_t>(n_segs, 1) * sizeof(PoolSeg), &slot, &host);
+        if (e != hipSuccess) return fail_hip(ctx, "query_attn_pool_batched: pinned segments", e);
+        PoolSeg* segs = (PoolSeg*)host;
+        int32_t ns = 0;
+        for (int32_t l = 0; l < n_lists; ++l) {
+            const int32_t* order = orders ? orders[l] : nullptr;
+            int64_t slot0 = list_base[(size_t)l];
+            for (int32_t j = 0; j < m[l]; ++j) {
+                const int32_t s = shot_ids[l][order ? order[j] : j];
+                const int64_t src = ctx->shot_offsets[s], len = ctx->shot_offsets[s + 1] - src;
+                if (len > 0) segs[ns++] = PoolSeg{(int32_t)slot0, (int32_t)src, (int32_t)len, 0};
+                slot0 += len;
+            }
+        }
+        PoolPlanParams pp;
+        pp.segs = segs;
+        pp.slot_src = (int32_t*)ctx->pool_src.p;
+        pp.tile_rot = (float2*)ctx->pool_rot.p;
+        pp.tab_lo = ctx->tab_lo;
+        pp.tab_hi = ctx->tab_hi;
+        pp.pos0 = pos0;
+        pp.n_segs = ns;
+        pp.n_tiles = (int32_t)n_tiles;
+        pp.head_dim = d.head_dim;
+        e = timed_launch(ctx, ADAPSHOT_KERNEL_ROPE_ROWS, stream, [&] { return launch_pool_plan(pp, stream); });
+        if (e != hipSuccess) return fail_hip(ctx, "query_attn_pool_batched: plan launch", e);
+        e = ctx->tile_ring.mark_in_use(slot, stream);
+        if (e != hipSuccess) return fail_hip(ctx, "query_attn_pool_batched: event record", e);
+        pb.slot_src = (const int32_t*)ctx->pool_src.p;
+        pb.tile_rot = (const float2*)ctx->pool_rot.p;
+    }
+    // with nothing but empty lists every item has its own tokens only, and the kernel never looks at the tables
+    adapshot_status st = run_query_attn_batch(ctx, nullptr, layer, items, n_items, stream, &pb);
     if (st == ADAPSHOT_OK) ctx->last_error.clear();
     return st;
 }

@@ -186,7 +186,8 @@ struct CombineWork {  // one workgroup of the batched combine kernel: 16 (kv hea
 // Tables written by the host into pinned memory are brought to device memory by a kernel (a DMA copy
 // between two kernels of a stream costs more than the copy itself).  bytes is a multiple of 16.
 hipError_t launch_copy_table(void* dst, const void* src_pinned, size_t bytes, hipStream_t stream);
-hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, hipStream_t stream);
+hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, bool pool,
+                                    hipStream_t stream);
 hipError_t launch_attn_combine_batched(const AttnBatchItem* items, const CombineWork* work, int n_work, int dtype,
                                        hipStream_t stream);
 

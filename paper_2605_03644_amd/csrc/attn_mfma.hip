@@ -757,10 +757,15 @@ hipError_t launch_attn_mfma_pool(const AttnParams& p, const AttnFold& f, hipStre
     return hipGetLastError();
 }
 
-hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, hipStream_t stream) {
+hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, bool pool,
+                                    hipStream_t stream) {
     if (n_work <= 0) return hipSuccess;
-    launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), true, 4, false, true>), dim3((unsigned)n_work),
-                       dim3(kAttnWaves * 64), stream, AttnParams{}, AttnFold{}, 0, items, work);
+    if (pool)
+        launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), true, 4, true, true>), dim3((unsigned)n_work),
+                      dim3(kAttnWaves * 64), stream, AttnParams{}, AttnFold{}, 0, items, work);
+    else
+        launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), true, 4, false, true>), dim3((unsigned)n_work),
+                      dim3(kAttnWaves * 64), stream, AttnParams{}, AttnFold{}, 0, items, work);
     return hipGetLastError();
 }
 

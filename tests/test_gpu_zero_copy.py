@@ -118,3 +118,144 @@ def test_zero_copy_empty_context_and_errors(ad, oracle_mod):
         ctx.query_attn_pool(0, [1, 2], None, q, ks, vs, 0, out=out)
     assert e.value.status == ad.ESTATE
     ctx.close()
+
+
+# ---- adapshot_query_attn_pool_batched: prefixes of several shot lists in one call -------------------------------
+
+def _batched_case(ad, oracle_mod, w, lists, item_specs, pos0=0, layer=0, n_layers=1, n_pairs=None, splits=0, seed=0):
+    """lists: [(ids, order or None)]; item_specs: [(list index, n_ctx or None for the whole list, t_q)].  Every item
+    is checked against the oracle chain over its own list, and against the two-pass batched GPU path."""
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=n_layers)
+    ctx = ad.Context.for_workload(w, n_layers=n_layers)
+    ctx.pool_register(k_pool, v_pool, off)
+    totals = []
+    for ids, order in lists:
+        seq = [int(ids[o]) for o in order] if order is not None else [int(i) for i in ids]
+        totals.append(int(sum(off[s + 1] - off[s] for s in seq)))
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1234 + seed)
+    items = []
+    for li, n_ctx, t_q in item_specs:
+        n_ctx = totals[li] if n_ctx is None else n_ctx
+        q = torch.randn(t_q, w.n_q_heads, w.head_dim, device="cuda", generator=g).bfloat16()
+        ks = torch.randn(t_q, w.n_kv_heads, w.head_dim, device="cuda", generator=g).bfloat16()
+        vs = torch.randn(t_q, w.n_kv_heads, w.head_dim, device="cuda", generator=g).bfloat16()
+        items.append((li, n_ctx, q, ks, vs, pos0 + n_ctx, torch.full_like(q, 7.0)))
+    ctx.set_attn_splits(splits)
+    ctx.query_attn_pool_batched(layer, ([l[0] for l in lists], [l[1] for l in lists]), items, pos0=pos0)
+    torch.cuda.synchronize()
+    got = [it[6].float().cpu().numpy().copy() for it in items]
+    # the two-pass path: assemble every list, attend in one batched call
+    caches = [ad.Cache(ctx, max(t, 1), with_index=False) for t in totals]
+    ctx.assemble_batched(caches, [l[0] for l in lists], [l[1] for l in lists], pos0=pos0)
+    two_items = [(li, n, q, ks, vs, qp, torch.empty_like(q)) for (li, n, q, ks, vs, qp, _) in items]
+    ctx.query_attn_batched(caches, layer, two_items)
+    torch.cuda.synchronize()
+    kp, vp = H.to_storage(k_pool[layer:layer + 1]), H.to_storage(v_pool[layer:layer + 1])
+    oc = {}
+    rng = np.random.default_rng(77 + seed)
+    worst = 0.0
+    for i, (li, n_ctx, q, ks, vs, qp, _) in enumerate(items):
+        assert np.isfinite(got[i]).all()
+        two = two_items[i][6].float().cpu().numpy()
+        assert float(np.abs(got[i] - two).max()) <= 2.0 ** -6 * max(1.0, float(np.abs(two).max())), i
+        if li not in oc and totals[li] == 0:
+            oc[li] = (kp, vp, None)                        # an empty list: no slot is ever read
+        elif li not in oc:
+            pl = oracle_mod.plan(off, lists[li][0], lists[li][1], slot0=0, pos0=pos0)
+            oc[li] = oracle_mod.assemble(kp, vp, w.dtype, w.rope_theta, 0, pl, 0, totals[li])
+        ko, vo, _ = oc[li]
+        t_q = q.shape[0]
+        pairs = None
+        g_i = got[i]
+        if n_pairs is not None and t_q * w.n_q_heads > n_pairs:
+            flat = rng.choice(t_q * w.n_q_heads, n_pairs, replace=False)
+            pairs = np.stack([flat // w.n_q_heads, flat % w.n_q_heads], axis=1).astype(np.int32)
+            g_i = np.stack([got[i][j, h] for j, h in pairs])
+        ref = oracle_mod.query_attn(ko[0], vo[0], w.dtype, n_ctx, H.to_storage(q), H.to_storage(ks), H.to_storage(vs),
+                                    w.rope_theta, qp, pairs=pairs)
+        err, _ = H.check_attention(g_i, ref)
+        worst = max(worst, err)
+    ctx.close()
+    return worst
+
+
+def test_zero_copy_batched_nested_prefixes_and_ragged_items(ad, oracle_mod):
+    """Two lists (one with an order, one without, a shot picked twice); items over nested prefixes that end at shot
+    boundaries and in the middle of a shot, an empty prefix, single-token and ragged row counts."""
+    w = wl.WORKLOADS["llama8b_sweep"]
+    off = wl.shot_offsets(w)
+    ids0, order0 = wl.selection(w, query=0)
+    ids0, order0 = ids0[:24].copy(), np.argsort(np.argsort(order0[:24])).astype(np.int32)
+    ids0[3] = ids0[2]
+    ids1, _ = wl.selection(w, query=1)
+    ids1 = ids1[:9]
+    seq0 = [int(ids0[o]) for o in order0]
+    cum0 = np.cumsum([off[s + 1] - off[s] for s in seq0])
+    specs = [(0, int(cum0[3]), 64), (0, int(cum0[7]), 64), (0, int(cum0[15]), 64), (0, None, 64),
+             (0, int(cum0[5]) - 17, 5), (0, 0, 9), (1, None, 1), (1, 77, 33), (1, 64, 300)]
+    for splits in (0, 1, 3):
+        _batched_case(ad, oracle_mod, w, [(ids0, order0), (ids1, None)], specs, pos0=0 if splits else 129, splits=splits)
+
+
+def test_zero_copy_batched_other_shapes(ad, oracle_mod):
+    """g = 7 rows per kv head on layer 1 of two (decode-like single tokens), and g = 8 with an empty list beside a
+    full one."""
+    w = wl.WORKLOADS["qwen7b_decode"]
+    ids, _ = wl.selection(w)
+    _batched_case(ad, oracle_mod, w, [(ids[:20], None), (ids[20:50], None)], [(0, None, 1), (1, None, 1), (1, 100, 3)],
+                  layer=1, n_layers=2)
+    w = wl.WORKLOADS["llama70b_128k"]
+    ids, order = wl.selection(w)
+    _batched_case(ad, oracle_mod, w, [(ids[:0], None), (ids[:40], None)], [(0, 0, 16), (1, None, 40), (1, 1000, 40)],
+                  n_pairs=200)
+
+
+def test_zero_copy_batched_sweep_full_size_one_layer(ad, oracle_mod):
+    """Config 3 on one layer at its full batch: 8 queries with their own 512-shot orderings, six nested prefixes
+    each (16 .. 512 shots, up to ~53k tokens), 64 probe tokens per item; 25 sampled outputs per item (1200 in all)
+    against the oracle chain, every output against the two-pass batched path."""
+    w = wl.WORKLOADS["llama8b_sweep"]
+    off = wl.shot_offsets(w)
+    lists, specs = [], []
+    for qi in range(w.n_queries):
+        ids, order = wl.selection(w, query=qi)
+        lists.append((ids, order))
+        seq = [int(ids[o]) for o in order]
+        cum = np.cumsum([off[s + 1] - off[s] for s in seq])
+        for k in w.prefixes:
+            specs.append((qi, int(cum[k - 1]), w.t_q))
+    worst = _batched_case(ad, oracle_mod, w, lists, specs, n_pairs=25)
+    assert worst < 2e-2
+
+
+def test_zero_copy_batched_errors_write_nothing(ad):
+    w = wl.WORKLOADS["llama8b_1layer"]
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=1)
+    ctx = ad.Context.for_workload(w, n_layers=1)
+    q, ks, vs = wl.make_query(w, "cuda", t_q=9)
+    out = torch.full_like(q, 3.0)
+    lists = ([[1, 2, 3], [4]], None)
+    total0 = int(sum(off[s + 1] - off[s] for s in (1, 2, 3)))
+    good = (0, total0, q, ks, vs, total0, out)
+    with pytest.raises(ad.AdapshotError) as e:             # no pool yet
+        ctx.query_attn_pool_batched(0, lists, [good])
+    assert e.value.status == ad.ESTATE
+    ctx.pool_register(k_pool, v_pool, off)
+    cases = [(lists, [good, (2, 1, q, ks, vs, 1, out)], ad.EINVAL),                     # list index out of range
+             (lists, [good, (0, total0 + 1, q, ks, vs, 1, out)], ad.ESTATE),            # prefix longer than the list
+             (([[1, w.n_shots]], None), [(0, 1, q, ks, vs, 1, out)], ad.ESHOT),         # shot id out of range
+             (([[1, 2]], [[0, 2]]), [(0, 1, q, ks, vs, 1, out)], ad.ESHOT),             # order out of range
+             (lists, [good, (1, 1, q, ks, vs, -1, out)], ad.EINVAL)]                    # negative position
+    for ls, items, status in cases:
+        with pytest.raises(ad.AdapshotError) as e:
+            ctx.query_attn_pool_batched(0, ls, items)
+        assert e.value.status == status, e.value
+    with pytest.raises(ad.AdapshotError) as e:             # positions beyond the tables
+        ctx.query_attn_pool_batched(0, lists, [good], pos0=(1 << 20) - 10)
+    assert e.value.status == ad.ECAPACITY
+    torch.cuda.synchronize()
+    assert float(out.float().min()) == 3.0 and float(out.float().max()) == 3.0     # nothing was launched
+    ctx.query_attn_pool_batched(0, lists, [])              # no items: nothing to do
+    ctx.query_attn_pool_batched(0, ([], None), [])
+    ctx.close()
