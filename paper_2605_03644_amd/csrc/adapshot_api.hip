@@ -648,6 +648,7 @@ static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, c
     af.tab_hi = ctx->tab_hi;
     af.q_pos0 = q_pos0;
     af.q_scale = rp.q_scale;
+    af.pool_tokens = (int32_t)std::min<int64_t>(ctx->shot_offsets.empty() ? 0 : ctx->shot_offsets.back(), INT32_MAX);
     ap.part_o = ctx->part_o.p;
     ap.part_mlf = (float4*)ctx->part_ml.p;
     ap.part_half = mfma ? 1 : 0;
@@ -791,6 +792,7 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
         b.fold.tab_hi = ctx->tab_hi;
         b.fold.q_pos0 = it.q_pos0;
         b.fold.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
+        b.fold.pool_tokens = (int32_t)std::min<int64_t>(ctx->shot_offsets.empty() ? 0 : ctx->shot_offsets.back(), INT32_MAX);
         b.attn.part_o = (char*)ctx->part_o.p + pl.po_off;
         b.attn.part_mlf = (float4*)((char*)ctx->part_ml.p + pl.pml_off);
         b.attn.part_half = 1;
@@ -906,7 +908,7 @@ extern "C" adapshot_status adapshot_query_attn_pool(adapshot_ctx* ctx, int32_t l
     }
 
     const int64_t n_tiles = (total + 63) / 64;
-    hipError_t e = ctx->pool_src.reserve((size_t)total * sizeof(int32_t), ctx->retired);
+    hipError_t e = ctx->pool_src.reserve((size_t)(total + 256) * sizeof(int32_t), ctx->retired);  // the kernel reads it 1 KB at a time
     if (e == hipSuccess) e = ctx->pool_rot.reserve((size_t)n_tiles * (d.head_dim / 2) * sizeof(float2), ctx->retired);
     if (e != hipSuccess) return fail_hip(ctx, "query_attn_pool: workspace", e);
     int slot = -1;
@@ -966,7 +968,7 @@ extern "C" adapshot_status adapshot_query_attn_pool_batched(adapshot_ctx* ctx, i
         return fail(ctx, ADAPSHOT_ECAPACITY, "query_attn_pool_batched: a pool layer of 4 GiB or more is not supported");
 
     // ---- the lists: lengths, and where each one's slot table starts
-    std::vector<int64_t> list_base((size_t)n_lists + 1, 0);
+    std::vector<int64_t> list_base((size_t)n_lists + 1, 0), list_len((size_t)n_lists, 0);
     int64_t n_segs = 0, longest = 0;
     for (int32_t l = 0; l < n_lists; ++l) {
         if (m[l] < 0 || (m[l] > 0 && !shot_ids[l]))
@@ -987,7 +989,8 @@ extern "C" adapshot_status adapshot_query_attn_pool_batched(adapshot_ctx* ctx, i
                         (long long)(pos0 + total), (long long)ctx->max_position);
         if ((uint64_t)total * (uint64_t)ctx->row_bytes > 0xffffffffull)
             return fail(ctx, ADAPSHOT_ECAPACITY, "query_attn_pool_batched: list %d: context rows span more than 4 GiB", l);
-        list_base[(size_t)l + 1] = list_base[(size_t)l] + total;
+        list_len[(size_t)l] = total;
+        list_base[(size_t)l + 1] = (list_base[(size_t)l] + total + 63) & ~(int64_t)63;  // every list's table starts 16-byte aligned
         n_segs += m[l];
         longest = std::max(longest, total);
     }
@@ -1001,7 +1004,7 @@ extern "C" adapshot_status adapshot_query_attn_pool_batched(adapshot_ctx* ctx, i
         adapshot_cache as_cache{};
         as_cache.k = const_cast<void*>(ctx->k_pool);
         as_cache.v = const_cast<void*>(ctx->v_pool);
-        as_cache.len = as_cache.capacity = list_base[(size_t)it.cache_index + 1] - list_base[(size_t)it.cache_index];
+        as_cache.len = as_cache.capacity = list_len[(size_t)it.cache_index];
         adapshot_status st = check_query_attn(ctx, &as_cache, layer, it.n_ctx, it.q, it.k_self, it.v_self, it.t_q, it.q_pos0,
                                               it.out);
         if (st != ADAPSHOT_OK) {
@@ -1024,7 +1027,7 @@ extern "C" adapshot_status adapshot_query_attn_pool_batched(adapshot_ctx* ctx, i
     pb.tile_rot = nullptr;
     if (longest > 0) {
         const int64_t n_tiles = (longest + 63) / 64;
-        hipError_t e = ctx->pool_src.reserve((size_t)list_base[(size_t)n_lists] * sizeof(int32_t), ctx->retired);
+        hipError_t e = ctx->pool_src.reserve((size_t)(list_base[(size_t)n_lists] + 256) * sizeof(int32_t), ctx->retired);
         if (e == hipSuccess) e = ctx->pool_rot.reserve((size_t)n_tiles * (d.head_dim / 2) * sizeof(float2), ctx->retired);
         if (e != hipSuccess) return fail_hip(ctx, "query_attn_pool_batched: workspace", e);
         int slot = -1;

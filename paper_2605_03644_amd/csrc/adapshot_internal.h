@@ -115,9 +115,11 @@ struct AttnFold {
     const float2* tab_hi;
     int64_t q_pos0;
     float q_scale;
+    int32_t pool_tokens;  // zero-copy form: tokens in a pool layer (gathered rows are clamped to it)
     // Zero-copy form (template parameter POOL): k_cache / v_cache are the POOL's layer, context slot u holds pool
     // token slot_src[u], and its key is rotated to position pos0 + u inside the key loop;
-    // tile_rot[i][f] = (cos, sin)((pos0 + 64 i) theta_f) for every 64-slot tile of the context.
+    // tile_rot[i][f] = (cos, sin)((pos0 + 64 i) theta_f) for every 64-slot tile of the context.  slot_src is 16-byte
+    // aligned and readable for 256 entries past the context's last slot (the kernel fetches it 1 KB at a time).
     const int32_t* slot_src;
     const float2* tile_rot;
 };

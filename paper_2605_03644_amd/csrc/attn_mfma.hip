@@ -141,10 +141,15 @@ __device__ __forceinline__ T load_uniform(const T* ptr) {
 // POOL: the zero-copy form.  The context is not an assembled cache but the pool itself, read through the
 // table slot_src (context slot -> pool token): every 64-slot tile is gathered row by row into LDS, and its
 // keys are rotated there, in place, to the positions pos0 + slot before the first product reads them
-// (R(a)R(b) = R(a+b): tile_rot holds (cos, sin) of the tile's first position, the copy of the 64-row
-// second-level table in LDS adds the row's index inside the tile).  Two tiles in LDS per operand, two
-// workgroup barriers per tile (tile landed -> rotate -> rotated keys visible), every wavefront in the order
-// S, softmax, PV.  What a context split computes is what the plain form computes over the assembled cache.
+// (R(a)R(b) = R(a+b): tile_rot holds (cos, sin) of the tile's first position, every thread keeps the entries of
+// the 64-row second-level table that its share of a tile needs).  The key loop is the plain form's -- four K
+// tiles in LDS, one workgroup barrier per tile, the two wavefronts of a SIMD in rotated phase order -- with
+// three additions: K(t+1), which the pipeline has landed a tile early anyway, is rotated by all 512 threads
+// during tile t; the slot table entries and the rotation row of a tile arrive through the same direct-to-LDS
+// path as the tiles (one more load per tile for wavefronts 0 and 1, which changes their wait counts, nothing
+// else); and V keeps three tiles in LDS instead of four, which pays for the tables (V(t+1) has one tile of
+// time to land instead of two).  What a context split computes is what the plain form computes over the
+// assembled cache.
 // FOLD: the workgroup rotates its query rows (and the self split its keys) itself; otherwise rope_rows has
 // done that in a launch of its own and the kernel reads q_rot / k_self_rot.  Folding saves the launch and is
 // what the batched calls use (decode steps and probes have few rows per kv head); for one query with hundreds of
@@ -156,8 +161,18 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     constexpr int PASSES = (kTileKeys * 16) / (WAVES * 64);  // 1 KB blocks of a tile per wavefront
     static_assert(PASSES * WAVES * 64 == kTileKeys * 16, "tile must divide over the threads");
     static_assert(WAVES * NR * 32 == kAttnRowTile && NR == 1, "row tile");
-    __shared__ __attribute__((aligned(65536))) char k_s[kNBuf][kTileBytes];
-    __shared__ __attribute__((aligned(65536))) char v_s[kNBuf][kTileBytes];
+    // LDS: the K ring at byte 0, the V ring at 64 KB; the zero-copy form adds, after its shorter V ring, the ring of
+    // slot-table pieces (8 x 1 KB), the ring of rotation rows (4 x 1 KB) and the threads' second-level table entries.
+    constexpr int kVBuf = POOL ? 3 : kNBuf;
+    constexpr int kIdxSlots = 8, kRotSlots = 4;
+    constexpr int kLoBytes = WAVES * 64 * 64;
+    constexpr int kPoolBytes = POOL ? (kIdxSlots + kRotSlots) * 1024 + kLoBytes : 0;
+    __shared__ __attribute__((aligned(65536))) char lds_all[(kNBuf + kVBuf) * kTileBytes + kPoolBytes];
+    char (*const k_s)[kTileBytes] = (char (*)[kTileBytes])lds_all;
+    char (*const v_s)[kTileBytes] = (char (*)[kTileBytes])(lds_all + kNBuf * kTileBytes);
+    char* const idx_s = lds_all + (kNBuf + kVBuf) * kTileBytes;
+    char* const rot_s = idx_s + kIdxSlots * 1024;
+    char* const lo_s = rot_s + kRotSlots * 1024;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -221,6 +236,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
         k1 = k0 + p.keys_per_split < p.n_ctx ? k0 + p.keys_per_split : p.n_ctx;
     }
     const int n_tiles = (int)((k1 - k0 + kTileKeys - 1) / kTileKeys);  // >= 1
+    const int n_keys = (int)(k1 - k0);
 
     // ---- tile loads: wavefront w moves the 1 KB blocks (4 rows) w, w+WAVES, ...; lane = (row in block, chunk).
     // Every lane keeps the byte offset of its chunks inside a tile; the tile itself is addressed by a
@@ -280,86 +296,117 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     };
     // K(0) and V(0) of a context split start now; the other tiles of the pipeline follow once these have
     // landed.  (The split over the query's own tokens moves its tiles through registers, see below.)
-    // ---- zero-copy form: gathered tile loads.  LDS roles: k_s[0..1] and v_s[0..1] are the K and V rings, k_s[2]
-    // holds the two tiles' rotation rows (1 KB slots), v_s[2..3] the 32 KB second-level table.
-    char* const rot_s = k_s[2];
-    char* const lo_s = v_s[2];
+    // ---- zero-copy form: gathered tile loads
     AttnFold pf{};
     if (POOL) pf = fold();
-    unsigned pool_idx[PASSES];  // byte offsets of this lane's rows of the next tile to request
-    auto pool_index = [&](int t) __attribute__((always_inline)) {
+    // Byte offsets (inside the pool's layer) of this lane's rows of tile T, from the ring of slot-table pieces.
+    // The tiles past the end of the split stand for its last tile (their loads keep the number in flight the same
+    // and land where nobody reads any more); rows past the last key repeat it (the softmax masks them).
+    auto pool_rows = [&](int T, unsigned (&off)[PASSES]) __attribute__((always_inline)) {
+        const int Tc = T < n_tiles ? T : n_tiles - 1;
+        const char* piece = idx_s + (T & (kIdxSlots - 1)) * 1024;
+        const int last = n_keys - 1 - Tc * kTileKeys;
 #pragma unroll
         for (int ps = 0; ps < PASSES; ++ps) {
             const int r = 4 * (ps * WAVES + wave) + (lane >> 4);
-            int64_t key = k0 + (int64_t)t * kTileKeys + r;
-            key = key < k1 ? key : k1 - 1;  // rows past the end (masked by the softmax) repeat the last key
-            pool_idx[ps] = (unsigned)pf.slot_src[key] * (unsigned)kv_stride;  // the host keeps a pool layer below 4 GiB
+            unsigned tok = *(const unsigned*)(piece + (r < last ? r : last) * 4);
+            tok = tok < (unsigned)pf.pool_tokens ? tok : (unsigned)pf.pool_tokens - 1u;  // never outside the pool
+            off[ps] = tok * (unsigned)kv_stride;  // the host keeps a pool layer below 4 GiB
         }
     };
-    auto pool_issue = [&](int t, int buf) __attribute__((always_inline)) {
+    // the same offsets straight from the table in memory (prologue: tiles 0 and 1)
+    auto pool_rows_direct = [&](int T, unsigned (&off)[PASSES]) __attribute__((always_inline)) {
 #pragma unroll
         for (int ps = 0; ps < PASSES; ++ps) {
             const int r = 4 * (ps * WAVES + wave) + (lane >> 4);
-            load_lds_16(kbase, pool_idx[ps] + (((lane & 15) ^ (r & 15)) << 4),
-                        __builtin_amdgcn_readfirstlane(lds_addr(k_s[buf] + (ps * WAVES + wave) * 1024)));
-        }
-#pragma unroll
-        for (int ps = 0; ps < PASSES; ++ps) {
-            const int r = 4 * (ps * WAVES + wave) + (lane >> 4);
-            load_lds_16(vbase, pool_idx[ps] + (((lane & 15) ^ ((r & 3) << 2)) << 4),
-                        __builtin_amdgcn_readfirstlane(lds_addr(v_s[buf] + (ps * WAVES + wave) * 1024)));
-        }
-        if (wave == 0) {  // the tile's rotation row: 512 bytes (lanes 0-31); lanes 32-63 bring the next row along
-            const int64_t last = (p.n_ctx - 1) / kTileKeys;
-            int64_t gt = k0 / kTileKeys + t + (lane >> 5);
-            gt = gt < last ? gt : last;
-            load_lds_16((const char*)pf.tile_rot, (unsigned)(gt * 512 + (lane & 31) * 16),
-                        __builtin_amdgcn_readfirstlane(lds_addr(rot_s + buf * 1024)));
+            int64_t key = k0 + (int64_t)T * kTileKeys + r;
+            key = key < k1 ? key : k1 - 1;
+            unsigned tok = (unsigned)pf.slot_src[key];
+            tok = tok < (unsigned)pf.pool_tokens ? tok : (unsigned)pf.pool_tokens - 1u;
+            off[ps] = tok * (unsigned)kv_stride;
         }
     };
-    // rotate the keys of the tile in buffer `buf` in place: thread = (row r, chunk pair cp), the same
-    // pairing as the assemble kernel; position of row r = (tile's first position) + r
-    auto pool_rotate = [&](int buf) __attribute__((always_inline)) {
+    // lds_dst: LDS byte address of the destination tile (wave-uniform)
+    auto pool_gather_k = [&](const unsigned (&off)[PASSES], unsigned lds_dst) __attribute__((always_inline)) {
 #pragma unroll
-        for (int r = tid >> 3; r < kTileKeys; r += WAVES * 8) {
-            const int cp = tid & 7;
-            const f32x4* hi = (const f32x4*)(rot_s + buf * 1024 + cp * 64);
-            const f32x4* lo = (const f32x4*)(lo_s + r * 512 + cp * 64);
-            float c[8], sn[8];
-#pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                const f32x4 h = hi[e2], l = lo[e2];
-                c[2 * e2] = h[0] * l[0] - h[1] * l[1];
-                sn[2 * e2] = h[1] * l[0] + h[0] * l[1];
-                c[2 * e2 + 1] = h[2] * l[2] - h[3] * l[3];
-                sn[2 * e2 + 1] = h[3] * l[2] + h[2] * l[3];
-            }
-            u32x4* a1 = (u32x4*)(k_s[buf] + r * kRowBytes + ((cp ^ (r & 15)) << 4));
-            u32x4* a2 = (u32x4*)(k_s[buf] + r * kRowBytes + (((cp + 8) ^ (r & 15)) << 4));
-            u32x4 x1 = *a1, x2 = *a2;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const float a1l = __uint_as_float(x1[w] << 16), a1h = __uint_as_float(x1[w] & 0xffff0000u);
-                const float a2l = __uint_as_float(x2[w] << 16), a2h = __uint_as_float(x2[w] & 0xffff0000u);
-                x1[w] = pack2_bf16(a1l * c[2 * w] - a2l * sn[2 * w], a1h * c[2 * w + 1] - a2h * sn[2 * w + 1]);
-                x2[w] = pack2_bf16(a2l * c[2 * w] + a1l * sn[2 * w], a2h * c[2 * w + 1] + a1h * sn[2 * w + 1]);
-            }
-            *a1 = x1;
-            *a2 = x2;
+        for (int ps = 0; ps < PASSES; ++ps) {
+            const int r = 4 * (ps * WAVES + wave) + (lane >> 4);
+            load_lds_16(kbase, off[ps] + (((lane & 15) ^ (r & 15)) << 4),
+                        __builtin_amdgcn_readfirstlane(lds_dst + (ps * WAVES + wave) * 1024));
         }
+    };
+    auto pool_gather_v = [&](const unsigned (&off)[PASSES], unsigned lds_dst) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps) {
+            const int r = 4 * (ps * WAVES + wave) + (lane >> 4);
+            load_lds_16(vbase, off[ps] + (((lane & 15) ^ ((r & 3) << 2)) << 4),
+                        __builtin_amdgcn_readfirstlane(lds_dst + (ps * WAVES + wave) * 1024));
+        }
+    };
+    // one wavefront: 1 KB of the slot table starting at tile T's first slot (the tile's 64 entries and 192 more;
+    // the host pads the table by that much) into piece T % 8
+    auto issue_idx = [&](int T) __attribute__((always_inline)) {
+        const int Tc = T < n_tiles ? T : n_tiles - 1;
+        load_lds_16((const char*)(pf.slot_src + k0 + (int64_t)Tc * kTileKeys), (unsigned)lane * 16u,
+                    __builtin_amdgcn_readfirstlane(lds_addr(idx_s + (T & (kIdxSlots - 1)) * 1024)));
+    };
+    // one wavefront: the rotation row of tile T (512 bytes, lanes 0-31; lanes 32-63 bring the next row along)
+    // into slot T % 4
+    auto issue_rot = [&](int T) __attribute__((always_inline)) {
+        const int64_t last = (p.n_ctx - 1) / kTileKeys;
+        int64_t gt = k0 / kTileKeys + T + (lane >> 5);
+        gt = gt < last ? gt : last;
+        load_lds_16((const char*)pf.tile_rot, (unsigned)(gt * 512 + (lane & 31) * 16),
+                    __builtin_amdgcn_readfirstlane(lds_addr(rot_s + (T & (kRotSlots - 1)) * 1024)));
+    };
+    // rotate the keys of tile T, landed in K buffer `buf` (= T % 4), in place: thread = (row r, chunk pair cp), the
+    // same pairing as the assemble kernel; position of row r = (tile's first position) + r
+    auto pool_rotate = [&](int T, int buf) __attribute__((always_inline)) {
+        static_assert(!POOL || WAVES * 64 == kTileKeys * 8, "one (row, chunk pair) per thread");
+        if (T >= n_tiles) return;
+        __builtin_amdgcn_s_setprio(0);
+        const int r = tid >> 3, cp = tid & 7;
+        const f32x4* hi = (const f32x4*)(rot_s + buf * 1024 + cp * 64);
+        u32x4* a1 = (u32x4*)(k_s[buf] + r * kRowBytes + ((cp ^ (r & 15)) << 4));
+        u32x4* a2 = (u32x4*)(k_s[buf] + r * kRowBytes + (((cp + 8) ^ (r & 15)) << 4));
+        u32x4 x1 = *a1, x2 = *a2;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {  // word w holds elements 2w, 2w+1 of the chunk: frequencies 8 cp + 2w, + 2w + 1
+            const f32x4 h = hi[w], l = *(const f32x4*)(lo_s + w * (WAVES * 64 * 16) + tid * 16);
+            const float c0 = h[0] * l[0] - h[1] * l[1], s0 = h[1] * l[0] + h[0] * l[1];
+            const float c1 = h[2] * l[2] - h[3] * l[3], s1 = h[3] * l[2] + h[2] * l[3];
+            const float a1l = __uint_as_float(x1[w] << 16), a1h = __uint_as_float(x1[w] & 0xffff0000u);
+            const float a2l = __uint_as_float(x2[w] << 16), a2h = __uint_as_float(x2[w] & 0xffff0000u);
+            x1[w] = pack2_bf16(a1l * c0 - a2l * s0, a1h * c1 - a2h * s1);
+            x2[w] = pack2_bf16(a2l * c0 + a1l * s0, a2h * c1 + a1h * s1);
+        }
+        *a1 = x1;
+        *a2 = x2;
     };
     if (!self || !FOLD) {
         if (POOL) {
-            // the second-level table (32 KB), then tiles 0 and 1; the row indices of tile 2 stay in registers
+            // this thread's entries of the second-level table: (cos, sin)(r theta_f), f = 8 cp .. 8 cp + 7
+            const f32x4* tl = (const f32x4*)(pf.tab_lo + (tid >> 3) * (kD / 2) + 8 * (tid & 7));
 #pragma unroll
-            for (int blk = wave; blk < 32; blk += WAVES)
-                load_lds_16((const char*)pf.tab_lo, (unsigned)(blk * 1024 + lane * 16),
-                            __builtin_amdgcn_readfirstlane(lds_addr(lo_s + blk * 1024)));
-            pool_index(0);
-            pool_issue(0, 0);
-            pool_index(1);
-            pool_issue(1, 1);
-            pool_index(2);
+            for (int e2 = 0; e2 < 4; ++e2) *(f32x4*)(lo_s + e2 * (WAVES * 64 * 16) + tid * 16) = tl[e2];
+            // K(0), V(0), K(1); the slot-table pieces of tiles 1-4 and the rotation rows of tiles 0-2
+            unsigned off[PASSES];
+            pool_rows_direct(0, off);
+            pool_gather_k(off, lds_addr(k_s[0]));
+            pool_gather_v(off, lds_addr(v_s[0]));
+            pool_rows_direct(1, off);
+            pool_gather_k(off, lds_addr(k_s[1]));
+            if (wave == 0) {
+                issue_idx(1);
+                issue_idx(2);
+                issue_idx(3);
+                issue_idx(4);
+            }
+            if (wave == 1) {
+                issue_rot(0);
+                issue_rot(1);
+                issue_rot(2);
+            }
         } else {
             issue_k(0);
             issue_v(0);
@@ -454,8 +501,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
         const u32x4 w = *(const __attribute__((address_space(3))) u32x4*)(kp[kk] + buf * kTileBytes + kb * (32 * kRowBytes));
         return __builtin_bit_cast(bf16x8, w);
     };
-    auto v_frag = [&](int buf, int ks, int db) __attribute__((always_inline)) -> bf16x8 {
-        lds_char* a = vp[db] + buf * kTileBytes + ks * (16 * kRowBytes);
+    auto v_frag = [&](int buf, int ks, int db, unsigned voff) __attribute__((always_inline)) -> bf16x8 {
+        lds_char* a = vp[db] + voff + buf * kTileBytes + ks * (16 * kRowBytes);
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)a);
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a + 8 * kRowBytes));
         const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -477,37 +524,39 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     u32x4 pb[4];              // P^T of the current tile (packed bf16), one B operand per 16-key step
 
     // S^T(t) - m = K(t) . Q^T - m from K buffer `buf`: 16 MFMAs, fragments read kPD steps ahead
+    constexpr int kFD = POOL ? 2 : kPD;  // fragment reads in flight (the zero-copy form has fewer registers to spare)
     auto s_phase = [&](int buf) __attribute__((always_inline)) {
         __builtin_amdgcn_s_setprio(1);  // matrix-core phases win the issue arbitration over the other wave's softmax
-        bf16x8 fr[kPD];
+        bf16x8 fr[kFD];
 #pragma unroll
-        for (int i = 0; i < kPD; ++i) fr[i] = k_frag(buf, i & 1, i >> 1);
+        for (int i = 0; i < kFD; ++i) fr[i] = k_frag(buf, i & 1, i >> 1);
 #pragma unroll
         for (int i = 0; i < 16; ++i) {  // kk = i/2, kb = i%2
-            const bf16x8 a = fr[i % kPD];
-            if (i + kPD < 16) fr[i % kPD] = k_frag(buf, (i + kPD) & 1, (i + kPD) >> 1);
+            const bf16x8 a = fr[i % kFD];
+            if (i + kFD < 16) fr[i % kFD] = k_frag(buf, (i + kFD) & 1, (i + kFD) >> 1);
             if (i < 2) s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0], negm, 0, 0, 0);
             else s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[i >> 1], s[i & 1], 0, 0, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x100, kPD, 0);  // the first kPD fragment reads, then MFMA / read pairs
+        __builtin_amdgcn_sched_group_barrier(0x100, kFD, 0);  // the first kFD fragment reads, then MFMA / read pairs
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (i + kPD < 16) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (i + kFD < 16) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
     };
-    // O^T += V^T . P^T from V buffer `buf`: 4 * PVB MFMAs, 2 transposing reads per fragment
-    auto pv_phase = [&](int buf) __attribute__((always_inline)) {
+    // O^T += V^T . P^T from V buffer `buf` (plus voff bytes, the zero-copy form's run-time ring position):
+    // 4 * PVB MFMAs, 2 transposing reads per fragment
+    auto pv_phase = [&](int buf, unsigned voff = 0u) __attribute__((always_inline)) {
         constexpr int NPV = 4 * PVB;
-        constexpr int PD = kPD < NPV ? kPD : NPV;
+        constexpr int PD = kFD < NPV ? kFD : NPV;
         __builtin_amdgcn_s_setprio(1);
         bf16x8 fr[PD];
 #pragma unroll
-        for (int i = 0; i < PD; ++i) fr[i] = v_frag(buf, i / PVB, i % PVB);
+        for (int i = 0; i < PD; ++i) fr[i] = v_frag(buf, i / PVB, i % PVB, voff);
 #pragma unroll
         for (int i = 0; i < NPV; ++i) {  // ks = i / PVB, db = i % PVB
             const bf16x8 a = fr[i % PD];
-            if (i + PD < NPV) fr[i % PD] = v_frag(buf, (i + PD) / PVB, (i + PD) % PVB);
+            if (i + PD < NPV) fr[i % PD] = v_frag(buf, (i + PD) / PVB, (i + PD) % PVB, voff);
             o[i % PVB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, pb[i / PVB]), o[i % PVB], 0, 0, 0);
         }
         __builtin_amdgcn_sched_group_barrier(0x100, 2 * PD, 0);
@@ -520,7 +569,6 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     // masks + online softmax of tile t with a lazily updated reference maximum; leaves P^T(t) in pb
     // Key visibility in 32-bit arithmetic relative to k0: a key of this lane is visible while its index
     // 64*t + 32*kb + 8*(r/4) + (r%4) stays below lim (the 4*hh of the lane is folded into lim).
-    const int n_keys = (int)(k1 - k0);
     const int lim = (self ? (jrow[0] < n_keys ? jrow[0] + 1 : n_keys) : n_keys) - 4 * hh;
     auto softmax_phase = [&](int t) __attribute__((always_inline)) {
         __builtin_amdgcn_s_setprio(0);
@@ -627,28 +675,86 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
             __syncthreads();
         }
     } else if (POOL) {
-        // ---- zero-copy key loop.  Tiles 0 and 1 and the table have landed (wait and barrier above).
-        pool_rotate(0);
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        auto tile_z = [&](int t, int b) __attribute__((always_inline)) {
-            if (!wave_idle) {
+        // ---- zero-copy key loop.  K(0), K(1), V(0), the table pieces and rotation rows requested so far have
+        // landed (wait and barrier above).  K(0) is rotated now; the rest of the pipeline starts in the order the
+        // waits below assume: K(2), then the group V(1), K(3) and the extra load of wavefronts 0 and 1.
+        pool_rotate(0, 0);
+        {
+            unsigned off[PASSES];
+            pool_rows(2, off);
+            pool_gather_k(off, lds_addr(k_s[2]));
+            pool_rows(1, off);
+            pool_gather_v(off, lds_addr(v_s[1]));
+            pool_rows(3, off);
+            pool_gather_k(off, lds_addr(k_s[3]));
+            if (wave == 0) issue_idx(5);
+            if (wave == 1) issue_rot(3);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");  // the rotated K(0) is visible
+        // V ring positions (bytes from V buffer 0) of V(t) and V(t-1); the third buffer holds V(t+1)
+        unsigned vo_cur = 0u, vo_prev = 2u * kTileBytes;
+        // End of tile t (b = t % 4).  Every load but the last K tile's (and the extra one behind it) has landed:
+        // V(t+1), K(t+2) with its rotation row, the table pieces up to tile t+5.  The buffers of V(t-1) and K(t)
+        // are refilled with V(t+2) and K(t+4); piece (t+6) % 8 and rotation slot (t+4) % 4 were last read tiles ago.
+        auto end_of_tile_z = [&](int t, int b) __attribute__((always_inline)) {
+            if (wave < 2) asm volatile("s_waitcnt vmcnt(3) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(2) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            unsigned off[PASSES];
+            pool_rows(t + 2, off);
+            pool_gather_v(off, lds_addr(v_s[0]) + vo_prev);
+            pool_rows(t + 4, off);
+            pool_gather_k(off, lds_addr(k_s[b]));
+            if (wave == 0) issue_idx(t + 6);
+            if (wave == 1) issue_rot(t + 4);
+            const unsigned vo_next = 3u * kTileBytes - vo_cur - vo_prev;
+            vo_prev = vo_cur;
+            vo_cur = vo_next;
+        };
+        if (wave_idle) {
+            for (int t = 0; t < n_tiles; ++t) {
+                pool_rotate(t + 1, (t + 1) & 3);
+                end_of_tile_z(t, t & 3);
+            }
+        } else if (wave < WAVES / 2) {
+            // order A: S(t), softmax(t), PV(t), rotate K(t+1)
+            auto tile_a = [&](int t, int b) __attribute__((always_inline)) {
                 s_phase(b);
                 softmax_phase(t);
-                pv_phase(b);
+                pv_phase(0, vo_cur);
+                pool_rotate(t + 1, (b + 1) & 3);
+                end_of_tile_z(t, b);
+            };
+            int t = 0;
+            for (; t + 4 <= n_tiles; t += 4) {
+                tile_a(t, 0);
+                tile_a(t + 1, 1);
+                tile_a(t + 2, 2);
+                tile_a(t + 3, 3);
             }
-            // tile t+1, requested a tile ago, has landed for every wavefront; buffer b is free
-            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            pool_issue(t + 2, b);
-            pool_index(t + 3);
-            if (t + 1 < n_tiles) pool_rotate(b ^ 1);
-            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        };
-        int t = 0;
-        for (; t + 2 <= n_tiles; t += 2) {
-            tile_z(t, 0);
-            tile_z(t + 1, 1);
+            for (; t < n_tiles; ++t) tile_a(t, t & 3);
+        } else {
+            // order B: PV(t-1), rotate K(t+1), S(t), softmax(t)
+            auto tile_b = [&](int t, int b) __attribute__((always_inline)) {
+                pv_phase(0, vo_prev);
+                pool_rotate(t + 1, (b + 1) & 3);
+                s_phase(b);
+                softmax_phase(t);
+                end_of_tile_z(t, b);
+            };
+            pool_rotate(1, 1);
+            s_phase(0);
+            softmax_phase(0);
+            end_of_tile_z(0, 0);
+            int t = 1;
+            for (; t + 4 <= n_tiles; t += 4) {
+                tile_b(t, 1);
+                tile_b(t + 1, 2);
+                tile_b(t + 2, 3);
+                tile_b(t + 3, 0);
+            }
+            for (; t < n_tiles; ++t) tile_b(t, t & 3);
+            pv_phase(0, vo_prev);
         }
-        if (t < n_tiles) tile_z(t, 0);
     } else {
     issue_k(1);
     issue_v(1);
