@@ -30,9 +30,16 @@ namespace adapshot {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+constexpr int64_t kAssembleStreamBytes = 256ll << 20;  // launches that write more than this use non-temporal stores
+
 __device__ __forceinline__ u32x4 ld16(const char* p) { return __builtin_nontemporal_load((const u32x4*)p); }
-// plain stores: measured against non-temporal ones, which were ~10 % slower when attention reads the cache next
-__device__ __forceinline__ void st16(char* p, u32x4 v) { *(u32x4*)p = v; }
+// Plain stores when what the launch writes fits the 256 MB last-level cache (attention reads the cache next, and
+// non-temporal stores were ~10 % slower for the pair); non-temporal stores for the launches that stream past it.
+template <bool NT>
+__device__ __forceinline__ void st16(char* p, u32x4 v) {
+    if (NT) __builtin_nontemporal_store(v, (u32x4*)p);
+    else *(u32x4*)p = v;
+}
 
 __device__ __forceinline__ float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
@@ -72,7 +79,7 @@ __device__ __forceinline__ void rotate_chunks(u32x4& a, u32x4& b, const float2* 
 }
 
 // DTYPE: element type; CH: 16-byte chunks per half head (head_dim/2 * elem / 16).
-template <int DTYPE, int CH>
+template <int DTYPE, int CH, bool NT>
 __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p) {
     constexpr int E = DTYPE == ADAPSHOT_BF16 ? 2 : 4;
     constexpr int NP = 16 / E;            // pairs per chunk
@@ -106,7 +113,7 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
             char* dst = dc.v_out + (int64_t)l * dc.layer_stride_bytes + dst_off;
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                if (i0 + 256 * u < n16) st16(dst + ((int64_t)(i0 + 256 * u) << 4), r[u]);
+                if (i0 + 256 * u < n16) st16<NT>(dst + ((int64_t)(i0 + 256 * u) << 4), r[u]);
         };
         const int l = blockIdx.y;
         u32x4 cur[4];
@@ -162,8 +169,8 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
             const int f = base + u * 256 + tid;
             if (f < n_items) {
                 rotate_chunks<DTYPE>(st.a[u], st.b[u], cs + st.csi[u]);
-                st16(dst + st.off[u], st.a[u]);
-                st16(dst + st.off[u] + CH * 16, st.b[u]);
+                st16<NT>(dst + st.off[u], st.a[u]);
+                st16<NT>(dst + st.off[u] + CH * 16, st.b[u]);
             }
         }
     };
@@ -206,7 +213,13 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
 template <int DTYPE, int CH>
 static hipError_t launch_t(const AssembleParams& p, hipStream_t stream) {
     dim3 grid((unsigned)p.n_tiles * (unsigned)(kTileTok / p.wg_tok), (unsigned)p.n_layers, 2);
-    launch_kernel((assemble_reencode_kernel<DTYPE, CH>), grid, dim3(256), stream, p);
+    // upper bound of what the launch writes: every tile full, K and V
+    const int64_t e = DTYPE == ADAPSHOT_BF16 ? 2 : 4;
+    const int64_t written = 2 * (int64_t)p.n_tiles * kTileTok * p.n_kv_heads * p.head_dim * e * p.n_layers;
+    if (written > kAssembleStreamBytes)
+        launch_kernel((assemble_reencode_kernel<DTYPE, CH, true>), grid, dim3(256), stream, p);
+    else
+        launch_kernel((assemble_reencode_kernel<DTYPE, CH, false>), grid, dim3(256), stream, p);
     return hipGetLastError();
 }
 
@@ -272,10 +285,10 @@ __global__ __launch_bounds__(128) void decode_append_kernel(DecodeAppendParams p
             cs[w] = make_float2(hi.x * lo.x - hi.y * lo.y, hi.y * lo.x + hi.x * lo.y);
         }
         rotate_chunks<DTYPE>(x1, x2, cs);
-        st16(kdst + off, x1);
-        st16(kdst + off + CH * 16, x2);
-        st16(vdst + off, ld16(vsrc + off));
-        st16(vdst + off + CH * 16, ld16(vsrc + off + CH * 16));
+        st16<false>(kdst + off, x1);
+        st16<false>(kdst + off + CH * 16, x2);
+        st16<false>(vdst + off, ld16(vsrc + off));
+        st16<false>(vdst + off + CH * 16, ld16(vsrc + off + CH * 16));
     }
 }
 
