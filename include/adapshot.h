@@ -162,8 +162,9 @@ adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot_cache* cac
  * it for a context that is attended once; a context that is attended again (further layers' probes, every
  * decode step) is cheaper assembled once.  shot_ids, order: HOST int32[m] as in adapshot_assemble; q, k_self,
  * v_self, out, q_pos0 as in adapshot_query_attn.  Two launches besides the merge of the split partials: a small
- * one that expands the plan, and the attention.  bf16 models with head_dim 128 and pools registered with
- * ADAPSHOT_KEYS_UNROTATED only (ESTATE otherwise); a pool layer must stay below 4 GiB (ECAPACITY). */
+ * one that expands the plan, and the attention.  Pools registered with ADAPSHOT_KEYS_UNROTATED only (ESTATE
+ * otherwise).  bf16 models with head_dim 128 run the matrix-core kernel described above, for which a pool layer
+ * must stay below 4 GiB (ECAPACITY); other shapes run a plain kernel that gathers and rotates key by key. */
 adapshot_status adapshot_query_attn_pool(adapshot_ctx* ctx, int32_t layer, const int32_t* shot_ids,
                                          const int32_t* order, int32_t m, int64_t pos0, const void* q,
                                          const void* k_self, const void* v_self, int32_t t_q, int64_t q_pos0,
@@ -213,8 +214,9 @@ adapshot_status adapshot_query_attn_batched(adapshot_ctx* ctx, const adapshot_ca
  * list (Probe-based Dynamic Evaluation) are items of one list, and no shot is copied for a prefix that the stopping
  * rule then rejects.  Out[i] is what adapshot_query_attn_batched gives over caches assembled from the same lists
  * (same kernels' arithmetic; parity bar of adapshot_query_attn).  Three launches: the plan of all lists, the
- * attention grid over all items, the merge of the partials.  bf16 models with head_dim 128 and pools registered
- * with ADAPSHOT_KEYS_UNROTATED only (ESTATE otherwise); a pool layer must stay below 4 GiB (ECAPACITY). */
+ * attention grid over all items, the merge of the partials (bf16 models with head_dim 128, for which a pool layer
+ * must stay below 4 GiB, ECAPACITY; other shapes run item by item).  Pools registered with ADAPSHOT_KEYS_UNROTATED
+ * only (ESTATE otherwise). */
 adapshot_status adapshot_query_attn_pool_batched(adapshot_ctx* ctx, int32_t layer, const int32_t* const* shot_ids,
                                                  const int32_t* const* orders, const int32_t* m, int32_t n_lists,
                                                  int64_t pos0, const adapshot_attn_item* items, int32_t n_items,

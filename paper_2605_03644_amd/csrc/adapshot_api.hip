@@ -564,7 +564,7 @@ static int64_t plan_mfma_splits(int64_t n_cu, int64_t units, int64_t key_tiles, 
 static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, const void* v_ctx, int64_t n_ctx,
                                          const void* q, const void* k_self, const void* v_self, int32_t t_q,
                                          int64_t q_pos0, void* out, const int32_t* slot_src, const float2* tile_rot,
-                                         hipStream_t stream);
+                                         hipStream_t stream, int64_t ctx_pos0 = 0);
 
 static adapshot_status run_query_attn(adapshot_ctx* ctx, const adapshot_cache* cache, int32_t layer, int64_t n_ctx,
                                       const void* q, const void* k_self, const void* v_self, int32_t t_q,
@@ -577,7 +577,7 @@ static adapshot_status run_query_attn(adapshot_ctx* ctx, const adapshot_cache* c
 static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, const void* v_ctx, int64_t n_ctx,
                                          const void* q, const void* k_self, const void* v_self, int32_t t_q,
                                          int64_t q_pos0, void* out, const int32_t* slot_src, const float2* tile_rot,
-                                         hipStream_t stream) {
+                                         hipStream_t stream, int64_t ctx_pos0) {
     const adapshot_model_desc& d = ctx->desc;
     const int g = d.n_q_heads / d.n_kv_heads;
     const int64_t rows = (int64_t)t_q * g;
@@ -604,7 +604,7 @@ static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, c
 
     const size_t esz = (size_t)ctx->elem_bytes;
     hipError_t e = hipSuccess;
-    const bool fold = slot_src != nullptr;  // the zero-copy kernel rotates its rows itself
+    const bool fold = slot_src != nullptr && mfma;  // the matrix-core zero-copy kernel rotates its rows itself
     if (!fold) {
         e = ctx->q_rot.reserve((size_t)t_q * d.n_q_heads * d.head_dim * esz, ctx->retired);
         if (e == hipSuccess) e = ctx->k_rot.reserve((size_t)t_q * d.n_kv_heads * d.head_dim * esz, ctx->retired);
@@ -665,8 +665,8 @@ static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, c
     ap.head_dim = d.head_dim;
     ap.dtype = d.dtype;
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream, [&] {
-        if (slot_src) return launch_attn_mfma_pool(ap, af, stream);
-        return mfma ? launch_attn_mfma(ap, af, stream) : launch_attn_generic(ap, stream);
+        if (!mfma) return launch_attn_generic(ap, GenericPool{slot_src, ctx->tab_lo, ctx->tab_hi, ctx_pos0}, stream);
+        return slot_src ? launch_attn_mfma_pool(ap, af, stream) : launch_attn_mfma(ap, af, stream);
     });
     if (e != hipSuccess) return fail_hip(ctx, "query_attn: attention launch", e);
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream, [&] { return launch_attn_combine(ap, stream); });
@@ -866,8 +866,6 @@ extern "C" adapshot_status adapshot_query_attn_pool(adapshot_ctx* ctx, int32_t l
                                                     int64_t q_pos0, void* out, void* hip_stream) {
     if (!ctx) return ADAPSHOT_EINVAL;
     const adapshot_model_desc& d = ctx->desc;
-    if (!attn_mfma_supported(d))
-        return fail(ctx, ADAPSHOT_ESTATE, "query_attn_pool: needs a bf16 model with head_dim 128 (matrix-core kernel)");
     if (d.key_state != ADAPSHOT_KEYS_UNROTATED)
         return fail(ctx, ADAPSHOT_ESTATE, "query_attn_pool: needs a pool registered with ADAPSHOT_KEYS_UNROTATED");
     if (!ctx->k_pool) return fail(ctx, ADAPSHOT_ESTATE, "query_attn_pool: no pool registered");
@@ -892,9 +890,10 @@ extern "C" adapshot_status adapshot_query_attn_pool(adapshot_ctx* ctx, int32_t l
     if (pos0 + total > ctx->max_position)
         return fail(ctx, ADAPSHOT_ECAPACITY, "query_attn_pool: position %lld exceeds max_position %lld",
                     (long long)(pos0 + total), (long long)ctx->max_position);
-    // a lane addresses its key row by a 32-bit byte offset inside the pool's layer
-    if ((uint64_t)ctx->shot_offsets[(size_t)ctx->n_shots] * (uint64_t)ctx->row_bytes > 0xffffffffull ||
-        (uint64_t)std::max<int64_t>(total, t_q) * (uint64_t)ctx->row_bytes > 0xffffffffull)
+    // a lane of the matrix-core kernel addresses its key row by a 32-bit byte offset inside the pool's layer
+    if (attn_mfma_supported(d) &&
+        ((uint64_t)ctx->shot_offsets[(size_t)ctx->n_shots] * (uint64_t)ctx->row_bytes > 0xffffffffull ||
+         (uint64_t)std::max<int64_t>(total, t_q) * (uint64_t)ctx->row_bytes > 0xffffffffull))
         return fail(ctx, ADAPSHOT_ECAPACITY, "query_attn_pool: a pool layer of 4 GiB or more is not supported");
     hipStream_t stream = (hipStream_t)hip_stream;
     const int64_t layer_off = (int64_t)layer * ctx->pool_layer_stride_tokens * ctx->row_bytes;
@@ -939,7 +938,7 @@ extern "C" adapshot_status adapshot_query_attn_pool(adapshot_ctx* ctx, int32_t l
     e = ctx->tile_ring.mark_in_use(slot, stream);
     if (e != hipSuccess) return fail_hip(ctx, "query_attn_pool: event record", e);
     adapshot_status st = run_query_attn_on(ctx, k_layer, v_layer, total, q, k_self, v_self, t_q, q_pos0, out,
-                                           (const int32_t*)ctx->pool_src.p, (const float2*)ctx->pool_rot.p, stream);
+                                           (const int32_t*)ctx->pool_src.p, (const float2*)ctx->pool_rot.p, stream, pos0);
     if (st == ADAPSHOT_OK) ctx->last_error.clear();
     return st;
 }
@@ -954,8 +953,6 @@ extern "C" adapshot_status adapshot_query_attn_pool_batched(adapshot_ctx* ctx, i
                                                             void* hip_stream) {
     if (!ctx) return ADAPSHOT_EINVAL;
     const adapshot_model_desc& d = ctx->desc;
-    if (!attn_mfma_supported(d))
-        return fail(ctx, ADAPSHOT_ESTATE, "query_attn_pool_batched: needs a bf16 model with head_dim 128 (matrix-core kernel)");
     if (d.key_state != ADAPSHOT_KEYS_UNROTATED)
         return fail(ctx, ADAPSHOT_ESTATE, "query_attn_pool_batched: needs a pool registered with ADAPSHOT_KEYS_UNROTATED");
     if (!ctx->k_pool) return fail(ctx, ADAPSHOT_ESTATE, "query_attn_pool_batched: no pool registered");
@@ -964,7 +961,7 @@ extern "C" adapshot_status adapshot_query_attn_pool_batched(adapshot_ctx* ctx, i
     if (n_items > 0 && !items) return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool_batched: null items");
     if (layer < 0 || layer >= d.n_layers) return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool_batched: layer out of range");
     if (pos0 < 0) return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool_batched: negative position");
-    if ((uint64_t)ctx->shot_offsets[(size_t)ctx->n_shots] * (uint64_t)ctx->row_bytes > 0xffffffffull)
+    if (attn_mfma_supported(d) && (uint64_t)ctx->shot_offsets[(size_t)ctx->n_shots] * (uint64_t)ctx->row_bytes > 0xffffffffull)
         return fail(ctx, ADAPSHOT_ECAPACITY, "query_attn_pool_batched: a pool layer of 4 GiB or more is not supported");
 
     // ---- the lists: lengths, and where each one's slot table starts
@@ -1063,8 +1060,18 @@ extern "C" adapshot_status adapshot_query_attn_pool_batched(adapshot_ctx* ctx, i
         pb.slot_src = (const int32_t*)ctx->pool_src.p;
         pb.tile_rot = (const float2*)ctx->pool_rot.p;
     }
-    // with nothing but empty lists every item has its own tokens only, and the kernel never looks at the tables
-    adapshot_status st = run_query_attn_batch(ctx, nullptr, layer, items, n_items, stream, &pb);
+    adapshot_status st = ADAPSHOT_OK;
+    if (attn_mfma_supported(d)) {
+        // with nothing but empty lists every item has its own tokens only, and the kernel never looks at the tables
+        st = run_query_attn_batch(ctx, nullptr, layer, items, n_items, stream, &pb);
+    } else {  // other shapes run item by item through the generic kernel
+        for (int32_t i = 0; i < n_items && st == ADAPSHOT_OK; ++i) {
+            const adapshot_attn_item& it = items[i];
+            st = run_query_attn_on(ctx, pb.k_layer, pb.v_layer, it.n_ctx, it.q, it.k_self, it.v_self, it.t_q, it.q_pos0, it.out,
+                                   it.n_ctx > 0 ? pb.slot_src + list_base[(size_t)it.cache_index] : nullptr, pb.tile_rot, stream,
+                                   pos0);
+        }
+    }
     if (st == ADAPSHOT_OK) ctx->last_error.clear();
     return st;
 }

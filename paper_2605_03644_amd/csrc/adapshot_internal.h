@@ -151,7 +151,13 @@ struct AttnParams {
     int32_t t_q, n_q_heads, n_kv_heads, head_dim, dtype;
 };
 constexpr int kAttnRowTile = 256;  // query rows per workgroup of the MFMA kernel
-hipError_t launch_attn_generic(const AttnParams& p, hipStream_t stream);
+struct GenericPool {  // zero-copy form of the generic kernel; slot_src == nullptr: the context is an assembled cache
+    const int32_t* slot_src;
+    const float2* tab_lo;
+    const float2* tab_hi;
+    int64_t pos0;  // position of context slot 0
+};
+hipError_t launch_attn_generic(const AttnParams& p, const GenericPool& pool, hipStream_t stream);
 hipError_t launch_attn_mfma(const AttnParams& p, const AttnFold& f, hipStream_t stream);
 hipError_t launch_attn_mfma_pool(const AttnParams& p, const AttnFold& f, hipStream_t stream);  // zero-copy form
 // Expands the per-shot segments of a zero-copy context into slot_src and builds tile_rot.

@@ -170,10 +170,14 @@ __device__ __forceinline__ float wave_sum(float v) {
 // grid = (t_q * h_q, n_split + 1); one wavefront each.  Lanes run over 64 keys for the
 // scores and over the head dimension for p.v.  Works in log2 units: q is pre-scaled by
 // log2(e)/sqrt(d), so p = 2^(s - m).
+// With pool.slot_src given (zero-copy form) the context is one layer of the POOL: slot u holds pool token
+// slot_src[u], and its key is rotated to position pos0 + u on the way into the score (Eq. rope_compensation;
+// rounded to the storage type, as the assembled cache would hold it).
 template <int DTYPE>
-__global__ __launch_bounds__(64) void attn_generic_kernel(AttnParams p) {
+__global__ __launch_bounds__(64) void attn_generic_kernel(AttnParams p, GenericPool pool) {
     __shared__ float q_s[256];
     __shared__ float p_s[64];
+    __shared__ int tok_s[64];
     const int lane = threadIdx.x;
     const int d = p.head_dim;
     const int g = p.n_q_heads / p.n_kv_heads;
@@ -197,11 +201,32 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(AttnParams p) {
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     for (int64_t kb = k0; kb < k1; kb += 64) {
         const int64_t u = kb + lane;
+        const bool gather = pool.slot_src && !self;
         float s = -INFINITY;
         if (u < k1) {
-            const int64_t o = (u * p.n_kv_heads + hk) * d;
+            const int64_t tok = gather ? (int64_t)pool.slot_src[u] : u;
+            tok_s[lane] = (int)tok;
+            const int64_t o = (tok * p.n_kv_heads + hk) * d;
             float dot = 0.f;
-            for (int e = 0; e < d; ++e) dot += q_s[e] * load_elem<DTYPE>(kbase, o + e);
+            if (gather) {
+                const int half = d >> 1;
+                const int64_t a = pool.pos0 + u;
+                const float2* th = pool.tab_hi + (a >> kRopeLoBits) * half;
+                const float2* tl = pool.tab_lo + (a & (kRopeLo - 1)) * half;
+                for (int i = 0; i < half; ++i) {
+                    const float2 hh = th[i], ll = tl[i];
+                    const float c = hh.x * ll.x - hh.y * ll.y, sn = hh.y * ll.x + hh.x * ll.y;
+                    const float x1 = load_elem<DTYPE>(kbase, o + i), x2 = load_elem<DTYPE>(kbase, o + i + half);
+                    float y1 = x1 * c - x2 * sn, y2 = x2 * c + x1 * sn;
+                    if (DTYPE == ADAPSHOT_BF16) {
+                        y1 = __uint_as_float((unsigned)f32_to_bf16_rne(y1) << 16);
+                        y2 = __uint_as_float((unsigned)f32_to_bf16_rne(y2) << 16);
+                    }
+                    dot += q_s[i] * y1 + q_s[i + half] * y2;
+                }
+            } else {
+                for (int e = 0; e < d; ++e) dot += q_s[e] * load_elem<DTYPE>(kbase, o + e);
+            }
             s = dot;
         }
         const float m_new = fmaxf(m, wave_max(s));
@@ -218,7 +243,7 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(AttnParams p) {
             if (e < d) {
                 float a = acc[c] * alpha;
                 for (int t = 0; t < nk; ++t)
-                    a += p_s[t] * load_elem<DTYPE>(vbase, ((kb + t) * p.n_kv_heads + hk) * d + e);
+                    a += p_s[t] * load_elem<DTYPE>(vbase, ((int64_t)(gather ? tok_s[t] : kb + t) * p.n_kv_heads + hk) * d + e);
                 acc[c] = a;
             }
         }
@@ -233,12 +258,12 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(AttnParams p) {
     }
 }
 
-hipError_t launch_attn_generic(const AttnParams& p, hipStream_t stream) {
+hipError_t launch_attn_generic(const AttnParams& p, const GenericPool& pool, hipStream_t stream) {
     dim3 grid((unsigned)(p.t_q * p.n_q_heads), (unsigned)(p.n_split + 1));
     if (p.dtype == ADAPSHOT_BF16)
-        launch_kernel(attn_generic_kernel<ADAPSHOT_BF16>, grid, dim3(64), stream, p);
+        launch_kernel(attn_generic_kernel<ADAPSHOT_BF16>, grid, dim3(64), stream, p, pool);
     else
-        launch_kernel(attn_generic_kernel<ADAPSHOT_F32>, grid, dim3(64), stream, p);
+        launch_kernel(attn_generic_kernel<ADAPSHOT_F32>, grid, dim3(64), stream, p, pool);
     return hipGetLastError();
 }
 
