@@ -280,7 +280,9 @@ adapshot_status adapshot_probe_entropy_tokens(adapshot_ctx* ctx, const float* lo
  * adapshot_pool_register again before ranking.  The query is encoded on its own: token j at position
  * q_pos0 + j.  The reduction order is fixed: the same inputs give bit-identical scores.
  * q: DEVICE [t_q][n_q_heads][head_dim] without rotation; scores_out: DEVICE fp32 [n_shots].
- * bf16 models with head_dim 128 only (ESTATE otherwise); every shot must hold at least one token. */
+ * Every shot must hold at least one token.  bf16 models with head_dim 128 run the matrix-core attention kernel
+ * over the pool (a pool layer must stay below 4 GiB, ECAPACITY); other shapes run a plain kernel (one wavefront
+ * per query token and head over the whole layer: for small models and checks, not tuned), head_dim <= 1024. */
 adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer, const void* q, int32_t t_q, int64_t q_pos0,
                                     float* scores_out, void* hip_stream);
 

@@ -1323,14 +1323,72 @@ static adapshot_status rank_prepare(adapshot_ctx* ctx, int32_t layer, hipStream_
     return ADAPSHOT_OK;
 }
 
+// Ranking for the shapes the matrix-core kernel does not cover (arguments validated by the caller).
+static adapshot_status rank_shots_generic(adapshot_ctx* ctx, int32_t layer, const void* q, int32_t t_q, int64_t q_pos0,
+                                          float* scores_out, hipStream_t stream) {
+    const adapshot_model_desc& d = ctx->desc;
+    if (d.head_dim > 1024) return fail(ctx, ADAPSHOT_ESTATE, "rank_shots: head_dim above 1024 is not supported");
+    const size_t off_bytes = ((size_t)(ctx->n_shots + 1) * sizeof(int64_t) + 15) & ~(size_t)15;
+    const size_t rows = (size_t)t_q * d.n_q_heads;
+    hipError_t e = ctx->q_rot.reserve(rows * d.head_dim * (size_t)ctx->elem_bytes, ctx->retired);
+    if (e == hipSuccess) e = ctx->rank_tab.reserve(off_bytes, ctx->retired);
+    if (e == hipSuccess) e = ctx->rank_w.reserve(rows * (size_t)ctx->n_shots * sizeof(float), ctx->retired);
+    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: workspace", e);
+    ctx->rank_layer = -1;  // the table buffer is shared with the matrix-core path's prepared state
+    int slot = -1;
+    void* host = nullptr;
+    e = ctx->tile_ring.acquire(off_bytes, &slot, &host);
+    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: pinned tables", e);
+    memcpy(host, ctx->shot_offsets.data(), (size_t)(ctx->n_shots + 1) * sizeof(int64_t));
+    e = launch_copy_table(ctx->rank_tab.p, host, off_bytes, stream);
+    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: table copy", e);
+    e = ctx->tile_ring.mark_in_use(slot, stream);
+    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: event record", e);
+
+    RopeRowsParams rp;
+    rp.q = q;
+    rp.k_self = nullptr;
+    rp.q_rot = ctx->q_rot.p;
+    rp.k_rot = nullptr;
+    rp.tab_lo = ctx->tab_lo;
+    rp.tab_hi = ctx->tab_hi;
+    rp.q_pos0 = q_pos0;
+    rp.t_q = t_q;
+    rp.n_q_heads = d.n_q_heads;
+    rp.n_kv_heads = d.n_kv_heads;
+    rp.head_dim = d.head_dim;
+    rp.dtype = d.dtype;
+    rp.q_scale = (float)(1.4426950408889634 / sqrt((double)d.head_dim));
+    e = timed_launch(ctx, ADAPSHOT_KERNEL_ROPE_ROWS, stream, [&] { return launch_rope_rows(rp, stream); });
+    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: rope launch", e);
+
+    RankGenericParams gp;
+    gp.k_pool = (const char*)ctx->k_pool + (int64_t)layer * ctx->pool_layer_stride_tokens * ctx->row_bytes;
+    gp.q_rot = ctx->q_rot.p;
+    gp.shot_off = (const int64_t*)ctx->rank_tab.p;
+    gp.tab_lo = ctx->tab_lo;
+    gp.tab_hi = ctx->tab_hi;
+    gp.mass = (float*)ctx->rank_w.p;
+    gp.scores = scores_out;
+    gp.n_shots = ctx->n_shots;
+    gp.t_q = t_q;
+    gp.n_q_heads = d.n_q_heads;
+    gp.n_kv_heads = d.n_kv_heads;
+    gp.head_dim = d.head_dim;
+    gp.dtype = d.dtype;
+    gp.key_state = d.key_state;
+    e = launch_rank_generic(gp, stream);
+    if (e != hipSuccess) return fail_hip(ctx, "rank_shots: launch", e);
+    ctx->last_error.clear();
+    return ADAPSHOT_OK;
+}
+
 extern "C" adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer, const void* q, int32_t t_q,
                                                int64_t q_pos0, float* scores_out, void* hip_stream) {
     if (!ctx) return ADAPSHOT_EINVAL;
     const adapshot_model_desc& d = ctx->desc;
     hipStream_t stream = (hipStream_t)hip_stream;
     if (!ctx->k_pool) return fail(ctx, ADAPSHOT_ESTATE, "rank_shots: no pool registered");
-    if (!attn_mfma_supported(d))
-        return fail(ctx, ADAPSHOT_ESTATE, "rank_shots: needs a bf16 model with head_dim 128 (matrix-core kernel)");
     if (layer < 0 || layer >= d.n_layers) return fail(ctx, ADAPSHOT_EINVAL, "rank_shots: layer out of range");
     if (!q || !scores_out) return fail(ctx, ADAPSHOT_EINVAL, "rank_shots: null pointer");
     if (!aligned16(q) || ((uintptr_t)scores_out & 3u)) return fail(ctx, ADAPSHOT_EINVAL, "rank_shots: q must be 16-byte aligned");
@@ -1345,6 +1403,7 @@ extern "C" adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer,
         if (len < 1) return fail(ctx, ADAPSHOT_ESTATE, "rank_shots: shot %d is empty", i);
         if (len > ctx->max_position) return fail(ctx, ADAPSHOT_ECAPACITY, "rank_shots: shot %d longer than max_position", i);
     }
+    if (!attn_mfma_supported(d)) return rank_shots_generic(ctx, layer, q, t_q, q_pos0, scores_out, stream);
     if (n_tok * ctx->row_bytes >= ((int64_t)1 << 32))
         return fail(ctx, ADAPSHOT_ECAPACITY, "rank_shots: a pool layer of 4 GiB or more is not supported");
     if (ctx->rank_layer != layer) {

@@ -232,6 +232,20 @@ hipError_t launch_rank_weights(const RankReduceParams& p, hipStream_t stream);  
 hipError_t launch_rank_reduce(const RankReduceParams& p, hipStream_t stream);   // weighted sum over blocks of rows
 hipError_t launch_rank_finish(const RankReduceParams& p, hipStream_t stream);   // row blocks added in a fixed order
 
+// Ranking for the shapes the matrix-core kernel does not cover: one wavefront per (query token, head) walks the
+// whole pool layer twice (normaliser, then the mass of every shot), a second kernel adds the rows in a fixed order.
+struct RankGenericParams {
+    const void* k_pool;       // one layer [tokens][h_kv][d]
+    const void* q_rot;        // [t_q][h_q][d] rotated to q_pos0 + j, scaled by log2(e)/sqrt(d)
+    const int64_t* shot_off;  // DEVICE [n_shots + 1]
+    const float2* tab_lo;
+    const float2* tab_hi;
+    float* mass;              // [t_q * h_q][n_shots] scratch: attention received by every shot from one row
+    float* scores;            // [n_shots]
+    int32_t n_shots, t_q, n_q_heads, n_kv_heads, head_dim, dtype, key_state;
+};
+hipError_t launch_rank_generic(const RankGenericParams& p, hipStream_t stream);
+
 // ---- entropy ------------------------------------------------------------------------
 struct EntropyParams {
     const float* logits;

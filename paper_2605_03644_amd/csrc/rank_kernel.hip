@@ -167,4 +167,104 @@ hipError_t launch_rank_finish(const RankReduceParams& p, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// ---- shapes the matrix-core kernel does not cover ------------------------------------------------------
+template <int DTYPE>
+__device__ __forceinline__ float rank_load(const void* base, int64_t i) {
+    if (DTYPE == ADAPSHOT_BF16) return __uint_as_float(((unsigned)((const unsigned short*)base)[i]) << 16);
+    return ((const float*)base)[i];
+}
+__device__ __forceinline__ float rank_wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float rank_wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// One wavefront per (query token j, head h).  score(u) = q~ . k~_u in log2 units, k~_u = the key of pool token u
+// as a cache holds it: encoded at its position inside its shot and rounded to the storage type (a pool that
+// stores un-rotated keys), or as stored.  Pass 1: the row's maximum and sum over the whole pool; pass 2: the
+// normalised mass of every shot.
+template <int DTYPE>
+__global__ __launch_bounds__(64) void rank_generic_kernel(RankGenericParams p) {
+    __shared__ float q_s[1024];
+    const int lane = threadIdx.x;
+    const int d = p.head_dim, half = d >> 1;
+    const int g = p.n_q_heads / p.n_kv_heads;
+    const int r = blockIdx.x;  // j * h_q + h
+    const int h = r % p.n_q_heads;
+    const int hk = h / g;
+    for (int e = lane; e < d; e += 64) q_s[e] = rank_load<DTYPE>(p.q_rot, (int64_t)r * d + e);
+    __syncthreads();
+    auto score = [&](int64_t u, int64_t t_local) -> float {
+        const int64_t o = (u * p.n_kv_heads + hk) * d;
+        float dot = 0.f;
+        if (p.key_state == ADAPSHOT_KEYS_UNROTATED) {
+            const float2* th = p.tab_hi + (t_local >> kRopeLoBits) * half;
+            const float2* tl = p.tab_lo + (t_local & (kRopeLo - 1)) * half;
+            for (int i = 0; i < half; ++i) {
+                const float2 hh = th[i], ll = tl[i];
+                const float c = hh.x * ll.x - hh.y * ll.y, sn = hh.y * ll.x + hh.x * ll.y;
+                const float x1 = rank_load<DTYPE>(p.k_pool, o + i), x2 = rank_load<DTYPE>(p.k_pool, o + i + half);
+                float y1 = x1 * c - x2 * sn, y2 = x2 * c + x1 * sn;
+                if (DTYPE == ADAPSHOT_BF16) {
+                    y1 = __uint_as_float((unsigned)__builtin_bit_cast(unsigned short, (__bf16)y1) << 16);
+                    y2 = __uint_as_float((unsigned)__builtin_bit_cast(unsigned short, (__bf16)y2) << 16);
+                }
+                dot += q_s[i] * y1 + q_s[i + half] * y2;
+            }
+        } else {
+            for (int e = 0; e < d; ++e) dot += q_s[e] * rank_load<DTYPE>(p.k_pool, o + e);
+        }
+        return dot;
+    };
+    float m = -INFINITY, l = 0.f;  // per lane; merged below
+    for (int i = 0; i < p.n_shots; ++i) {
+        const int64_t t0 = p.shot_off[i], t1 = p.shot_off[i + 1];
+        for (int64_t u = t0 + lane; u < t1; u += 64) {
+            const float s = score(u, u - t0);
+            const float mn = fmaxf(m, s);
+            l = l * exp2f(m - mn) + exp2f(s - mn);
+            m = mn;
+        }
+    }
+    const float M = rank_wave_max(m);
+    const float L = rank_wave_sum(m == -INFINITY ? 0.f : l * exp2f(m - M));
+    const float inv_l = 1.0f / L;
+    for (int i = 0; i < p.n_shots; ++i) {
+        const int64_t t0 = p.shot_off[i], t1 = p.shot_off[i + 1];
+        float a = 0.f;
+        for (int64_t u = t0 + lane; u < t1; u += 64) a += exp2f(score(u, u - t0) - M);
+        a = rank_wave_sum(a);
+        if (lane == 0) p.mass[(int64_t)r * p.n_shots + i] = a * inv_l;
+    }
+}
+
+// One thread per shot: the rows' masses added in row order, scaled by 1 / (T_q H_q T_i).
+__global__ __launch_bounds__(256) void rank_generic_finish_kernel(RankGenericParams p) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= p.n_shots) return;
+    const int n_rows = p.t_q * p.n_q_heads;
+    float a = 0.f;
+    for (int r = 0; r < n_rows; ++r) a += p.mass[(int64_t)r * p.n_shots + i];
+    const float len = (float)(p.shot_off[i + 1] - p.shot_off[i]);
+    p.scores[i] = a / ((float)n_rows * len);
+}
+
+hipError_t launch_rank_generic(const RankGenericParams& p, hipStream_t stream) {
+    if (p.head_dim > 1024) return hipErrorInvalidValue;
+    const unsigned rows = (unsigned)(p.t_q * p.n_q_heads);
+    if (p.dtype == ADAPSHOT_BF16)
+        launch_kernel(rank_generic_kernel<ADAPSHOT_BF16>, dim3(rows), dim3(64), stream, p);
+    else
+        launch_kernel(rank_generic_kernel<ADAPSHOT_F32>, dim3(rows), dim3(64), stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    launch_kernel(rank_generic_finish_kernel, dim3((unsigned)((p.n_shots + 255) / 256)), dim3(256), stream, p);
+    return hipGetLastError();
+}
+
 }  // namespace adapshot

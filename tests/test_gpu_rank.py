@@ -110,3 +110,38 @@ def test_rank_full_pool_mass_and_time(ad):
     s2 = ctx.rank_shots(0, q).cpu().numpy().astype(np.float64)
     assert float(np.abs(s2 - s).max()) <= 1e-3 * s.max()
     ctx.close()
+
+
+@pytest.mark.parametrize("key_state", [0, 1])
+@pytest.mark.parametrize("dtype,head_dim,h_q,h_kv", [("f32", 64, 4, 2), ("bf16", 64, 6, 2), ("f32", 128, 8, 8)])
+def test_rank_scores_other_shapes(ad, oracle_mod, key_state, dtype, head_dim, h_q, h_kv):
+    """Shapes the matrix-core kernel does not cover (fp32 models, head_dim 64) go through the plain kernels:
+    every score against the oracle, the mass invariant, the same bits on a second call."""
+    rng = np.random.default_rng(31 + head_dim + h_q)
+    n_shots, t_q = 23, 7
+    lens = rng.integers(1, 90, n_shots, endpoint=True)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    g = torch.Generator(device="cuda"); g.manual_seed(5 + head_dim)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    k = torch.randn(1, int(off[-1]), h_kv, head_dim, device="cuda", generator=g).to(tdt)
+    v = torch.randn(1, int(off[-1]), h_kv, head_dim, device="cuda", generator=g).to(tdt)
+    q = torch.randn(t_q, h_q, head_dim, device="cuda", generator=g).to(tdt)
+    ctx = ad.Context(1, h_q, h_kv, head_dim, 1.0e4, ad.F32 if dtype == "f32" else ad.BF16, key_state=key_state,
+                     max_position=1 << 12)
+    ctx.pool_register(k, v, off)
+    got = ctx.rank_shots(0, q, q_pos0=11).cpu().numpy()
+    again = ctx.rank_shots(0, q, q_pos0=11).cpu().numpy()
+    want = oracle_mod.rank_scores(H.to_storage(k)[0], dtype, off, H.to_storage(q), 1.0e4, key_state, q_pos0=11)
+    assert np.array_equal(got.view(np.int32), again.view(np.int32))
+    got = got.astype(np.float64)
+    assert abs(float((got * lens).sum()) - 1.0) < (1e-5 if dtype == "f32" else 2e-3)
+    err = np.abs(got - want)
+    if dtype == "f32":
+        assert float((err / want).max()) < 1e-4, float((err / want).max())
+    else:   # the rotated query is rounded to bf16 on the GPU (as in the matrix-core path), not in the oracle
+        assert float(err.max()) <= 2e-2 * want.max() and float((err / want).mean()) < 5e-3
+    ids = ctx.top_k(got.astype(np.float32), 5)
+    order = np.argsort(-want, kind="stable")
+    for r_, i in enumerate(ids):
+        assert want[i] >= want[order[r_]] - 4 * float(err.max())
+    ctx.close()
