@@ -306,6 +306,13 @@ adapshot_status adapshot_pick_shots(adapshot_ctx* ctx, const float* entropy, con
  * summation order of the partials. */
 adapshot_status adapshot_set_attn_splits(adapshot_ctx* ctx, int32_t n_split);
 
+/* The split plan adapshot_query_attn uses for t_q query tokens over n_ctx context slots on a GPU with
+ * n_compute_units compute units (host logic, nothing is launched, no GPU needed): the context is cut into
+ * *n_split pieces of *keys_per_split slots (a multiple of 64; the last piece may be shorter; an empty context
+ * has no piece), and the query's own tokens form one more.  EINVAL on a bad description or argument. */
+adapshot_status adapshot_attn_split_plan(const adapshot_model_desc* desc, int32_t n_compute_units, int32_t t_q,
+                                         int64_t n_ctx, int32_t* n_split, int64_t* keys_per_split);
+
 /* Measurement aid (not a step of the method).  While enabled, every kernel the context
  * launches carries a pair of HIP events attached to its dispatch on the launch stream, whose
  * difference is the kernel's own execution time (events recorded before and after a launch

@@ -29,7 +29,8 @@ EXPORTS = ["adapshot_create", "adapshot_destroy", "adapshot_last_error", "adapsh
            "adapshot_profile_enable", "adapshot_profile_read", "adapshot_profile_read_each", "adapshot_assemble_batched",
            "adapshot_query_attn_batched", "adapshot_decode_append", "adapshot_probe_entropy_tokens",
            "adapshot_pick_shots", "adapshot_rank_shots", "adapshot_top_k", "adapshot_set_attn_splits",
-           "adapshot_probe_entropy_static", "adapshot_query_attn_pool", "adapshot_query_attn_pool_batched"]
+           "adapshot_probe_entropy_static", "adapshot_query_attn_pool", "adapshot_query_attn_pool_batched",
+           "adapshot_attn_split_plan"]
 ENTROPY_FULL_P, ENTROPY_RENORMALISED = 0, 1
 KERNEL_KINDS = ["assemble_reencode", "rope_rows", "query_attn", "attn_combine", "entropy_chunk", "entropy_finish"]
 
@@ -107,6 +108,8 @@ def load_library() -> ctypes.CDLL:
     L.adapshot_query_attn_batched.argtypes = [vp, ctypes.POINTER(CacheStruct), i32, i32, ctypes.POINTER(AttnItem), i32, vp]
     L.adapshot_decode_append.restype = ctypes.c_int
     L.adapshot_decode_append.argtypes = [vp, ctypes.POINTER(CacheStruct), i32, vp, vp, i64, vp]
+    L.adapshot_attn_split_plan.restype = ctypes.c_int
+    L.adapshot_attn_split_plan.argtypes = [ctypes.POINTER(ModelDesc), i32, i32, i64, ctypes.POINTER(i32), ctypes.POINTER(i64)]
     L.adapshot_set_attn_splits.restype = ctypes.c_int
     L.adapshot_set_attn_splits.argtypes = [vp, i32]
     L.adapshot_profile_enable.restype = ctypes.c_int
@@ -117,6 +120,18 @@ def load_library() -> ctypes.CDLL:
     L.adapshot_profile_read_each.argtypes = [vp, i32, vp, i64, ctypes.POINTER(i64)]
     _lib = L
     return L
+
+
+def attn_split_plan(n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: int, n_compute_units: int, t_q: int,
+                    n_ctx: int):
+    """(n_split, keys_per_split) of one adapshot_query_attn call (host logic only: runs without a GPU)."""
+    desc = ModelDesc(1, n_q_heads, n_kv_heads, head_dim, 1.0e4, dtype, KEYS_UNROTATED, 0)
+    ns, kps = ctypes.c_int32(), ctypes.c_int64()
+    st = load_library().adapshot_attn_split_plan(ctypes.byref(desc), n_compute_units, t_q, n_ctx, ctypes.byref(ns),
+                                                 ctypes.byref(kps))
+    if st != OK:
+        raise AdapshotError(st, "attn_split_plan: bad arguments")
+    return ns.value, kps.value
 
 
 def _stream_ptr(stream: Optional[torch.cuda.Stream] = None) -> int:

@@ -559,6 +559,32 @@ static int64_t plan_mfma_splits(int64_t n_cu, int64_t units, int64_t key_tiles, 
     return best;
 }
 
+// Split the context of one attention call so that (kv heads x row tiles x splits) fills the chip: once for the
+// MFMA kernel (one 8-wave workgroup per compute unit), several times for the one-wave generic kernel.  Keys per
+// split is a multiple of the 64-key tile; an empty context has no split.
+static void plan_single_attn(const adapshot_model_desc& d, int64_t n_cu, int32_t force_splits, int32_t t_q, int64_t n_ctx,
+                             int64_t* n_split_out, int64_t* keys_per_split_out) {
+    const bool mfma = attn_mfma_supported(d);
+    const int64_t rows = (int64_t)t_q * (d.n_q_heads / d.n_kv_heads);
+    const int64_t row_tile = mfma ? kAttnRowTile : 1;
+    const int64_t units = d.n_kv_heads * ((rows + row_tile - 1) / row_tile);
+    const int64_t key_tiles = (n_ctx + 63) / 64;
+    int64_t n_split = 0, keys_per_split = 64;
+    if (key_tiles > 0) {
+        if (mfma) {
+            n_split = plan_mfma_splits(n_cu, units, key_tiles, ((int64_t)t_q + 63) / 64);
+        } else {
+            const int64_t target = std::max<int64_t>(1, n_cu * 8 / units);
+            n_split = std::min<int64_t>(std::min<int64_t>(target, key_tiles), 64);
+        }
+        if (force_splits > 0) n_split = std::min<int64_t>(force_splits, key_tiles);
+        keys_per_split = ((key_tiles + n_split - 1) / n_split) * 64;
+        n_split = (n_ctx + keys_per_split - 1) / keys_per_split;
+    }
+    *n_split_out = n_split;
+    *keys_per_split_out = keys_per_split;
+}
+
 // k_ctx / v_ctx: one layer of the context the rows attend over -- the assembled cache, or, for the zero-copy form
 // (slot_src and tile_rot given), one layer of the pool.
 static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, const void* v_ctx, int64_t n_ctx,
@@ -583,24 +609,8 @@ static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, c
     const int64_t rows = (int64_t)t_q * g;
     const bool mfma = attn_mfma_supported(d);
 
-    // Split the context so that (kv heads x row tiles x splits) fills the chip: once for the MFMA
-    // kernel (one 8-wave workgroup per compute unit), several times for the one-wave generic kernel.
-    // Keys per split is a multiple of the 64-key tile.
-    const int64_t row_tile = mfma ? kAttnRowTile : 1;
-    const int64_t units = d.n_kv_heads * ((rows + row_tile - 1) / row_tile);
-    const int64_t key_tiles = (n_ctx + 63) / 64;
     int64_t n_split = 0, keys_per_split = 64;
-    if (key_tiles > 0) {
-        if (mfma) {
-            n_split = plan_mfma_splits(ctx->n_cu, units, key_tiles, ((int64_t)t_q + 63) / 64);
-        } else {
-            const int64_t target = std::max<int64_t>(1, (int64_t)ctx->n_cu * 8 / units);
-            n_split = std::min<int64_t>(std::min<int64_t>(target, key_tiles), 64);
-        }
-        if (ctx->force_splits > 0) n_split = std::min<int64_t>(ctx->force_splits, key_tiles);
-        keys_per_split = ((key_tiles + n_split - 1) / n_split) * 64;
-        n_split = (n_ctx + keys_per_split - 1) / keys_per_split;
-    }
+    plan_single_attn(d, ctx->n_cu, ctx->force_splits, t_q, n_ctx, &n_split, &keys_per_split);
 
     const size_t esz = (size_t)ctx->elem_bytes;
     hipError_t e = hipSuccess;
@@ -1535,6 +1545,18 @@ extern "C" adapshot_status adapshot_set_attn_splits(adapshot_ctx* ctx, int32_t n
     if (n_split < 0 || n_split > 64) return fail(ctx, ADAPSHOT_EINVAL, "set_attn_splits: n_split must be in [0, 64]");
     ctx->force_splits = n_split;
     ctx->last_error.clear();
+    return ADAPSHOT_OK;
+}
+
+extern "C" adapshot_status adapshot_attn_split_plan(const adapshot_model_desc* desc, int32_t n_compute_units,
+                                                    int32_t t_q, int64_t n_ctx, int32_t* n_split,
+                                                    int64_t* keys_per_split) {
+    if (!desc || !n_split || !keys_per_split || n_compute_units < 1 || t_q < 1 || n_ctx < 0) return ADAPSHOT_EINVAL;
+    if (check_desc(*desc) != nullptr) return ADAPSHOT_EINVAL;
+    int64_t ns = 0, kps = 64;
+    plan_single_attn(*desc, n_compute_units, 0, t_q, n_ctx, &ns, &kps);
+    *n_split = (int32_t)ns;
+    *keys_per_split = kps;
     return ADAPSHOT_OK;
 }
 

@@ -142,3 +142,35 @@ def test_top_k_is_host_logic(lib):
     assert lib.adapshot_top_k(None, None, i32(2), i32(1), None) != 0
     # the device entry point refuses a null context before touching anything
     assert lib.adapshot_rank_shots(None, i32(0), None, i32(1), ctypes.c_int64(0), None, None) != 0
+
+
+def test_attn_split_plan_properties(lib):
+    """The attention split planner is host logic: checked here without a GPU.  Whatever the shape, the splits cover
+    the context exactly once in pieces of one length that is a multiple of the 64-key tile, at most 64 of them; the
+    two workloads the kernel was sized on get the plans their measurements were made with."""
+    import numpy as np
+    from paper_2605_03644_amd import binding as ad
+    # the headline workload: 32 q / 8 kv heads, 128 query tokens (16 units), ~27k context on 256 compute units:
+    # 15 splits of 29 tiles share one round with the 16 self workgroups
+    assert ad.attn_split_plan(32, 8, 128, ad.BF16, 256, 128, 27189) == (15, 29 * 64)
+    # 64 q / 8 kv heads, 256 query tokens (64 units), 126617 slots: one context split per compute unit
+    assert ad.attn_split_plan(64, 8, 128, ad.BF16, 256, 256, 126617) == (4, 495 * 64)
+    assert ad.attn_split_plan(32, 8, 128, ad.BF16, 256, 128, 0) == (0, 64)
+    rng = np.random.default_rng(3)
+    shapes = [(32, 8, 128, ad.BF16), (28, 4, 128, ad.BF16), (4, 2, 64, ad.F32), (8, 8, 128, ad.F32), (64, 8, 128, ad.BF16)]
+    for _ in range(400):
+        hq, hkv, d, dt = shapes[rng.integers(len(shapes))]
+        n_cu = int(rng.choice([1, 8, 64, 104, 256, 304]))
+        t_q = int(rng.choice([1, 2, 7, 64, 128, 300, 4096]))
+        n_ctx = int(rng.choice([1, 63, 64, 65, 1000, 27189, 126617, 2_000_000]))
+        ns, kps = ad.attn_split_plan(hq, hkv, d, dt, n_cu, t_q, n_ctx)
+        assert 1 <= ns <= 64 and kps % 64 == 0 and kps >= 64
+        assert ns * kps >= n_ctx and (ns - 1) * kps < n_ctx, (hq, hkv, d, n_cu, t_q, n_ctx, ns, kps)
+    # more compute units never mean fewer, longer splits for the same problem beyond one round
+    assert ad.attn_split_plan(32, 8, 128, ad.BF16, 64, 128, 27189)[0] <= ad.attn_split_plan(32, 8, 128, ad.BF16, 256, 128, 27189)[0]
+    with pytest.raises(ad.AdapshotError):
+        ad.attn_split_plan(32, 7, 128, ad.BF16, 256, 128, 100)      # heads do not divide
+    with pytest.raises(ad.AdapshotError):
+        ad.attn_split_plan(32, 8, 128, ad.BF16, 0, 128, 100)
+    with pytest.raises(ad.AdapshotError):
+        ad.attn_split_plan(32, 8, 128, ad.BF16, 256, 128, -1)
