@@ -85,6 +85,19 @@ def test_zero_copy_other_shapes_layers_and_identity_order(ad, oracle_mod):
     _case(ad, oracle_mod, w, ids, order, 64, pairs=pairs)
 
 
+def test_zero_copy_llama70b_128k_sampled(ad, oracle_mod):
+    """Config 4's context on one layer: 1000 of 4000 shots (~127k tokens, 495 key tiles per context split, so the
+    rings of table pieces and rotation rows wrap many times), 256 query tokens, 64 q / 8 kv heads; 400 sampled
+    outputs against the oracle chain, every output against the two-pass path."""
+    w = wl.WORKLOADS["llama70b_128k"]
+    ids, order = wl.selection(w)
+    rng = np.random.default_rng(8)
+    pairs = np.stack([rng.integers(0, w.t_q, 400), rng.integers(0, w.n_q_heads, 400)], axis=1).astype(np.int32)
+    pairs[0] = (0, 0); pairs[1] = (w.t_q - 1, w.n_q_heads - 1)
+    err, fro = _case(ad, oracle_mod, w, ids, order, w.t_q, pairs=pairs)
+    assert err < 2e-2
+
+
 def test_zero_copy_generic_kernel_fp32(ad, oracle_mod):
     """The fp32 / head_dim 64 workload goes through the generic kernel, which gathers and rotates on the way into the
     score: single calls (with an order, a position base, a duplicate) and a batch over two lists."""
