@@ -684,11 +684,75 @@ static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, c
     return ADAPSHOT_OK;
 }
 
+// Common split length (in 64-key tiles) of a batch.  The longest item is cut into n equal splits, every other item
+// into splits of that length plus a remainder; n is the candidate whose work list finishes first when the
+// workgroups, sorted longest first, are dealt round-robin over the compute units (the first workgroup of every
+// round is the longest of that round, so the finish time is the sum of those), or rather the fewest splits that come
+// within 8 % of it: whole rounds of equal workgroups win
+// over an average that leaves a few compute units one workgroup more (32 queries x 4 kv heads x 16k tokens: 4 splits,
+// 512 workgroups in two rounds, 199 us; the 4-or-5 splits of an average-based length: 210 us; 3 splits: 230 us).
+struct BatchShape {
+    int64_t units, key_tiles, self_tiles;
+};
+static int64_t plan_batch_split_tiles(int64_t n_cu, const std::vector<BatchShape>& shapes, int32_t force_splits) {
+    int64_t longest = 1;
+    for (const BatchShape& b : shapes) longest = std::max(longest, b.key_tiles);
+    if (force_splits > 0) return (longest + force_splits - 1) / force_splits;
+    const double fixed = 2.5;  // launch, first tile round trip and partial write-out of a workgroup, in tiles
+    struct Class {
+        double cost;
+        int64_t count;
+    };
+    std::vector<Class> cls;
+    int64_t best_st = longest;
+    double best_t = 1e300;
+    static const int kCand[] = {1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 14, 16, 20, 24, 32, 48, 64};
+    int64_t cand_st[sizeof(kCand) / sizeof(kCand[0])];
+    double cand_t[sizeof(kCand) / sizeof(kCand[0])];
+    int n_cand = 0;
+    int64_t last_st = -1;
+    for (int n : kCand) {
+        int64_t st = (longest + n - 1) / n;
+        if (st < 8 && longest >= 8) st = 8;  // shorter splits are all prologue
+        if (st == last_st) continue;
+        last_st = st;
+        cls.clear();
+        int64_t partials = 0;
+        for (const BatchShape& b : shapes) {
+            const int64_t full = b.key_tiles / st, rem = b.key_tiles - full * st;
+            if (full > 0) cls.push_back(Class{(double)st + fixed, full * b.units});
+            if (rem > 0) cls.push_back(Class{(double)rem + fixed, b.units});
+            cls.push_back(Class{(double)b.self_tiles + fixed, b.units});
+            partials += (full + (rem > 0)) * b.units;
+        }
+        std::sort(cls.begin(), cls.end(), [](const Class& a, const Class& b) { return a.cost > b.cost; });
+        // finish time of the compute unit that gets the first workgroup of every round
+        double t = 0.0;
+        int64_t rank = 0, next_pick = 0;  // workgroups dealt so far; rank of the next round's first workgroup
+        for (const Class& c : cls) {
+            while (next_pick < rank + c.count) {
+                t += c.cost;
+                next_pick += n_cu;
+            }
+            rank += c.count;
+        }
+        t += 0.0005 * (double)partials;  // the partials are written and merged too
+        cand_st[n_cand] = st;
+        cand_t[n_cand++] = t;
+        best_t = std::min(best_t, t);
+    }
+    // The fewest splits within 8 % of the best: the chip clocks higher while some compute units idle, so a finer
+    // cut gains less than its balance promises, and every extra workgroup has a prologue, an epilogue and a
+    // partial of its own (the probe sweep's 48 items: 4-5 splits of the longest item 850 us, 8-16 splits 872-887 us).
+    for (int i = 0; i < n_cand; ++i)
+        if (cand_t[i] <= 1.08 * best_t) return cand_st[i];
+    return best_st;
+}
+
 // All items of a batch in two launches: one MFMA attention grid over the work list of all (item, kv head,
 // row tile, split) workgroups (each rotates the query rows it needs itself), one combine grid.  Items are validated
-// by the caller.  The context is cut into splits of one common length, chosen so that the whole batch
-// makes about two rounds of workgroups over the chip (long splits keep the partial traffic low, two
-// rounds even out items of different length); the work list is ordered longest first.
+// by the caller.  The context is cut into splits of one common length (plan_batch_split_tiles: whole rounds of
+// equal workgroups over the chip); the work list is ordered longest first.
 // With `pool` given the items' contexts are shot lists read where they lie in the pool (zero-copy form): an item's
 // cache_index names a list, and its context is the first n_ctx slots of that list's slot table.
 struct PoolBatch {
@@ -705,19 +769,14 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
     const int g = d.n_q_heads / d.n_kv_heads;
 
     // ---- split plan
-    int64_t tile_units = 0;
+    std::vector<BatchShape> shapes((size_t)n_items);
     for (int32_t i = 0; i < n_items; ++i) {
         const int64_t rows = (int64_t)items[i].t_q * g;
-        const int64_t units = d.n_kv_heads * ((rows + kAttnRowTile - 1) / kAttnRowTile);
-        tile_units += units * ((items[i].n_ctx + 63) / 64);
+        shapes[(size_t)i].units = d.n_kv_heads * ((rows + kAttnRowTile - 1) / kAttnRowTile);
+        shapes[(size_t)i].key_tiles = (items[i].n_ctx + 63) / 64;
+        shapes[(size_t)i].self_tiles = ((int64_t)items[i].t_q + 63) / 64;
     }
-    const int64_t target_wgs = (int64_t)ctx->n_cu * 2;
-    int64_t split_tiles_common = std::max<int64_t>(8, (tile_units + target_wgs - 1) / target_wgs);
-    if (ctx->force_splits > 0) {  // the longest item gets the forced split count, the others the same split length
-        int64_t longest = 1;
-        for (int32_t i = 0; i < n_items; ++i) longest = std::max<int64_t>(longest, (items[i].n_ctx + 63) / 64);
-        split_tiles_common = (longest + ctx->force_splits - 1) / ctx->force_splits;
-    }
+    const int64_t split_tiles_common = plan_batch_split_tiles(ctx->n_cu, shapes, ctx->force_splits);
 
     struct Plan {
         int64_t rows, n_row_tiles, n_split, keys_per_split;
