@@ -190,7 +190,10 @@ adapshot_status adapshot_assemble_batched(adapshot_ctx* ctx, adapshot_cache* cac
  * have one common length, so
  * probes over nested prefixes of one cache read identical leading slices, and those workgroups are
  * scheduled next to each other.  Other shapes run item by item.  The outputs of distinct items must not
- * overlap; inputs may be shared between items. */
+ * overlap; inputs may be shared between items.  A call whose arguments other than `layer` equal the previous
+ * batched call's on this context (the same items, caches, pointers and lengths: the next layer of a forward pass)
+ * reuses the tables the previous call left in device memory and only launches; nothing the caller does between
+ * the two calls can make that wrong except freeing or moving the buffers the items name. */
 typedef struct {
     const void* q;       /* DEVICE [t_q][n_q_heads][head_dim] */
     const void* k_self;  /* DEVICE [t_q][n_kv_heads][head_dim] */

@@ -291,6 +291,8 @@ extern "C" adapshot_status adapshot_pool_register(adapshot_ctx* ctx, const void*
     ctx->n_shots = n_shots;
     ctx->pool_layer_stride_tokens = layer_stride_tokens;
     ctx->rank_layer = -1;  // ranking state belongs to the previous pool
+    ctx->batch_key.clear();  // so do the tables kept for the next layer of a batch
+    ctx->pool_key.clear();
     ctx->last_error.clear();
     return ADAPSHOT_OK;
 }
@@ -674,6 +676,7 @@ static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, c
     ap.n_kv_heads = d.n_kv_heads;
     ap.head_dim = d.head_dim;
     ap.dtype = d.dtype;
+    ap.layer_stride_bytes = 0;
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream, [&] {
         if (!mfma) return launch_attn_generic(ap, GenericPool{slot_src, ctx->tab_lo, ctx->tab_hi, ctx_pos0}, stream);
         return slot_src ? launch_attn_mfma_pool(ap, af, stream) : launch_attn_mfma(ap, af, stream);
@@ -756,7 +759,7 @@ static int64_t plan_batch_split_tiles(int64_t n_cu, const std::vector<BatchShape
 // With `pool` given the items' contexts are shot lists read where they lie in the pool (zero-copy form): an item's
 // cache_index names a list, and its context is the first n_ctx slots of that list's slot table.
 struct PoolBatch {
-    const char* k_layer;        // one layer of the pool
+    const char* k_layer;        // the layer to attend in (what the item-by-item path of other shapes reads)
     const char* v_layer;
     const int32_t* slot_src;    // device: the lists' slot tables, one after the other
     const int64_t* list_base;   // host: first entry of every list in slot_src
@@ -767,6 +770,41 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
                                             const PoolBatch* pool = nullptr) {
     const adapshot_model_desc& d = ctx->desc;
     const int g = d.n_q_heads / d.n_kv_heads;
+
+    // ---- the same batch as the last call (the next layer of a model)?  Then the tables in device memory still
+    // hold: they name layer 0 of every context, and the launch names the layer.
+    std::vector<unsigned char> key;
+    {
+        auto put = [&](const void* ptr, size_t n) { key.insert(key.end(), (const unsigned char*)ptr, (const unsigned char*)ptr + n); };
+        const int32_t head[4] = {pool ? 1 : 0, ctx->force_splits, n_items, ctx->n_cu};
+        put(head, sizeof(head));
+        put(items, (size_t)n_items * sizeof(adapshot_attn_item));
+        for (int32_t i = 0; i < n_items; ++i) {
+            if (pool) {
+                const void* id[3] = {ctx->k_pool, pool->slot_src + pool->list_base[items[i].cache_index], pool->tile_rot};
+                put(id, sizeof(id));
+            } else {
+                const adapshot_cache& c = caches[items[i].cache_index];
+                const void* id[2] = {c.k, c.v};
+                put(id, sizeof(id));
+                put(&c.capacity, sizeof(c.capacity));
+            }
+        }
+    }
+    if (!ctx->batch_key.empty() && key == ctx->batch_key) {
+        const AttnBatchItem* dit = (const AttnBatchItem*)ctx->batch_tab.p;
+        const AttnWork* daw = (const AttnWork*)((const char*)ctx->batch_tab.p + ctx->batch_attn_off);
+        const CombineWork* dcw = (const CombineWork*)((const char*)ctx->batch_tab.p + ctx->batch_comb_off);
+        hipError_t e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream, [&] {
+            return launch_attn_mfma_batched(dit, daw, (int)ctx->batch_n_attn, pool != nullptr, layer, stream);
+        });
+        if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: attention launch", e);
+        e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream,
+                         [&] { return launch_attn_combine_batched(dit, dcw, (int)ctx->batch_n_comb, d.dtype, stream); });
+        if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: combine launch", e);
+        return ADAPSHOT_OK;
+    }
+    ctx->batch_key.clear();  // the tables are about to be rewritten
 
     // ---- split plan
     std::vector<BatchShape> shapes((size_t)n_items);
@@ -839,16 +877,17 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
         const adapshot_attn_item& it = items[i];
         const Plan& pl = plan[(size_t)i];
         AttnBatchItem& b = hit[i];
-        if (pool) {
-            b.attn.k_cache = pool->k_layer;
-            b.attn.v_cache = pool->v_layer;
+        if (pool) {  // layer 0 of the context; the launch names the layer
+            b.attn.k_cache = ctx->k_pool;
+            b.attn.v_cache = ctx->v_pool;
+            b.attn.layer_stride_bytes = ctx->pool_layer_stride_tokens * ctx->row_bytes;
             b.fold.slot_src = pool->slot_src + pool->list_base[it.cache_index];
             b.fold.tile_rot = pool->tile_rot;
         } else {
             const adapshot_cache& c = caches[it.cache_index];
-            const int64_t layer_off = (int64_t)layer * c.capacity * ctx->row_bytes;
-            b.attn.k_cache = (const char*)c.k + layer_off;
-            b.attn.v_cache = (const char*)c.v + layer_off;
+            b.attn.k_cache = c.k;
+            b.attn.v_cache = c.v;
+            b.attn.layer_stride_bytes = c.capacity * ctx->row_bytes;
             b.fold.slot_src = nullptr;
             b.fold.tile_rot = nullptr;
         }
@@ -908,11 +947,16 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
     const AttnWork* daw = (const AttnWork*)((const char*)ctx->batch_tab.p + attn_off);
     const CombineWork* dcw = (const CombineWork*)((const char*)ctx->batch_tab.p + comb_off);
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream,
-                     [&] { return launch_attn_mfma_batched(dit, daw, (int)n_attn, pool != nullptr, stream); });
+                     [&] { return launch_attn_mfma_batched(dit, daw, (int)n_attn, pool != nullptr, layer, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: attention launch", e);
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream,
                      [&] { return launch_attn_combine_batched(dit, dcw, (int)n_comb, d.dtype, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: combine launch", e);
+    ctx->batch_key.swap(key);
+    ctx->batch_n_attn = n_attn;
+    ctx->batch_n_comb = n_comb;
+    ctx->batch_attn_off = attn_off;
+    ctx->batch_comb_off = comb_off;
     return ADAPSHOT_OK;
 }
 
@@ -975,6 +1019,8 @@ extern "C" adapshot_status adapshot_query_attn_pool(adapshot_ctx* ctx, int32_t l
         return st;
     }
 
+    ctx->pool_key.clear();  // the batched call's plan, if any, is overwritten
+    ctx->batch_key.clear();
     const int64_t n_tiles = (total + 63) / 64;
     hipError_t e = ctx->pool_src.reserve((size_t)(total + 256) * sizeof(int32_t), ctx->retired);  // the kernel reads it 1 KB at a time
     if (e == hipSuccess) e = ctx->pool_rot.reserve((size_t)n_tiles * (d.head_dim / 2) * sizeof(float2), ctx->retired);
@@ -1091,7 +1137,28 @@ extern "C" adapshot_status adapshot_query_attn_pool_batched(adapshot_ctx* ctx, i
     pb.list_base = list_base.data();
     pb.slot_src = nullptr;
     pb.tile_rot = nullptr;
-    if (longest > 0) {
+    // the slot tables and rotation rows of the same lists at the same positions (the previous layer's call) still hold
+    std::vector<unsigned char> pkey;
+    {
+        auto put = [&](const void* ptr, size_t n) { pkey.insert(pkey.end(), (const unsigned char*)ptr, (const unsigned char*)ptr + n); };
+        const int64_t head[2] = {n_lists, pos0};
+        put(head, sizeof(head));
+        put(m, (size_t)n_lists * sizeof(int32_t));
+        for (int32_t l = 0; l < n_lists; ++l) {
+            const int32_t* order = orders ? orders[l] : nullptr;
+            for (int32_t j = 0; j < m[l]; ++j) {
+                const int32_t sid = shot_ids[l][order ? order[j] : j];
+                put(&sid, sizeof(sid));
+            }
+        }
+    }
+    const bool plan_holds = longest > 0 && !ctx->pool_key.empty() && pkey == ctx->pool_key;
+    if (plan_holds) {
+        pb.slot_src = (const int32_t*)ctx->pool_src.p;
+        pb.tile_rot = (const float2*)ctx->pool_rot.p;
+    } else if (longest > 0) {
+        ctx->pool_key.clear();
+        ctx->batch_key.clear();  // its tables point into what is rewritten now
         const int64_t n_tiles = (longest + 63) / 64;
         hipError_t e = ctx->pool_src.reserve((size_t)(list_base[(size_t)n_lists] + 256) * sizeof(int32_t), ctx->retired);
         if (e == hipSuccess) e = ctx->pool_rot.reserve((size_t)n_tiles * (d.head_dim / 2) * sizeof(float2), ctx->retired);
@@ -1128,6 +1195,7 @@ extern "C" adapshot_status adapshot_query_attn_pool_batched(adapshot_ctx* ctx, i
         if (e != hipSuccess) return fail_hip(ctx, "query_attn_pool_batched: event record", e);
         pb.slot_src = (const int32_t*)ctx->pool_src.p;
         pb.tile_rot = (const float2*)ctx->pool_rot.p;
+        ctx->pool_key.swap(pkey);
     }
     adapshot_status st = ADAPSHOT_OK;
     if (attn_mfma_supported(d)) {
@@ -1541,6 +1609,7 @@ extern "C" adapshot_status adapshot_rank_shots(adapshot_ctx* ctx, int32_t layer,
     ap.n_kv_heads = d.n_kv_heads;
     ap.head_dim = d.head_dim;
     ap.dtype = d.dtype;
+    ap.layer_stride_bytes = 0;
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream, [&] { return launch_attn_mfma(ap, af, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "rank_shots: attention launch", e);
 

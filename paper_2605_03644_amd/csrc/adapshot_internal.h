@@ -149,6 +149,9 @@ struct AttnParams {
     int64_t keys_per_split;
     int32_t n_split;
     int32_t t_q, n_q_heads, n_kv_heads, head_dim, dtype;
+    // Batched launches only: k_cache / v_cache point at layer 0 of the item's context and the launch names the
+    // layer, so that the tables of a batch serve every layer of a model (0 for single calls).
+    int64_t layer_stride_bytes;
 };
 constexpr int kAttnRowTile = 256;  // query rows per workgroup of the MFMA kernel
 struct GenericPool {  // zero-copy form of the generic kernel; slot_src == nullptr: the context is an assembled cache
@@ -194,7 +197,7 @@ struct CombineWork {  // one workgroup of the batched combine kernel: 16 (kv hea
 // Tables written by the host into pinned memory are brought to device memory by a kernel (a DMA copy
 // between two kernels of a stream costs more than the copy itself).  bytes is a multiple of 16.
 hipError_t launch_copy_table(void* dst, const void* src_pinned, size_t bytes, hipStream_t stream);
-hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, bool pool,
+hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, bool pool, int layer,
                                     hipStream_t stream);
 hipError_t launch_attn_combine_batched(const AttnBatchItem* items, const CombineWork* work, int n_work, int dtype,
                                        hipStream_t stream);
@@ -346,6 +349,12 @@ struct adapshot_ctx {
     // scratch
     adapshot::PinnedRing tile_ring;
     adapshot::DevBuf q_rot, k_rot, part_o, part_ml, ent_part, batch_tab, pool_src, pool_rot;
+    // What the device-side tables of the last batched attention call (batch_tab) and of the last zero-copy plan
+    // (pool_src, pool_rot) were built from: a call with the same inputs -- the next layer of the same batch --
+    // reuses them instead of planning and uploading again.  Empty = nothing to reuse.
+    std::vector<unsigned char> batch_key, pool_key;
+    int64_t batch_n_attn = 0, batch_n_comb = 0;
+    size_t batch_attn_off = 0, batch_comb_off = 0;
     // ranking state of one pool layer, built on first use
     int32_t rank_layer = -1;
     int32_t rank_n_split = 0;

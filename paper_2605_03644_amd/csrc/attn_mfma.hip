@@ -158,6 +158,7 @@ template <int WAVES, int NR, bool BATCHED, int PVB, bool POOL, bool FOLD>
 __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg, AttnFold f_arg,
                                                                int n_row_tiles_arg, const AttnBatchItem* items,
                                                                const AttnWork* work) {
+    // n_row_tiles_arg: row tiles per kv head of the single problem; for a batch, the layer to attend in
     constexpr int PASSES = (kTileKeys * 16) / (WAVES * 64);  // 1 KB blocks of a tile per wavefront
     static_assert(PASSES * WAVES * 64 == kTileKeys * 16, "tile must divide over the threads");
     static_assert(WAVES * NR * 32 == kAttnRowTile && NR == 1, "row tile");
@@ -187,6 +188,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
         const AttnWork w = load_uniform(work + blockIdx.x);
         item = w.item;
         p = load_uniform(&items[w.item].attn);
+        p.k_cache = (const char*)p.k_cache + (int64_t)n_row_tiles_arg * p.layer_stride_bytes;
+        p.v_cache = (const char*)p.v_cache + (int64_t)n_row_tiles_arg * p.layer_stride_bytes;
         hk = w.hk;
         row_tile = w.row_tile;
         split = w.split;
@@ -863,15 +866,15 @@ hipError_t launch_attn_mfma_pool(const AttnParams& p, const AttnFold& f, hipStre
     return hipGetLastError();
 }
 
-hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, bool pool,
+hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, bool pool, int layer,
                                     hipStream_t stream) {
     if (n_work <= 0) return hipSuccess;
     if (pool)
         launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), true, 4, true, true>), dim3((unsigned)n_work),
-                      dim3(kAttnWaves * 64), stream, AttnParams{}, AttnFold{}, 0, items, work);
+                      dim3(kAttnWaves * 64), stream, AttnParams{}, AttnFold{}, layer, items, work);
     else
         launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), true, 4, false, true>), dim3((unsigned)n_work),
-                      dim3(kAttnWaves * 64), stream, AttnParams{}, AttnFold{}, 0, items, work);
+                      dim3(kAttnWaves * 64), stream, AttnParams{}, AttnFold{}, layer, items, work);
     return hipGetLastError();
 }
 

@@ -123,3 +123,86 @@ def test_same_inputs_give_the_same_bits(ad):
     assert torch.equal(a[5].view(torch.int32), b[5].view(torch.int32))
     assert torch.equal(a[6].view(torch.int32), b[6].view(torch.int32))
     ctx.close()
+
+
+def test_batch_tables_kept_for_the_next_layer_give_the_same_bits(ad):
+    """A batched attention call whose inputs equal the previous call's (the next layer of a model) reuses the tables
+    in device memory; every such result must be bit-identical to what a fresh context computes for that layer alone,
+    for assembled caches and for the zero-copy form, and anything that changes the batch must drop the tables."""
+    w = wl.WORKLOADS["llama8b_sweep"]
+    L = 3
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=L)
+    lists = []
+    for qi in range(3):
+        ids, order = wl.selection(w, query=qi)
+        lists.append((ids[:20 + 5 * qi], np.argsort(np.argsort(order[:20 + 5 * qi])).astype(np.int32)))
+    totals = [int(sum(off[i + 1] - off[i] for i in ids)) for ids, _ in lists]
+    g = torch.Generator(device="cuda")
+    g.manual_seed(321)
+
+    def make_items(n_ctx_of):
+        its = []
+        for li, n_ctx, t_q in n_ctx_of:
+            q = torch.randn(t_q, w.n_q_heads, w.head_dim, device="cuda", generator=g).bfloat16()
+            ks = torch.randn(t_q, w.n_kv_heads, w.head_dim, device="cuda", generator=g).bfloat16()
+            vs = torch.randn(t_q, w.n_kv_heads, w.head_dim, device="cuda", generator=g).bfloat16()
+            its.append((li, n_ctx, q, ks, vs, n_ctx, torch.empty_like(q)))
+        return its
+
+    specs = [(0, totals[0], 64), (0, totals[0] // 2, 64), (1, totals[1], 7), (2, totals[2], 1), (2, 0, 3)]
+    items = make_items(specs)
+
+    def fresh(layer, its, zero_copy):
+        """The same batch on a context that has seen nothing else."""
+        c2 = ad.Context.for_workload(w, n_layers=L)
+        c2.pool_register(k_pool, v_pool, off)
+        outs = [(li, n, q, ks, vs, qp, torch.empty_like(q)) for (li, n, q, ks, vs, qp, _) in its]
+        if zero_copy:
+            c2.query_attn_pool_batched(layer, ([l[0] for l in lists], [l[1] for l in lists]), outs)
+        else:
+            cs = [ad.Cache(c2, t, with_index=False) for t in totals]
+            c2.assemble_batched(cs, [l[0] for l in lists], [l[1] for l in lists])
+            c2.query_attn_batched(cs, layer, outs)
+        torch.cuda.synchronize()
+        res = [o[6].clone() for o in outs]
+        c2.close()
+        return res
+
+    def same(its, ref):
+        torch.cuda.synchronize()
+        return all(torch.equal(a[6].view(torch.int16), b.view(torch.int16)) for a, b in zip(its, ref))
+
+    ctx = ad.Context.for_workload(w, n_layers=L)
+    ctx.pool_register(k_pool, v_pool, off)
+    caches = [ad.Cache(ctx, t, with_index=False) for t in totals]
+    ctx.assemble_batched(caches, [l[0] for l in lists], [l[1] for l in lists])
+    packed_lists = ctx.pack_shot_lists([l[0] for l in lists], [l[1] for l in lists])
+    for zero_copy in (False, True):
+        call = (lambda layer, its: ctx.query_attn_pool_batched(layer, packed_lists, its)) if zero_copy else \
+               (lambda layer, its: ctx.query_attn_batched(caches, layer, its))
+        packed = ctx.pack_attn_items(items)
+        for layer in (0, 1, 2, 1):                          # layers 1, 2, 1 reuse the tables of the first call
+            call(layer, packed)
+            assert same(items, fresh(layer, items, zero_copy)), (zero_copy, layer)
+        # another split count, another batch, another single call in between: each drops the tables
+        ctx.set_attn_splits(3)
+        call(2, packed)
+        ctx.set_attn_splits(0)
+        call(2, packed)
+        assert same(items, fresh(2, items, zero_copy))
+        items2 = make_items([(1, totals[1] - 5, 64), (0, totals[0], 64)])
+        call(1, items2)
+        assert same(items2, fresh(1, items2, zero_copy))
+        call(1, packed)
+        assert same(items, fresh(1, items, zero_copy))
+        q1, ks1, vs1 = items[0][2], items[0][3], items[0][4]
+        if zero_copy:
+            ctx.query_attn_pool(0, lists[2][0], lists[2][1], q1, ks1, vs1, totals[2])   # rewrites the slot tables
+        else:
+            ctx.query_attn(caches[1], 0, totals[1], q1, ks1, vs1, totals[1])
+        call(0, packed)
+        assert same(items, fresh(0, items, zero_copy))
+        ctx.pool_register(k_pool, v_pool, off)              # a new registration drops them too
+        call(2, packed)
+        assert same(items, fresh(2, items, zero_copy))
+    ctx.close()
