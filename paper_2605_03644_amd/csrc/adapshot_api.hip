@@ -691,7 +691,7 @@ static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, c
 // into splits of that length plus a remainder; n is the candidate whose work list finishes first when the
 // workgroups, sorted longest first, are dealt round-robin over the compute units (the first workgroup of every
 // round is the longest of that round, so the finish time is the sum of those), or rather the fewest splits that come
-// within 8 % of it: whole rounds of equal workgroups win
+// within 12 % of it: whole rounds of equal workgroups win
 // over an average that leaves a few compute units one workgroup more (32 queries x 4 kv heads x 16k tokens: 4 splits,
 // 512 workgroups in two rounds, 199 us; the 4-or-5 splits of an average-based length: 210 us; 3 splits: 230 us).
 struct BatchShape {
@@ -744,11 +744,11 @@ static int64_t plan_batch_split_tiles(int64_t n_cu, const std::vector<BatchShape
         cand_t[n_cand++] = t;
         best_t = std::min(best_t, t);
     }
-    // The fewest splits within 8 % of the best: the chip clocks higher while some compute units idle, so a finer
+    // The fewest splits within 12 % of the best: the chip clocks higher while some compute units idle, so a finer
     // cut gains less than its balance promises, and every extra workgroup has a prologue, an epilogue and a
     // partial of its own (the probe sweep's 48 items: 4-5 splits of the longest item 850 us, 8-16 splits 872-887 us).
     for (int i = 0; i < n_cand; ++i)
-        if (cand_t[i] <= 1.08 * best_t) return cand_st[i];
+        if (cand_t[i] <= 1.12 * best_t) return cand_st[i];
     return best_st;
 }
 
