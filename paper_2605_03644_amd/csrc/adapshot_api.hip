@@ -1019,7 +1019,25 @@ extern "C" adapshot_status adapshot_query_attn_pool(adapshot_ctx* ctx, int32_t l
         return st;
     }
 
-    ctx->pool_key.clear();  // the batched call's plan, if any, is overwritten
+    // the plan of the same shots at the same positions (the previous layer's call) still holds
+    std::vector<unsigned char> pkey;
+    {
+        auto put = [&](const void* ptr, size_t n) { pkey.insert(pkey.end(), (const unsigned char*)ptr, (const unsigned char*)ptr + n); };
+        const int64_t head[2] = {-1, pos0};  // -1: a single list at the start of the table (a batched plan names its list count)
+        put(head, sizeof(head));
+        put(&m, sizeof(m));
+        for (int32_t j = 0; j < m; ++j) {
+            const int32_t sid = shot_ids[order ? order[j] : j];
+            put(&sid, sizeof(sid));
+        }
+    }
+    if (!ctx->pool_key.empty() && pkey == ctx->pool_key) {
+        adapshot_status st = run_query_attn_on(ctx, k_layer, v_layer, total, q, k_self, v_self, t_q, q_pos0, out,
+                                               (const int32_t*)ctx->pool_src.p, (const float2*)ctx->pool_rot.p, stream, pos0);
+        if (st == ADAPSHOT_OK) ctx->last_error.clear();
+        return st;
+    }
+    ctx->pool_key.clear();  // the tables are about to be rewritten, and a batch's tables point into them
     ctx->batch_key.clear();
     const int64_t n_tiles = (total + 63) / 64;
     hipError_t e = ctx->pool_src.reserve((size_t)(total + 256) * sizeof(int32_t), ctx->retired);  // the kernel reads it 1 KB at a time
@@ -1054,7 +1072,10 @@ extern "C" adapshot_status adapshot_query_attn_pool(adapshot_ctx* ctx, int32_t l
     if (e != hipSuccess) return fail_hip(ctx, "query_attn_pool: event record", e);
     adapshot_status st = run_query_attn_on(ctx, k_layer, v_layer, total, q, k_self, v_self, t_q, q_pos0, out,
                                            (const int32_t*)ctx->pool_src.p, (const float2*)ctx->pool_rot.p, stream, pos0);
-    if (st == ADAPSHOT_OK) ctx->last_error.clear();
+    if (st == ADAPSHOT_OK) {
+        ctx->pool_key.swap(pkey);
+        ctx->last_error.clear();
+    }
     return st;
 }
 

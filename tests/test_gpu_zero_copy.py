@@ -289,3 +289,42 @@ def test_zero_copy_batched_errors_write_nothing(ad):
     ctx.query_attn_pool_batched(0, lists, [])              # no items: nothing to do
     ctx.query_attn_pool_batched(0, ([], None), [])
     ctx.close()
+
+
+def test_zero_copy_plan_kept_for_the_next_layer(ad):
+    """A single zero-copy call over the same shots at the same positions as the previous one (the next layer) keeps
+    the slot table: bit-identical to a fresh context's result for that layer; another list in between rebuilds it."""
+    w = wl.WORKLOADS["llama8b_1layer"]
+    L = 2
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=L)
+    ids, order = wl.selection(w)
+    ids, order = ids[:40], np.argsort(np.argsort(order[:40])).astype(np.int32)
+    total = int(sum(off[i + 1] - off[i] for i in ids))
+    q, ks, vs = wl.make_query(w, "cuda", t_q=33)
+
+    def fresh(layer, the_ids, the_order, n):
+        c2 = ad.Context.for_workload(w, n_layers=L)
+        c2.pool_register(k_pool, v_pool, off)
+        o = c2.query_attn_pool(layer, the_ids, the_order, q, ks, vs, n)
+        torch.cuda.synchronize()
+        c2.close()
+        return o
+
+    ctx = ad.Context.for_workload(w, n_layers=L)
+    ctx.pool_register(k_pool, v_pool, off)
+    for layer in (0, 1, 1, 0):
+        o = ctx.query_attn_pool(layer, ids, order, q, ks, vs, total)
+        assert torch.equal(o.view(torch.int16), fresh(layer, ids, order, total).view(torch.int16)), layer
+    other = ids[::-1].copy()
+    n2 = int(sum(off[i + 1] - off[i] for i in other[:7]))
+    o = ctx.query_attn_pool(1, other[:7], None, q, ks, vs, n2)
+    assert torch.equal(o.view(torch.int16), fresh(1, other[:7], None, n2).view(torch.int16))
+    o = ctx.query_attn_pool(1, ids, order, q, ks, vs, total)
+    assert torch.equal(o.view(torch.int16), fresh(1, ids, order, total).view(torch.int16))
+    o = ctx.query_attn_pool(0, ids, order, q, ks, vs, total + 3, pos0=3)      # same shots, other positions
+    c2 = ad.Context.for_workload(w, n_layers=L)
+    c2.pool_register(k_pool, v_pool, off)
+    ref = c2.query_attn_pool(0, ids, order, q, ks, vs, total + 3, pos0=3)
+    assert torch.equal(o.view(torch.int16), ref.view(torch.int16))
+    c2.close()
+    ctx.close()
