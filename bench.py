@@ -183,7 +183,7 @@ def extras(ad, dev) -> dict:
             items.append((qi, n_ctx, qq, ks, vs, n_ctx, torch.empty_like(qq)))
             flops += attn_flops(w, n_ctx, w.t_q)
     packed = ctx.pack_attn_items(items)
-    dt = wall(lambda: ctx.query_attn_batched(caches, 0, packed), 5)
+    dt = wall(lambda: ctx.query_attn_batched(caches, 0, packed), 20)
     out["probe_sweep_attention"] = {"workload": "48 probes (8 queries x 6 nested prefixes up to 512 shots), 64 tokens each, 1 layer",
                                     "us_per_call": dt * 1e6, "tflops": flops / dt * 1e-12}
     ctx.close()
@@ -207,7 +207,7 @@ def extras(ad, dev) -> dict:
     od = [torch.empty_like(qd[i]) for i in range(nq)]
     items = [(i, caches[i].len, qd[i], kd[i], vd[i], caches[i].len, od[i]) for i in range(nq)]
     packed = ctx.pack_attn_items(items)
-    dt = wall(lambda: ctx.query_attn_batched(caches, 0, packed), 10)
+    dt = wall(lambda: ctx.query_attn_batched(caches, 0, packed), 30)
     kv_bytes = sum(totals) * w.n_kv_heads * w.head_dim * 2 * 2
     out["decode_step_attention"] = {"workload": f"{nq} queries, ~{int(np.mean(totals))} context tokens each, 1 layer",
                                     "us_per_step": dt * 1e6, "kv_gbps": kv_bytes / dt * 1e-9,
