@@ -776,6 +776,7 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
     std::vector<unsigned char> key;
     {
         auto put = [&](const void* ptr, size_t n) { key.insert(key.end(), (const unsigned char*)ptr, (const unsigned char*)ptr + n); };
+        key.reserve(16 + (size_t)n_items * (sizeof(adapshot_attn_item) + 3 * sizeof(void*)));
         const int32_t head[4] = {pool ? 1 : 0, ctx->force_splits, n_items, ctx->n_cu};
         put(head, sizeof(head));
         put(items, (size_t)n_items * sizeof(adapshot_attn_item));
@@ -1023,6 +1024,7 @@ extern "C" adapshot_status adapshot_query_attn_pool(adapshot_ctx* ctx, int32_t l
     std::vector<unsigned char> pkey;
     {
         auto put = [&](const void* ptr, size_t n) { pkey.insert(pkey.end(), (const unsigned char*)ptr, (const unsigned char*)ptr + n); };
+        pkey.reserve(sizeof(int64_t) * 2 + sizeof(int32_t) * (size_t)(m + 1));
         const int64_t head[2] = {-1, pos0};  // -1: a single list at the start of the table (a batched plan names its list count)
         put(head, sizeof(head));
         put(&m, sizeof(m));
@@ -1162,6 +1164,7 @@ extern "C" adapshot_status adapshot_query_attn_pool_batched(adapshot_ctx* ctx, i
     std::vector<unsigned char> pkey;
     {
         auto put = [&](const void* ptr, size_t n) { pkey.insert(pkey.end(), (const unsigned char*)ptr, (const unsigned char*)ptr + n); };
+        pkey.reserve(sizeof(int64_t) * 2 + sizeof(int32_t) * (size_t)(n_lists + n_segs));
         const int64_t head[2] = {n_lists, pos0};
         put(head, sizeof(head));
         put(m, (size_t)n_lists * sizeof(int32_t));
