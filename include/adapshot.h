@@ -216,8 +216,9 @@ adapshot_status adapshot_query_attn_batched(adapshot_ctx* ctx, const adapshot_ca
  * n_ctx is a token count, at most the list's length: the probes of one query over nested prefixes of its ranked
  * list (Probe-based Dynamic Evaluation) are items of one list, and no shot is copied for a prefix that the stopping
  * rule then rejects.  Out[i] is what adapshot_query_attn_batched gives over caches assembled from the same lists
- * (same kernels' arithmetic; parity bar of adapshot_query_attn).  Three launches: the plan of all lists, the
- * attention grid over all items, the merge of the partials (bf16 models with head_dim 128, for which a pool layer
+ * (same kernels' arithmetic; parity bar of adapshot_query_attn).  Three launches (two when the lists equal
+ * the previous call's: the plan is kept for the next layer): the plan of all lists, the attention grid over
+ * all items, the merge of the partials (bf16 models with head_dim 128, for which a pool layer
  * must stay below 4 GiB, ECAPACITY; other shapes run item by item).  Pools registered with ADAPSHOT_KEYS_UNROTATED
  * only (ESTATE otherwise). */
 adapshot_status adapshot_query_attn_pool_batched(adapshot_ctx* ctx, int32_t layer, const int32_t* const* shot_ids,
