@@ -212,6 +212,10 @@ extern "C" adapshot_status adapshot_create(const adapshot_model_desc* desc, adap
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, ctx->device) == hipSuccess && prop.multiProcessorCount > 0)
         ctx->n_cu = prop.multiProcessorCount;
+    // One workgroup per row keeps the memory system busy once there are as many rows as compute units (256 rows of
+    // 128256 logits: 24.4 us in one launch against 26.3 us for chunks + merge; 4096 rows: 303 against 318 us, 6.9 TB/s;
+    // 128 rows: 16.5 against 16.1 us, 48 rows: 14.8 against 10.4 us -- a lone workgroup streams ~40 GB/s).
+    ctx->entropy_rows_min = ctx->n_cu;
 
     // RoPE tables in fp64, rounded once to fp32.
     const int half = desc->head_dim / 2;
@@ -1309,10 +1313,16 @@ static adapshot_status run_probe_entropy(adapshot_ctx* ctx, const float* logits,
         ctx->last_error.clear();
         return ADAPSHOT_OK;
     }
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (n_rows >= ctx->entropy_rows_min && vocab >= 16384) {  // enough rows of at least one full step for one workgroup each: one launch, no partials
+        hipError_t e1 = timed_launch(ctx, ADAPSHOT_KERNEL_ENTROPY_CHUNK, stream, [&] { return launch_entropy_rows(p, answer, stream); });
+        if (e1 != hipSuccess) return fail_hip(ctx, "probe_entropy: launch", e1);
+        ctx->last_error.clear();
+        return ADAPSHOT_OK;
+    }
     hipError_t e = ctx->ent_part.reserve((size_t)n_rows * p.n_chunks * 3 * sizeof(float), ctx->retired);
     if (e != hipSuccess) return fail_hip(ctx, "probe_entropy: workspace", e);
     p.partials = (float*)ctx->ent_part.p;
-    hipStream_t stream = (hipStream_t)hip_stream;
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ENTROPY_CHUNK, stream, [&] { return launch_entropy_chunk(p, stream); });
     if (e == hipSuccess)
         e = timed_launch(ctx, ADAPSHOT_KERNEL_ENTROPY_FINISH, stream, [&] {

@@ -271,6 +271,8 @@ struct AnswerTokens {
     int32_t id[kMaxAnswerTokens];
 };
 hipError_t launch_entropy_finish_tokens(const EntropyParams& p, const AnswerTokens& c, hipStream_t stream);
+// Whole rows in one launch (one workgroup per row); c == nullptr: the vocabulary-wide entropy.
+hipError_t launch_entropy_rows(const EntropyParams& p, const AnswerTokens* c, hipStream_t stream);
 
 // ---- host-side helpers -----------------------------------------------------------------
 struct DevBuf {
@@ -369,5 +371,6 @@ struct adapshot_ctx {
     int n_cu = 256;
     int32_t assemble_wg_tok = adapshot::kTileTok;  // tokens of a tile per assemble workgroup
     int32_t force_splits = 0;  // adapshot_set_attn_splits: 0 = the planner chooses
+    int32_t entropy_rows_min = 256;  // from this many rows on, probe entropy runs one workgroup per row in one launch
     std::string last_error;
 };

@@ -204,6 +204,128 @@ __global__ __launch_bounds__(256) void entropy_chunk_kernel(EntropyParams p) {
     }
 }
 
+// Whole rows in one launch: a workgroup of 1024 threads reduces one row and writes its entropy (or, with answer
+// tokens, Eq. (entropy) over those) itself.  The same per-thread stream and merge as the chunk kernel; used when
+// there are enough rows to keep the memory system busy with one workgroup per row, which saves the second launch.
+template <bool VEC, bool TOKENS>
+__global__ __launch_bounds__(1024) void entropy_row_kernel(EntropyParams p, AnswerTokens c) {
+    __shared__ Mst red[16];
+    const int tid = threadIdx.x;
+    const int row = blockIdx.x;
+    const float* z = p.logits + (int64_t)row * p.row_stride;
+    const int c1 = p.vocab;
+    Mst acc = {-INFINITY, 0.f, 0.f};
+    if (VEC) {
+        auto load_full = [&](int base, float (&v)[16]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const f32x4 x = __builtin_nontemporal_load((const f32x4*)(z + base + u * 4096 + tid * 4));
+#pragma unroll
+                for (int k = 0; k < 4; ++k) v[4 * u + k] = x[k];
+            }
+        };
+        // one step (16384 logits) ahead; more in flight does not help a lone workgroup (a compute unit alone sustains
+        // about 40 GB/s: 12.8 us for a 513 KB row, 14.5 us with three steps in flight)
+        int base = 0;
+        if (base + 16384 <= c1) {
+            float cur[16];
+            load_full(base, cur);
+            base += 16384;
+            while (base + 16384 <= c1) {
+                float nxt[16];
+                load_full(base, nxt);
+                base += 16384;
+                mst_add_batch<16>(acc, cur);
+#pragma unroll
+                for (int k = 0; k < 16; ++k) cur[k] = nxt[k];
+            }
+            mst_add_batch<16>(acc, cur);
+        }
+        for (; base < c1; base += 16384) {
+            float v[16];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + u * 4096 + tid * 4;
+                f32x4 x = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+                if (i + 3 < c1) {
+                    x = __builtin_nontemporal_load((const f32x4*)(z + i));
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        if (i + k < c1) x[k] = z[i + k];
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) v[4 * u + k] = x[k];
+            }
+            mst_add_batch<16>(acc, v);
+        }
+    } else {
+        for (int base = 0; base < c1; base += 4096) {
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + u * 1024 + tid;
+                v[u] = i < c1 ? z[i] : -INFINITY;
+            }
+            mst_add_batch<4>(acc, v);
+        }
+    }
+    acc = mst_wave_reduce(acc);
+    if ((tid & 63) == 0) red[tid >> 6] = acc;
+    __syncthreads();
+    if (tid >= 64) return;
+    const int lane = tid;
+    Mst r = {-INFINITY, 0.f, 0.f};
+    if (lane < 16) r = red[lane];
+    r = mst_wave_reduce(r);
+    if (!TOKENS) {
+        if (lane == 0) {
+            float h;
+            if (r.m == -INFINITY || r.m == INFINITY) h = NAN;  // no finite logit, or a +inf logit
+            else h = logf(r.s) - r.t / r.s;                   // NaN sums propagate
+            p.out[row] = h;
+        }
+        return;
+    }
+    // Eq. (entropy) over the answer tokens, as in entropy_finish_tokens_kernel
+    const bool row_bad = r.m == -INFINITY || r.m == INFINITY || r.s != r.s;
+    const float zc = lane < c.n ? z[c.id[lane]] : -INFINITY;
+    float lse;
+    if (c.mode == ADAPSHOT_ENTROPY_FULL_P) {
+        lse = r.m + logf(r.s);
+    } else {
+        float mc = zc;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mc = fmaxf(mc, __shfl_xor(mc, o, 64));
+        float sc = mc == -INFINITY ? 0.f : expf(zc - mc);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sc += __shfl_xor(sc, o, 64);
+        lse = mc + logf(sc);
+        if (mc == -INFINITY) lse = NAN;
+    }
+    const float lp = zc - lse;
+    const float pc = expf(lp);
+    float h = (lane < c.n && pc > 0.f) ? -pc * lp : 0.f;
+    if (lse != lse) h = NAN;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) h += __shfl_xor(h, o, 64);
+    if (lane == 0) p.out[row] = row_bad ? NAN : h;
+}
+
+hipError_t launch_entropy_rows(const EntropyParams& p, const AnswerTokens* c, hipStream_t stream) {
+    const bool vec = (((uintptr_t)p.logits & 15u) == 0) && (p.row_stride % 4 == 0);
+    const dim3 grid((unsigned)p.n_rows);
+    const AnswerTokens none{};
+    if (c) {
+        if (vec) launch_kernel((entropy_row_kernel<true, true>), grid, dim3(1024), stream, p, *c);
+        else launch_kernel((entropy_row_kernel<false, true>), grid, dim3(1024), stream, p, *c);
+    } else {
+        if (vec) launch_kernel((entropy_row_kernel<true, false>), grid, dim3(1024), stream, p, none);
+        else launch_kernel((entropy_row_kernel<false, false>), grid, dim3(1024), stream, p, none);
+    }
+    return hipGetLastError();
+}
+
 // One wavefront per row merges its chunk partials and writes H.
 __global__ __launch_bounds__(64) void entropy_finish_kernel(EntropyParams p) {
     const int row = blockIdx.x;

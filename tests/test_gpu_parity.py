@@ -161,6 +161,30 @@ def test_entropy_shapes(ad, oracle_mod, rows, vocab):
     _entropy_case(ad, oracle_mod, z)
 
 
+@pytest.mark.parametrize("rows,vocab", [(256, 128256), (300, 16387), (512, 16389), (257, 16384), (700, 40000)])
+def test_entropy_many_rows_one_workgroup_per_row(ad, oracle_mod, rows, vocab):
+    """From as many rows as the GPU has compute units on, a row is reduced by one workgroup in one launch: full
+    steps, ragged tails, unaligned rows, degenerate rows and the answer-token epilogue on that path."""
+    g = torch.Generator(device="cuda"); g.manual_seed(rows * 7919 + vocab)
+    z = torch.randn(rows, vocab, device="cuda", generator=g) * 3.0
+    z[1] = -float("inf"); z[1, vocab - 1] = 2.0       # single finite logit: H = 0
+    z[2, vocab // 2] = float("nan")
+    z[3, 0] = float("inf")
+    z[4] = -float("inf")
+    z[5, : vocab // 3] = -float("inf")
+    got, want = _entropy_case(ad, oracle_mod, z)
+    assert got[1] == 0.0
+    _entropy_case(ad, oracle_mod, z[:, 1:vocab - 2])   # base pointer off by 4 bytes, stride > vocab
+    ctx = ad.Context(1, 4, 2, 64, 1.0e4, ad.F32)
+    ids = [0, vocab - 1, vocab // 2, 7]
+    zz = z[6:]                                         # rows without planted infinities
+    for mode in (0, 1):
+        got = ctx.probe_entropy_tokens(zz, ids, mode).cpu().numpy().astype(np.float64)
+        want = oracle_mod.entropy_subset(zz.cpu().numpy(), ids, mode)
+        assert np.all(np.isfinite(want)) and float(np.abs(got - want).max()) < 1e-4
+    ctx.close()
+
+
 def test_entropy_strided_and_unaligned_rows(ad, oracle_mod):
     g = torch.Generator(device="cuda"); g.manual_seed(5)
     big = torch.randn(6, 5003, device="cuda", generator=g)
