@@ -234,7 +234,7 @@ def extras(ad, dev) -> dict:
         it = iter(range(10 ** 9))
         dt = wall(lambda: ctx.probe_entropy(views[next(it) % 8], out=ho), 20)
         ent[str(rows)] = {"us": dt * 1e6, "gbps": rows * w.vocab * 4 / dt * 1e-9}
-    out["probe_entropy_by_rows"] = {"workload": f"{w.vocab}-way fp32 logits, wall clock per call (two kernels)", **ent}
+    out["probe_entropy_by_rows"] = {"workload": f"{w.vocab}-way fp32 logits, wall clock per call (chunks + merge; one launch from 256 rows on)", **ent}
     ctx.close()
     del big, views
     torch.cuda.empty_cache()
