@@ -796,12 +796,26 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
             }
         }
     }
+    // Few rows per kv head and every context read by one item only: the launch streams its tiles.
+    bool stream_tiles = pool == nullptr;
+    if (stream_tiles) {
+        std::vector<int32_t> seen;
+        seen.reserve((size_t)n_items);
+        for (int32_t i = 0; i < n_items && stream_tiles; ++i) {
+            if ((int64_t)items[i].t_q * g > kAttnStreamRows) stream_tiles = false;
+            if (items[i].n_ctx > 0) seen.push_back(items[i].cache_index);
+        }
+        if (stream_tiles) {
+            std::sort(seen.begin(), seen.end());
+            stream_tiles = std::adjacent_find(seen.begin(), seen.end()) == seen.end();
+        }
+    }
     if (!ctx->batch_key.empty() && key == ctx->batch_key) {
         const AttnBatchItem* dit = (const AttnBatchItem*)ctx->batch_tab.p;
         const AttnWork* daw = (const AttnWork*)((const char*)ctx->batch_tab.p + ctx->batch_attn_off);
         const CombineWork* dcw = (const CombineWork*)((const char*)ctx->batch_tab.p + ctx->batch_comb_off);
         hipError_t e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream, [&] {
-            return launch_attn_mfma_batched(dit, daw, (int)ctx->batch_n_attn, pool != nullptr, layer, stream);
+            return launch_attn_mfma_batched(dit, daw, (int)ctx->batch_n_attn, pool != nullptr, stream_tiles, layer, stream);
         });
         if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: attention launch", e);
         e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream,
@@ -952,7 +966,7 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
     const AttnWork* daw = (const AttnWork*)((const char*)ctx->batch_tab.p + attn_off);
     const CombineWork* dcw = (const CombineWork*)((const char*)ctx->batch_tab.p + comb_off);
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN, stream,
-                     [&] { return launch_attn_mfma_batched(dit, daw, (int)n_attn, pool != nullptr, layer, stream); });
+                     [&] { return launch_attn_mfma_batched(dit, daw, (int)n_attn, pool != nullptr, stream_tiles, layer, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: attention launch", e);
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream,
                      [&] { return launch_attn_combine_batched(dit, dcw, (int)n_comb, d.dtype, stream); });

@@ -154,6 +154,10 @@ struct AttnParams {
     int64_t layer_stride_bytes;
 };
 constexpr int kAttnRowTile = 256;  // query rows per workgroup of the MFMA kernel
+// With at most this many rows per kv head half of a workgroup's wavefronts only move tiles and the launch is bound
+// by the memory path, not by the matrix cores: its tile loads are then marked non-temporal (when no other workgroup
+// reads the same tiles).
+constexpr int kAttnStreamRows = 128;
 struct GenericPool {  // zero-copy form of the generic kernel; slot_src == nullptr: the context is an assembled cache
     const int32_t* slot_src;
     const float2* tab_lo;
@@ -197,8 +201,9 @@ struct CombineWork {  // one workgroup of the batched combine kernel: 16 (kv hea
 // Tables written by the host into pinned memory are brought to device memory by a kernel (a DMA copy
 // between two kernels of a stream costs more than the copy itself).  bytes is a multiple of 16.
 hipError_t launch_copy_table(void* dst, const void* src_pinned, size_t bytes, hipStream_t stream);
-hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, bool pool, int layer,
-                                    hipStream_t stream);
+// stream_tiles: no two items read the same context and none has more than kAttnStreamRows rows per kv head
+hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, bool pool,
+                                    bool stream_tiles, int layer, hipStream_t stream);
 hipError_t launch_attn_combine_batched(const AttnBatchItem* items, const CombineWork* work, int n_work, int dtype,
                                        hipStream_t stream);
 
