@@ -206,3 +206,53 @@ def test_batch_tables_kept_for_the_next_layer_give_the_same_bits(ad):
         call(2, packed)
         assert same(items, fresh(2, items, zero_copy))
     ctx.close()
+
+
+def test_streamed_tile_loads_give_the_same_bits(ad):
+    """A batch whose items have few rows per kv head and contexts of their own reads its K/V tiles with the
+    non-temporal cache policy; one more item on a cache that is already in the batch switches the launch back to the
+    default policy.  The policy is not arithmetic: with the split length pinned, the items the two batches share
+    must come out bit-identical."""
+    w = wl.WORKLOADS["llama8b_sweep"]
+    k_pool, v_pool, off = wl.make_pool(w, "cuda", n_layers=1)
+    ctx = ad.Context.for_workload(w, n_layers=1)
+    ctx.pool_register(k_pool, v_pool, off)
+    lists = []
+    for qi in range(2):
+        ids, order = wl.selection(w, query=qi)
+        lists.append((ids[:30 + 9 * qi], np.argsort(np.argsort(order[:30 + 9 * qi])).astype(np.int32)))
+    totals = [int(sum(off[i + 1] - off[i] for i in ids)) for ids, _ in lists]
+    caches = [ad.Cache(ctx, t, with_index=False) for t in totals]
+    ctx.assemble_batched(caches, [l[0] for l in lists], [l[1] for l in lists])
+    g = torch.Generator(device="cuda")
+    g.manual_seed(2718)
+    rows_limit = 128 // (w.n_q_heads // w.n_kv_heads)  # query tokens that still make a streaming launch
+
+    def item(ci, n_ctx, t_q):
+        q = torch.randn(t_q, w.n_q_heads, w.head_dim, device="cuda", generator=g).bfloat16()
+        ks = torch.randn(t_q, w.n_kv_heads, w.head_dim, device="cuda", generator=g).bfloat16()
+        vs = torch.randn(t_q, w.n_kv_heads, w.head_dim, device="cuda", generator=g).bfloat16()
+        return (ci, n_ctx, q, ks, vs, n_ctx, torch.empty_like(q))
+
+    shared = [item(0, totals[0], 1), item(1, totals[1] - 37, rows_limit)]
+    extra = item(0, totals[0] // 2, 3)
+    ctx.set_attn_splits(3)  # the longest item is the same in both batches, so every shared item gets the same splits
+    ctx.query_attn_batched(caches, 0, shared)
+    torch.cuda.synchronize()
+    streamed = [it[6].clone() for it in shared]
+    for it in shared:
+        it[6].zero_()
+    ctx.query_attn_batched(caches, 0, shared + [extra])
+    torch.cuda.synchronize()
+    for a, it in zip(streamed, shared):
+        assert torch.isfinite(a.float()).all() and float(a.float().abs().max()) > 0
+        assert torch.equal(a.view(torch.int16), it[6].view(torch.int16))
+    # the single call of such a problem streams too; it runs another instantiation (its rows are rotated by a launch
+    # of their own), so it agrees to rounding, not bit for bit
+    _, n_ctx, q, ks, vs, qp, _ = shared[1]
+    ctx.set_attn_splits(0)
+    one = ctx.query_attn(caches[1], 0, n_ctx, q, ks, vs, qp)
+    torch.cuda.synchronize()
+    ref = streamed[1].float()
+    assert float((one.float() - ref).abs().max()) <= 2.0 ** -6 * max(1.0, float(ref.abs().max()))
+    ctx.close()
