@@ -427,8 +427,12 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
                 issue_rot(2);
             }
         } else {
+            // the second tile is requested with the first: the memory system is idle at this point, and the first
+            // two tiles then run without waiting for a round trip that only started after the first barrier
             issue_k(0);
             issue_v(0);
+            issue_k(1);
+            issue_v(1);
         }
     }
 
@@ -643,11 +647,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
         issue_v((b + 3) & 3);  // V(t+3)
     };
 
-    // ---- prologue: K(0), V(0) and the Q fragments have landed.  The Q registers pass through the wait
-    // statement so that the compiler places no counter wait of its own after the loads below, which it
-    // cannot see (it would drain them).  Then the rest of the pipeline starts: K(1) V(1) K(2) V(2) K(3),
-    // in the order the tiles are needed, so that "all but the youngest four loads" covers K(t+1) and
-    // V(t+1) at the end of every tile t from the first one on.
+    // ---- prologue: the first two tiles (the zero-copy form: K(0) V(0) K(1)) and the Q fragments have landed.
+    // The Q registers pass through the wait statement so that the compiler places no counter wait of its own
+    // after the loads below, which it cannot see (it would drain them).  Then the rest of the pipeline starts:
+    // K(2) V(2) K(3), in the order the tiles are needed, so that "all but the youngest four loads" covers K(t+1)
+    // and V(t+1) at the end of every tile t from the first one on.
     asm volatile("s_waitcnt vmcnt(0)"
                  : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3]), "+v"(qf[4]), "+v"(qf[5]), "+v"(qf[6]), "+v"(qf[7])
                  :
@@ -775,8 +779,6 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
             pv_phase(0, vo_prev);
         }
     } else {
-    issue_k(1);
-    issue_v(1);
     issue_k(2);
     issue_v(2);
     issue_k(3);
