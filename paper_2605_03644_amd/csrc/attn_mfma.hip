@@ -184,7 +184,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     constexpr int kIdxSlots = 8, kRotSlots = 4;
     constexpr int kLoBytes = WAVES * 64 * 64;
     constexpr int kPoolBytes = POOL ? (kIdxSlots + kRotSlots) * 1024 + kLoBytes : 0;
-    __shared__ __attribute__((aligned(65536))) char lds_all[(kNBuf + kVBuf) * kTileBytes + kPoolBytes];
+    // The plain form adds 4 KB per wavefront through which the partial rows leave (the zero-copy form reuses its
+    // threads' table entries for that).
+    constexpr int kStageBytes = POOL ? 0 : WAVES * 4096;
+    __shared__ __attribute__((aligned(65536))) char lds_all[(kNBuf + kVBuf) * kTileBytes + kPoolBytes + kStageBytes];
+    static_assert(sizeof(lds_all) <= 160 * 1024, "LDS of a compute unit");
     char (*const k_s)[kTileBytes] = (char (*)[kTileBytes])lds_all;
     char (*const v_s)[kTileBytes] = (char (*)[kTileBytes])(lds_all + kNBuf * kTileBytes);
     char* const idx_s = lds_all + (kNBuf + kVBuf) * kTileBytes;
@@ -838,19 +842,42 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     amax = max_xhalf(amax);
     const bool some = amax > 0.f && amax < INFINITY;  // all-zero row (or overflow): plain scale 1
     const float scale = some ? 1.0f / amax : 1.0f;
-    if (row[0] < rows) {
-        typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
-        const int64_t pr = ((int64_t)split * p.n_kv_heads + hk) * rows + row[0];
-        if (hh == 0) p.part_mlf[pr] = make_float4(m_run, l_tot, some ? amax : 1.0f, 0.f);
-        _Float16* orow = (_Float16*)p.part_o + pr * kD;
+    if (row[0] < rows && hh == 0)
+        p.part_mlf[((int64_t)split * p.n_kv_heads + hk) * rows + row[0]] = make_float4(m_run, l_tot, some ? amax : 1.0f, 0.f);
+    // The rows leave through 4 KB of LDS that only this wavefront touches, half a row (64 columns) at a time: a lane
+    // holds 4 consecutive columns of its row per register quad, and stored from there every instruction would write
+    // 8 bytes to each of 32 rows (the write-out took 3.4 of the kernel's 57 us at the headline size, 2.6 of them
+    // for that); read back row-wise, an instruction writes 128 contiguous bytes of each of eight rows.  Row r of
+    // the piece is 128 bytes whose 16-byte slots are permuted by (r / 2) % 8, which spreads both directions over
+    // the banks.  The plain form has the space to spare; the zero-copy form reuses the wavefront's share of the
+    // second-level table entries (four 1 KB pieces, one per plane), which the key loop is done with.
+    typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+    auto stage_row = [&](int r) __attribute__((always_inline)) -> char* {
+        if (POOL) return lo_s + (r >> 3) * (WAVES * 64 * 16) + wave * 1024 + (r & 7) * 128;
+        return lds_all + (kNBuf + kVBuf) * kTileBytes + kPoolBytes + wave * 4096 + r * 128;
+    };
+    const int row0 = row_tile * kAttnRowTile + wave * NR * 32;  // first row of this wavefront
+    char* const obase = (char*)p.part_o + ((((int64_t)split * p.n_kv_heads + hk) * rows + row0) * kD) * 2;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+    for (int half = 0; half < 2; ++half) {
+#pragma unroll
+        for (int dbl = 0; dbl < 2; ++dbl)
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
+                const int db = 2 * half + dbl;
                 const f32x4 w = {o[db][4 * rq] * scale, o[db][4 * rq + 1] * scale, o[db][4 * rq + 2] * scale,
                                  o[db][4 * rq + 3] * scale};
-                *(f16x4*)(orow + 32 * db + 8 * rq + 4 * hh) = __builtin_convertvector(w, f16x4);
+                const int slot = (4 * dbl + rq) ^ ((l32 >> 1) & 7);
+                *(f16x4*)(stage_row(l32) + slot * 16 + hh * 8) = __builtin_convertvector(w, f16x4);
             }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // written by other lanes of the wavefront, read below
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = 8 * j + (lane >> 3), sl = lane & 7;
+            const u32x4 v = *(const u32x4*)(stage_row(r) + ((sl ^ ((r >> 1) & 7)) << 4));
+            if (row0 + r < rows) *(u32x4*)(obase + (int64_t)r * (kD * 2) + half * 128 + sl * 16) = v;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // read before the second half overwrites the piece
     }
 }
 
