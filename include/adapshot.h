@@ -145,7 +145,8 @@ adapshot_status adapshot_assemble(adapshot_ctx* ctx, adapshot_cache* cache, cons
  * 2e-2 (max-abs) of the exact result; keys three times as large were measured at 1.9e-2, eight times
  * as large at 6e-2.  Accumulation, maxima and sums are fp32 throughout.
  * Errors, all found before anything is launched (out is then untouched): EINVAL (null or
- * misaligned pointer, t_q < 1, layer out of range, n_ctx < 0, q_pos0 < 0), ESTATE (n_ctx beyond
+ * misaligned pointer, t_q < 1, layer out of range, n_ctx < 0, q_pos0 < 0, a q of 2 GiB or more, or a
+ * context or query whose K/V rows span more than 4 GiB in one layer), ESTATE (n_ctx beyond
  * cache->len), ECAPACITY (q_pos0 + t_q beyond max_position). */
 adapshot_status adapshot_query_attn(adapshot_ctx* ctx, const adapshot_cache* cache, int32_t layer,
                                     int64_t n_ctx, const void* q, const void* k_self,

@@ -525,6 +525,9 @@ static adapshot_status check_query_attn(adapshot_ctx* ctx, const adapshot_cache*
 
     if ((uint64_t)std::max<int64_t>(n_ctx, t_q) * (uint64_t)ctx->row_bytes > 0xffffffffull)
         return fail(ctx, ADAPSHOT_EINVAL, "query_attn: context rows span more than 4 GiB per layer");
+    // the kernels address a query row by a 32-bit byte offset
+    if ((uint64_t)t_q * (uint64_t)ctx->desc.n_q_heads * (uint64_t)ctx->desc.head_dim * (uint64_t)ctx->elem_bytes > 0x7fffffffull)
+        return fail(ctx, ADAPSHOT_EINVAL, "query_attn: query rows span 2 GiB or more");
     return ADAPSHOT_OK;
 }
 
@@ -1027,6 +1030,8 @@ extern "C" adapshot_status adapshot_query_attn_pool(adapshot_ctx* ctx, int32_t l
         ((uint64_t)ctx->shot_offsets[(size_t)ctx->n_shots] * (uint64_t)ctx->row_bytes > 0xffffffffull ||
          (uint64_t)std::max<int64_t>(total, t_q) * (uint64_t)ctx->row_bytes > 0xffffffffull))
         return fail(ctx, ADAPSHOT_ECAPACITY, "query_attn_pool: a pool layer of 4 GiB or more is not supported");
+    if ((uint64_t)t_q * (uint64_t)d.n_q_heads * (uint64_t)d.head_dim * (uint64_t)ctx->elem_bytes > 0x7fffffffull)
+        return fail(ctx, ADAPSHOT_EINVAL, "query_attn_pool: query rows span 2 GiB or more");
     hipStream_t stream = (hipStream_t)hip_stream;
     const int64_t layer_off = (int64_t)layer * ctx->pool_layer_stride_tokens * ctx->row_bytes;
     const char* k_layer = (const char*)ctx->k_pool + layer_off;

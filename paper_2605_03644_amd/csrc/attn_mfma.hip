@@ -471,20 +471,36 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     // ---- Q fragments (B operand): lane holds row l32, d = 16*kk + 8*hh .. +7.  Fragments kk and kk + 4 hold
     // rotation partners (d, d + 64), so a lane rotates its own row to position q_pos0 + j and folds the
     // softmax scale in, without another pass over Q in memory.
+    // The wavefront's 32 rows come whole through LDS: 8 KB of the tile ring that no tile uses before the first
+    // barrier, filled by the direct-to-LDS path 4 rows (1 KB of whole 256-byte rows) per instruction, 16-byte
+    // pieces permuted by the row number like the K tiles'.  Read straight from memory a fragment is 32 bytes of
+    // each of 32 rows per instruction, and with every context split of a query fetching the same rows at the
+    // same moment that cost 2 % of the kernel at the headline size.  Rows past the last one stand for it.
     bf16x8 qf[8];
     {
         AttnFold f{};
         if (FOLD) f = fold();
         const bool valid = row[0] < rows;
         const int j = valid ? jrow[0] : 0;
-        const int gq = valid ? row[0] - j * g : 0;
-        const char* qrow = (const char*)(FOLD ? f.q_raw : p.q_rot) + ((int64_t)(j * p.n_q_heads + hk * g + gq) * kD) * 2;
+        const char* qbase = (const char*)(FOLD ? f.q_raw : p.q_rot);
+        const int r_last = rows - 1, j_last = r_last / g;
+        const int jc = valid ? j : j_last, gc = valid ? row[0] - j * g : r_last - j_last * g;
+        const unsigned qoff = (unsigned)(((jc * p.n_q_heads + hk * g + gc) * kD) * 2);  // the host keeps Q below 2 GiB
+        char* const qst = wave < WAVES / 2 ? k_s[2] + wave * 8192 : v_s[kVBuf - 2] + (wave - WAVES / 2) * 8192;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int rl = 4 * i + (lane >> 4);  // row of the wavefront that this lane fetches a piece of
+            const unsigned off_r = (unsigned)__builtin_amdgcn_ds_bpermute(rl * 4, (int)qoff);
+            load_lds_16(qbase, off_r + (((lane & 15) ^ (rl & 15)) << 4),
+                        __builtin_amdgcn_readfirstlane(lds_addr(qst + i * 1024)));
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // these rows, and the first tiles requested above
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             u32x4 x1 = {0u, 0u, 0u, 0u}, x2 = {0u, 0u, 0u, 0u};
             if (valid) {
-                x1 = *(const u32x4*)(qrow + (16 * kk + 8 * hh) * 2);
-                x2 = *(const u32x4*)(qrow + (16 * (kk + 4) + 8 * hh) * 2);
+                x1 = *(const u32x4*)(qst + l32 * 256 + (((2 * kk + hh) ^ (l32 & 15)) << 4));
+                x2 = *(const u32x4*)(qst + l32 * 256 + (((2 * (kk + 4) + hh) ^ (l32 & 15)) << 4));
                 if (FOLD) {
                     float c[8], sn[8];
                     cos_sin8(f, f.q_pos0 + j, 16 * kk + 8 * hh, c, sn);
@@ -651,7 +667,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
         issue_v((b + 3) & 3);  // V(t+3)
     };
 
-    // ---- prologue: the first two tiles (the zero-copy form: K(0) V(0) K(1)) and the Q fragments have landed.
+    // ---- prologue: the first two tiles (the zero-copy form: K(0) V(0) K(1)) have landed and the Q fragments
+    // are in registers (every wavefront has read its rows out of the ring buffers that the loads below fill).
     // The Q registers pass through the wait statement so that the compiler places no counter wait of its own
     // after the loads below, which it cannot see (it would drain them).  Then the rest of the pipeline starts:
     // K(2) V(2) K(3), in the order the tiles are needed, so that "all but the youngest four loads" covers K(t+1)
