@@ -875,10 +875,12 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
     };
     const int row0 = row_tile * kAttnRowTile + wave * NR * 32;  // first row of this wavefront
     char* const obase = (char*)p.part_o + ((((int64_t)split * p.n_kv_heads + hk) * rows + row0) * kD) * 2;
+    // (ranking's one block of columns: the first 64 bytes of every row are written and read, nothing else)
+    constexpr int kHalves = PVB == 1 ? 1 : 2, kBlocks = PVB == 1 ? 1 : 2, kSlots = PVB == 1 ? 4 : 8;
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
+    for (int half = 0; half < kHalves; ++half) {
 #pragma unroll
-        for (int dbl = 0; dbl < 2; ++dbl)
+        for (int dbl = 0; dbl < kBlocks; ++dbl)
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
                 const int db = 2 * half + dbl;
@@ -892,7 +894,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg,
         for (int j = 0; j < 4; ++j) {
             const int r = 8 * j + (lane >> 3), sl = lane & 7;
             const u32x4 v = *(const u32x4*)(stage_row(r) + ((sl ^ ((r >> 1) & 7)) << 4));
-            if (row0 + r < rows) *(u32x4*)(obase + (int64_t)r * (kD * 2) + half * 128 + sl * 16) = v;
+            if (row0 + r < rows && sl < kSlots) *(u32x4*)(obase + (int64_t)r * (kD * 2) + half * 128 + sl * 16) = v;
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // read before the second half overwrites the piece
     }

@@ -102,35 +102,36 @@ __global__ __launch_bounds__(256) void rank_weights_kernel(RankReduceParams p) {
         }
 }
 
-// grid = (n_split, ceil(n_pairs / 256)); 256 threads = 16 row groups x 16 lanes, a lane owning 8 shot slots
-// (16 bytes of a partial row; head_dim 128).  Row group rg takes rows pair0 + rg, + 16, ...; the 16 partial
-// sums of a slot meet in LDS and leave as block_part[window][row block][slot].
+// grid = (n_split, ceil(n_pairs / 256)); 256 threads = 64 row groups x 4 lanes, a lane owning 8 shot slots
+// (16 bytes of a partial row: a window holds at most 32 shots, so only the first 32 of a row's 128 columns
+// carry data, and the attention kernel writes only those).  Row group rg takes rows pair0 + rg, + 64, ...;
+// the 64 partial sums of a slot meet in LDS and leave as block_part[window][row block][slot].
 __global__ __launch_bounds__(256) void rank_reduce_kernel(RankReduceParams p) {
     typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-    __shared__ float red[16][129];
+    __shared__ float red[64][33];
     const int s = blockIdx.x;
-    const int lane16 = threadIdx.x & 15, rg = threadIdx.x >> 4;
+    const int lane4 = threadIdx.x & 3, rg = threadIdx.x >> 2;
     const int shot0 = p.split_shot0[s];
     const int n_here = p.split_shot0[s + 1] - shot0;
     const int64_t pair0 = (int64_t)blockIdx.y * 256;
     const int64_t pair1 = pair0 + 256 < p.n_pairs ? pair0 + 256 : p.n_pairs;
-    const _Float16* o = (const _Float16*)p.part_o + ((int64_t)s * p.n_pairs) * 128 + lane16 * 8;
+    const _Float16* o = (const _Float16*)p.part_o + ((int64_t)s * p.n_pairs) * 128 + lane4 * 8;
     const float* w = p.weights + (int64_t)s * p.n_pairs;
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int64_t r = pair0 + rg; r < pair1; r += 16) {
+    for (int64_t r = pair0 + rg; r < pair1; r += 64) {
         const f16x8 v = __builtin_nontemporal_load((const f16x8*)(o + r * 128));
         const float wr = w[r];
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] += wr * (float)v[i];
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) red[rg][lane16 * 8 + i] = acc[i];
+    for (int i = 0; i < 8; ++i) red[rg][lane4 * 8 + i] = acc[i];
     __syncthreads();
     const int c = threadIdx.x;
-    if (c < 128 && c < n_here) {
+    if (c < 32 && c < n_here) {
         float t = 0.f;
 #pragma unroll
-        for (int g = 0; g < 16; ++g) t += red[g][c];
+        for (int g = 0; g < 64; ++g) t += red[g][c];
         p.block_part[((int64_t)s * gridDim.y + blockIdx.y) * 128 + c] = t;
     }
 }
