@@ -3,6 +3,7 @@ seeded inputs.  Bars: indexing bit-exact; fp32 re-encode 1e-5 relative per rotat
 bf16 keys >= 99 % identical to the oracle's rounding and each within
 half a bf16 spacing + 1e-5 relative of the exact key; attention 2e-2 max-abs and
 1e-2 relative Frobenius (bf16), 1e-4 / 1e-5 (fp32 path); entropy 1e-4."""
+import ctypes
 import math
 
 import numpy as np
@@ -460,6 +461,15 @@ def test_attention_entropy_and_ranking_errors_launch_nothing(ad):
     bad(ad.ECAPACITY, q_pos0=4096 - 4)       # the query's positions run past max_position
     bad(ad.EINVAL, q_pos0=-1)
     bad(ad.EINVAL, q=q.view(-1)[1:1 + 7 * q.shape[1] * q.shape[2]].view(7, q.shape[1], q.shape[2]))  # not 16-byte aligned
+    # a query of 2 GiB or more (the kernels address its rows by 32-bit offsets); found from the sizes alone
+    ctx2 = ad.Context.for_workload(w, n_layers=1, max_position=1 << 20)
+    cache2 = ad.Cache(ctx2, 64)
+    t_big = (1 << 31) // (w.n_q_heads * w.head_dim * 2) + 1
+    with pytest.raises(ad.AdapshotError) as e:
+        ctx2._check(ctx2.lib.adapshot_query_attn(ctx2._h, ctypes.byref(cache2.c), 0, 0, q.data_ptr(), ks.data_ptr(),
+                                                 vs.data_ptr(), t_big, 0, out.data_ptr(), None))
+    assert e.value.status == ad.EINVAL and "2 GiB" in e.value.message
+    ctx2.close()
     # a batch with one bad item among good ones launches nothing at all
     outs = [torch.full_like(q, 7.0) for _ in range(3)]
     items = [(0, n, q, ks, vs, n, outs[0]), (0, n + 1, q, ks, vs, n, outs[1]), (0, n // 2, q, ks, vs, n // 2, outs[2])]
