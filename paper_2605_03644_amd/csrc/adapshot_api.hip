@@ -623,7 +623,7 @@ static adapshot_status run_query_attn_on(adapshot_ctx* ctx, const void* k_ctx, c
 
     const size_t esz = (size_t)ctx->elem_bytes;
     hipError_t e = hipSuccess;
-    const bool fold = slot_src != nullptr && mfma;  // the matrix-core zero-copy kernel rotates its rows itself
+    const bool fold = mfma;  // the matrix-core kernels rotate the query rows (and the query's own keys) themselves
     if (!fold) {
         e = ctx->q_rot.reserve((size_t)t_q * d.n_q_heads * d.head_dim * esz, ctx->retired);
         if (e == hipSuccess) e = ctx->k_rot.reserve((size_t)t_q * d.n_kv_heads * d.head_dim * esz, ctx->retired);

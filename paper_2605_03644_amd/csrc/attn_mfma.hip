@@ -165,9 +165,9 @@ __device__ __forceinline__ T load_uniform(const T* ptr) {
 // time to land instead of two).  What a context split computes is what the plain form computes over the
 // assembled cache.
 // FOLD: the workgroup rotates its query rows (and the self split its keys) itself; otherwise rope_rows has
-// done that in a launch of its own and the kernel reads q_rot / k_self_rot.  Folding saves the launch and is
-// what the batched calls use (decode steps and probes have few rows per kv head); for one query with hundreds of
-// rows per kv head the rotation repeated in every context split costs the kernel more than the launch did.
+// done that in a launch of its own and the kernel reads q_rot / k_self_rot.  Folding saves the launch: at the
+// headline size the rotation repeated in every context split costs the kernel 1.4 us and the launch it replaces
+// cost the step 3 us.  Ranking, whose one block of columns needs no keys of the query, keeps the launch.
 // NT: the K/V tile loads of the plain form carry the non-temporal bit (see load_lds_16).
 template <int WAVES, int NR, bool BATCHED, int PVB, bool POOL, bool FOLD, bool NT = false>
 __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(AttnParams p_arg, AttnFold f_arg,
@@ -911,11 +911,11 @@ hipError_t launch_attn_mfma(const AttnParams& p, const AttnFold& f, hipStream_t 
                       dim3(kAttnWaves * 64), stream, p, f, n_row_tiles, (const AttnBatchItem*)nullptr,
                       (const AttnWork*)nullptr);
     else if (rows <= kAttnStreamRows)  // every tile is read by one workgroup per kv head, which has few rows to feed
-        launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 4, false, false, true>),
+        launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 4, false, true, true>),
                       dim3(blocks), dim3(kAttnWaves * 64), stream, p, f, n_row_tiles, (const AttnBatchItem*)nullptr,
                       (const AttnWork*)nullptr);
     else
-        launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 4, false, false>), dim3(blocks),
+        launch_kernel((attn_mfma_kernel<kAttnWaves, kAttnRowTile / (32 * kAttnWaves), false, 4, false, true>), dim3(blocks),
                       dim3(kAttnWaves * 64), stream, p, f, n_row_tiles, (const AttnBatchItem*)nullptr,
                       (const AttnWork*)nullptr);
     return hipGetLastError();
