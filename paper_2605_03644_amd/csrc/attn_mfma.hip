@@ -38,6 +38,9 @@
 // tiles deep for K and for V, with an XOR swizzle of the 16-byte chunks instead of row padding:
 //   K row r keeps chunk c at position c ^ (r & 15)      (16 rows of a 16-byte read: 16 bank groups)
 //   V row r keeps chunk c at position c ^ ((r & 3) << 2) (4 rows x 64 B of a transposing read: 64 banks)
+// The query rows come in and the partial rows go out through LDS as well, as whole rows: a lane's own share of a
+// row is 32 bytes of a fragment and 8 bytes of an accumulator quad, and memory instructions that touch 32 rows for
+// that little each cost 5 % of the kernel when every workgroup of the grid issues them at the same moment.
 
 #include "adapshot_internal.h"
 
