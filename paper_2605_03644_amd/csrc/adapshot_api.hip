@@ -301,6 +301,25 @@ extern "C" adapshot_status adapshot_pool_register(adapshot_ctx* ctx, const void*
     return ADAPSHOT_OK;
 }
 
+// How the shots of an assemble call are cut into tiles.  Few layers: tiles of kTileTok tokens, and the grid gives every
+// tile kTileTok / wg_tok workgroups (a shot's last tile leaves some of them empty or nearly so, but the list is
+// short: the host plans 49 us per call at the headline size as it is, and a workgroup's first act is to fetch its
+// descriptor from host memory).  Many layers: the host cuts the shots into pieces of wg_tok tokens itself, one
+// workgroup per piece and layer, what is left over of a shot joined to its last piece when the two fit a tile's
+// table -- no empty workgroups and none that runs for a handful of tokens, four times the descriptors, read again by
+// every layer's workgroups (28 layers of the decode caches -5 %, 80 layers of the 70B shape -2 %, the sweep's 32
+// layers 0 to -14 % from process to process; a single layer +5 %, and its planning would overtake the GPU).
+constexpr int kAssemblePieceLayers = 8;
+static inline int64_t assemble_unit(const adapshot_ctx* ctx) {
+    return ctx->desc.n_layers >= kAssemblePieceLayers ? ctx->assemble_wg_tok : kTileTok;
+}
+static inline int64_t shot_tiles(int64_t len, int64_t unit) {
+    if (len <= 0) return 0;
+    const int64_t q = len / unit, r = len - q * unit;
+    if (q == 0) return 1;
+    return r != 0 && unit + r > kTileTok ? q + 1 : q;
+}
+
 // Validation + integer plan totals of one assemble call; nothing is launched or written.
 static adapshot_status check_assemble(adapshot_ctx* ctx, const adapshot_cache* cache, const int32_t* shot_ids,
                                       const int32_t* order, int32_t m, int64_t pos0, int64_t* total_out,
@@ -323,7 +342,7 @@ static adapshot_status check_assemble(adapshot_ctx* ctx, const adapshot_cache* c
         if (s < 0 || s >= ctx->n_shots) return fail(ctx, ADAPSHOT_ESHOT, "assemble: shot id %d out of range", s);
         int64_t len = ctx->shot_offsets[s + 1] - ctx->shot_offsets[s];
         total += len;
-        n_tiles += (len + kTileTok - 1) / kTileTok;
+        n_tiles += shot_tiles(len, assemble_unit(ctx));
     }
     if (cache->len + total > cache->capacity)
         return fail(ctx, ADAPSHOT_ECAPACITY, "assemble: %lld + %lld tokens exceed capacity %lld",
@@ -363,7 +382,8 @@ static adapshot_status run_assemble(adapshot_ctx* ctx, AssembleJob* jobs, int32_
         if (e != hipSuccess) return fail_hip(ctx, "assemble: pinned tile buffer", e);
         TileDesc* tiles = (TileDesc*)host;
         AssembleParams p;
-        int64_t nt = 0;
+        const int64_t unit = assemble_unit(ctx);
+        int64_t nt = 0, n_tok_group = 0;
         for (int32_t b = j0; b < j1; ++b) {
             const AssembleJob& jb = jobs[b];
             AssembleDst& dc = p.dst[b - j0];
@@ -379,18 +399,20 @@ static adapshot_status run_assemble(adapshot_ctx* ctx, AssembleJob* jobs, int32_
             for (int32_t j = 0; j < jb.m; ++j) {
                 const int32_t s = jb.shot_ids[jb.order ? jb.order[j] : j];
                 const int64_t src = ctx->shot_offsets[s], len = ctx->shot_offsets[s + 1] - src;
-                for (int64_t t0 = 0; t0 < len; t0 += kTileTok) {
+                const int64_t n_here = shot_tiles(len, unit);
+                for (int64_t i = 0, t0 = 0; i < n_here; ++i, t0 += unit) {
                     TileDesc& d = tiles[nt++];
                     d.src_tok = (int32_t)(src + t0);
                     d.dst_slot = (int32_t)(slot0 + t0);
                     d.angle0 = (int32_t)(local ? pos0 + slot0 : pos0 + slot0 + t0);
                     d.angle_step = local ? 0 : 1;
-                    d.n_tok = (int32_t)std::min<int64_t>(kTileTok, len - t0);
+                    d.n_tok = (int32_t)(i + 1 == n_here ? len - t0 : unit);  // the last tile takes what is left
                     d.shot = s;
                     d.tok0 = (int32_t)t0;
                     d.cache = b - j0;
                 }
                 slot0 += len;
+                n_tok_group += len;
             }
         }
         for (int32_t i = j1 - j0; i < kAssembleBatch; ++i) p.dst[i] = AssembleDst{};
@@ -401,9 +423,10 @@ static adapshot_status run_assemble(adapshot_ctx* ctx, AssembleJob* jobs, int32_
         p.tab_hi = ctx->tab_hi;
         p.pool_layer_stride_bytes = ctx->pool_layer_stride_tokens * ctx->row_bytes;
         p.n_tiles = (int32_t)nt;
+        p.n_tokens = n_tok_group;
         p.n_layers = ctx->desc.n_layers;
         p.n_dst = j1 - j0;
-        p.wg_tok = ctx->assemble_wg_tok;
+        p.wg_tok = unit == kTileTok ? ctx->assemble_wg_tok : kTileTok;  // pieces cut by the host: one workgroup each
         p.n_kv_heads = ctx->desc.n_kv_heads;
         p.head_dim = ctx->desc.head_dim;
         p.dtype = ctx->desc.dtype;

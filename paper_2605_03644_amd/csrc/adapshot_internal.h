@@ -55,10 +55,12 @@ struct AssembleParams {
     const float2* tab_lo;
     const float2* tab_hi;
     int64_t pool_layer_stride_bytes;
+    int64_t n_tokens;      // tokens of all tiles together
     int32_t n_tiles;
     int32_t n_layers;
     int32_t n_dst;         // caches of this launch (entries of dst in use)
-    int32_t wg_tok;        // tokens of a tile per workgroup: a power of two <= kTileTok (kTileTok / wg_tok workgroups per tile)
+    int32_t wg_tok;        // tokens of a tile per workgroup: a power of two <= kTileTok (kTileTok / wg_tok workgroups per tile;
+                           // kTileTok: the host has cut the shots into one-workgroup tiles already)
     int32_t n_kv_heads;
     int32_t head_dim;
     int32_t dtype;

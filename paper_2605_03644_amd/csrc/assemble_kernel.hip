@@ -213,9 +213,9 @@ __global__ __launch_bounds__(256) void assemble_reencode_kernel(AssembleParams p
 template <int DTYPE, int CH>
 static hipError_t launch_t(const AssembleParams& p, hipStream_t stream) {
     dim3 grid((unsigned)p.n_tiles * (unsigned)(kTileTok / p.wg_tok), (unsigned)p.n_layers, 2);
-    // upper bound of what the launch writes: every tile full, K and V
+    // what the launch writes, K and V
     const int64_t e = DTYPE == ADAPSHOT_BF16 ? 2 : 4;
-    const int64_t written = 2 * (int64_t)p.n_tiles * kTileTok * p.n_kv_heads * p.head_dim * e * p.n_layers;
+    const int64_t written = 2 * p.n_tokens * p.n_kv_heads * p.head_dim * e * p.n_layers;
     if (written > kAssembleStreamBytes)
         launch_kernel((assemble_reencode_kernel<DTYPE, CH, true>), grid, dim3(256), stream, p);
     else

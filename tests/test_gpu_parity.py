@@ -106,6 +106,20 @@ def test_assemble_qwen_shape_bf16_two_layers(ad, oracle_mod):
     _run_assemble_case(ad, oracle_mod, w, 0, 3, [0.3, 0.9], n_layers=2)
 
 
+@pytest.mark.parametrize("key_state", [0, 1])
+def test_assemble_many_layers_host_cut_pieces(ad, oracle_mod, key_state):
+    """From 8 layers on the host cuts every shot into one-workgroup pieces (8 tokens for this row size) and joins
+    what is left over to the last piece: shot lengths 1..70 cover shots shorter than a piece, shots with no
+    remainder and every remainder 1..7; three appends."""
+    import dataclasses
+    w = dataclasses.replace(wl.WORKLOADS["llama8b_1layer"], name="llama8b_pieces", n_layers=8, n_shots=90, len_lo=1,
+                            len_hi=70, m_select=60)
+    lens = wl.shot_lengths(w)
+    assert lens.min() == 1 and lens.max() == 70 and len({int(x) % 8 for x in lens}) == 8
+    r = _run_assemble_case(ad, oracle_mod, w, key_state, 5, [0.2, 0.7])
+    assert r["total"] > 1000
+
+
 def test_assemble_errors_write_nothing(ad):
     w = wl.WORKLOADS["tiny_fp32"]
     k_pool, v_pool, off = wl.make_pool(w, "cuda")
