@@ -845,7 +845,7 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
         });
         if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: attention launch", e);
         e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream,
-                         [&] { return launch_attn_combine_batched(dit, dcw, (int)ctx->batch_n_comb, d.dtype, stream); });
+                         [&] { return launch_attn_combine_batched(dit, dcw, (int)ctx->batch_n_comb, d.dtype, ctx->batch_max_partials, stream); });
         if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: combine launch", e);
         return ADAPSHOT_OK;
     }
@@ -868,6 +868,7 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
     std::vector<Plan> plan((size_t)n_items);
     size_t po_bytes = 0, pml_bytes = 0;
     int64_t n_attn = 0, n_comb = 0;
+    int32_t max_partials = 1;
     for (int32_t i = 0; i < n_items; ++i) {
         const adapshot_attn_item& it = items[i];
         Plan& pl = plan[(size_t)i];
@@ -888,6 +889,7 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
         pl.pml_off = pml_bytes;
         pml_bytes += up((size_t)(pl.n_split + 1) * d.n_kv_heads * pl.rows * sizeof(float4));
         n_attn += d.n_kv_heads * pl.n_row_tiles * (pl.n_split + 1);
+        max_partials = std::max<int32_t>(max_partials, (int32_t)pl.n_split + 1);
         n_comb += (d.n_kv_heads * pl.rows + 15) / 16;
     }
     if (n_attn > INT32_MAX || n_comb > INT32_MAX)
@@ -995,10 +997,11 @@ static adapshot_status run_query_attn_batch(adapshot_ctx* ctx, const adapshot_ca
                      [&] { return launch_attn_mfma_batched(dit, daw, (int)n_attn, pool != nullptr, stream_tiles, layer, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: attention launch", e);
     e = timed_launch(ctx, ADAPSHOT_KERNEL_ATTN_COMBINE, stream,
-                     [&] { return launch_attn_combine_batched(dit, dcw, (int)n_comb, d.dtype, stream); });
+                     [&] { return launch_attn_combine_batched(dit, dcw, (int)n_comb, d.dtype, max_partials, stream); });
     if (e != hipSuccess) return fail_hip(ctx, "query_attn_batched: combine launch", e);
     ctx->batch_key.swap(key);
     ctx->batch_n_attn = n_attn;
+    ctx->batch_max_partials = max_partials;
     ctx->batch_n_comb = n_comb;
     ctx->batch_attn_off = attn_off;
     ctx->batch_comb_off = comb_off;

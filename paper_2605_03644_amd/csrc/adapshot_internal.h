@@ -206,8 +206,9 @@ hipError_t launch_copy_table(void* dst, const void* src_pinned, size_t bytes, hi
 // stream_tiles: no two items read the same context and none has more than kAttnStreamRows rows per kv head
 hipError_t launch_attn_mfma_batched(const AttnBatchItem* items, const AttnWork* work, int n_work, bool pool,
                                     bool stream_tiles, int layer, hipStream_t stream);
+// max_partials: the most partial rows that any item merges per output row (its context splits + 1)
 hipError_t launch_attn_combine_batched(const AttnBatchItem* items, const CombineWork* work, int n_work, int dtype,
-                                       hipStream_t stream);
+                                       int max_partials, hipStream_t stream);
 
 // ---- relevance ranking over the pool (Eq. attention_score) ----------------------------------
 // The query attends over the locally encoded keys of ALL pool tokens at one layer with a one-hot "value"
@@ -363,6 +364,7 @@ struct adapshot_ctx {
     // reuses them instead of planning and uploading again.  Empty = nothing to reuse.
     std::vector<unsigned char> batch_key, pool_key;
     int64_t batch_n_attn = 0, batch_n_comb = 0;
+    int32_t batch_max_partials = 0;
     size_t batch_attn_off = 0, batch_comb_off = 0;
     // ranking state of one pool layer, built on first use
     int32_t rank_layer = -1;

@@ -368,52 +368,67 @@ __device__ __forceinline__ void attn_combine_rows(const AttnParams& p, int64_t p
     }
 }
 
+// One kernel per (row type, head width, splits in flight): the register count follows the splits in flight (16
+// partial rows and their (m, l, f) are 128 registers), and a launch with thousands of workgroups -- the combine of
+// a probe sweep -- lives on how many of them fit a compute unit (one kernel for all forms: 244 registers, two
+// wavefronts per SIMD, 40 us for the sweep's 6144 workgroups).
 // SB splits in flight: 8 when the problem has at most 8 partials per row, else 16 (fp16 rows) or 8 (fp32 rows).
-template <int DTYPE, bool HALF>
-__device__ __forceinline__ void attn_combine_block(const AttnParams& p, int64_t pair0) {
-    const bool wide = p.head_dim > 128;
-    if (HALF && p.n_split + 1 > 8) {
-        if (wide) attn_combine_rows<DTYPE, HALF, 2, 16>(p, pair0);
-        else attn_combine_rows<DTYPE, HALF, 1, 16>(p, pair0);
-    } else {
-        if (wide) attn_combine_rows<DTYPE, HALF, 2, 8>(p, pair0);
-        else attn_combine_rows<DTYPE, HALF, 1, 8>(p, pair0);
-    }
-}
-
-template <int DTYPE>
+template <int DTYPE, bool HALF, int NV, int SB>
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
-    if (p.part_half) attn_combine_block<DTYPE, true>(p, (int64_t)blockIdx.x * 16);
-    else attn_combine_block<DTYPE, false>(p, (int64_t)blockIdx.x * 8);
+    attn_combine_rows<DTYPE, HALF, NV, SB>(p, (int64_t)blockIdx.x * (HALF ? 16 : 8));
 }
 
-template <int DTYPE>
+template <int DTYPE, bool HALF, int NV, int SB>
 __global__ __launch_bounds__(256) void attn_combine_batched_kernel(const AttnBatchItem* items, const CombineWork* work) {
     const CombineWork w = work[blockIdx.x];
-    const AttnParams& p = items[w.item].attn;
-    if (p.part_half) attn_combine_block<DTYPE, true>(p, w.pair0);
-    else attn_combine_block<DTYPE, false>(p, w.pair0);
+    attn_combine_rows<DTYPE, HALF, NV, SB>(items[w.item].attn, w.pair0);
+}
+
+template <int DTYPE, bool HALF, int NV, int SB>
+static void launch_combine_form(const AttnParams* p, const AttnBatchItem* items, const CombineWork* work, unsigned blocks,
+                                hipStream_t stream) {
+    if (p) launch_kernel((attn_combine_kernel<DTYPE, HALF, NV, SB>), dim3(blocks), dim3(256), stream, *p);
+    else launch_kernel((attn_combine_batched_kernel<DTYPE, HALF, NV, SB>), dim3(blocks), dim3(256), stream, items, work);
+}
+template <int DTYPE>
+static void launch_combine_dtype(const AttnParams* p, const AttnBatchItem* items, const CombineWork* work, unsigned blocks,
+                                 bool half, bool wide, bool many, hipStream_t stream) {
+    if (half) {
+        if (many) {
+            if (wide) launch_combine_form<DTYPE, true, 2, 16>(p, items, work, blocks, stream);
+            else launch_combine_form<DTYPE, true, 1, 16>(p, items, work, blocks, stream);
+        } else {
+            if (wide) launch_combine_form<DTYPE, true, 2, 8>(p, items, work, blocks, stream);
+            else launch_combine_form<DTYPE, true, 1, 8>(p, items, work, blocks, stream);
+        }
+    } else {
+        if (wide) launch_combine_form<DTYPE, false, 2, 8>(p, items, work, blocks, stream);
+        else launch_combine_form<DTYPE, false, 1, 8>(p, items, work, blocks, stream);
+    }
 }
 
 hipError_t launch_attn_combine(const AttnParams& p, hipStream_t stream) {
     const int g = p.n_q_heads / p.n_kv_heads;
     const int64_t n_pairs = (int64_t)p.n_kv_heads * p.t_q * g;
     const int per_wg = p.part_half ? 16 : 8;
-    dim3 grid((unsigned)((n_pairs + per_wg - 1) / per_wg));
+    const unsigned blocks = (unsigned)((n_pairs + per_wg - 1) / per_wg);
+    const bool wide = p.head_dim > 128, many = p.n_split + 1 > 8;
     if (p.dtype == ADAPSHOT_BF16)
-        launch_kernel(attn_combine_kernel<ADAPSHOT_BF16>, grid, dim3(256), stream, p);
+        launch_combine_dtype<ADAPSHOT_BF16>(&p, nullptr, nullptr, blocks, p.part_half != 0, wide, many, stream);
     else
-        launch_kernel(attn_combine_kernel<ADAPSHOT_F32>, grid, dim3(256), stream, p);
+        launch_combine_dtype<ADAPSHOT_F32>(&p, nullptr, nullptr, blocks, p.part_half != 0, wide, many, stream);
     return hipGetLastError();
 }
 
+// All items of a batch have fp16 partial rows of 128 columns (the matrix-core kernel's); max_partials is the largest
+// number of partial rows that any item merges per output row.
 hipError_t launch_attn_combine_batched(const AttnBatchItem* items, const CombineWork* work, int n_work, int dtype,
-                                       hipStream_t stream) {
+                                       int max_partials, hipStream_t stream) {
     if (n_work <= 0) return hipSuccess;
     if (dtype == ADAPSHOT_BF16)
-        launch_kernel(attn_combine_batched_kernel<ADAPSHOT_BF16>, dim3((unsigned)n_work), dim3(256), stream, items, work);
+        launch_combine_dtype<ADAPSHOT_BF16>(nullptr, items, work, (unsigned)n_work, true, false, max_partials > 8, stream);
     else
-        launch_kernel(attn_combine_batched_kernel<ADAPSHOT_F32>, dim3((unsigned)n_work), dim3(256), stream, items, work);
+        launch_combine_dtype<ADAPSHOT_F32>(nullptr, items, work, (unsigned)n_work, true, false, max_partials > 8, stream);
     return hipGetLastError();
 }
 
